@@ -1,0 +1,210 @@
+/* chunkflow.h -- C ABI of the layerwise-offloaded DiT block path for one MI355X (gfx950).
+ *
+ * What the library does: runs one GPU's Ulysses share of a diffusion-transformer block
+ * forward (App. B block designs; Sec. 2.1 for the Ulysses split) while that block's bf16
+ * weights are streamed from pinned host memory in fixed-size chunks on a copy stream
+ * (Sec. 2.2 layerwise offloading loop; Sec. 3.2 chunked prefetch with pause/resume at chunk
+ * boundaries; Sec. 3.3 chunk-granular partial residency).
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative cf_status; cf_last_error() gives text.
+ *   - Pointers named `host_*` are host memory, everything inside cf_block_io is DEVICE memory.
+ *   - The caller owns all host blobs and all device tensors it passes in.  The library owns its
+ *     context, its events, the two staging slots, the per-block resident buffers and (when the
+ *     pause/resume worker is enabled) one host thread.  Nothing is freed behind the caller's back.
+ *   - Streams are hipStream_t handles passed as void*.  Calls only enqueue work unless stated;
+ *     no call blocks the host except cf_sync, cf_destroy, set_resident_fraction,
+ *     cf_checksum_block, cf_kernel_times and the bounded waits of the prefetch worker.
+ *   - bf16 tensors are uint16_t bit patterns.  The residual stream (x in, y out) is fp32.
+ *   - A context is not thread-safe; use it from one host thread.
+ */
+#ifndef CHUNKFLOW_H
+#define CHUNKFLOW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cf_ctx cf_ctx;
+
+typedef enum {
+    CF_OK = 0,
+    CF_ERR_ARG = -1,         /* bad argument (shape, alignment, range, null pointer)            */
+    CF_ERR_STATE = -2,       /* call order violated (wait before begin, slot still in use, ...) */
+    CF_ERR_HIP = -3,         /* a HIP runtime call failed; text has hipGetErrorString           */
+    CF_ERR_NOMEM = -4,       /* device or host allocation failed                                */
+    CF_ERR_UNSUPPORTED = -5  /* valid request this build does not implement                     */
+} cf_status;
+
+/* Block designs of App. B. */
+typedef enum {
+    CF_SINGLE_STREAM = 0,    /* MM-DiT single-stream: fused linear_1 (QKV + MLP-up), linear_2    */
+    CF_DIT_CROSS = 1,        /* DiT: self-attention, cross-attention to text, MLP                */
+    CF_DOUBLE_STREAM = 2     /* MM-DiT double-stream: per-stream weights, joint attention        */
+} cf_block_kind;
+
+/* Shape of one rank's share.  n_local = n_total / sp_degree tokens go through the linear
+ * layers; attention covers all n_total tokens for heads [sp_rank*H/P, (sp_rank+1)*H/P).
+ * Tokens split contiguously per stream; for CF_DOUBLE_STREAM the joint order is text then image
+ * and the local rows are this rank's n_txt_local text rows followed by its image rows. */
+typedef struct {
+    int32_t kind;            /* cf_block_kind */
+    int32_t n_blocks;
+    int32_t d;               /* hidden size, multiple of 256, <= 4096 */
+    int32_t n_heads;         /* H; d == n_heads * head_dim */
+    int32_t head_dim;        /* 64 or 128 */
+    int32_t f;               /* MLP width, multiple of 64 */
+    int32_t n_total;         /* N */
+    int32_t sp_degree;       /* P; divides n_heads, n_total (and n_txt_total) */
+    int32_t sp_rank;
+    int32_t n_txt_total;     /* CF_DOUBLE_STREAM: text tokens in the joint sequence, else 0 */
+    int32_t l_ctx;           /* CF_DIT_CROSS: context length, else 0 */
+    int32_t qk_rmsnorm;      /* per-head RMSNorm on q and k (learned weight, eps 1e-6) */
+    uint64_t chunk_bytes;    /* C of Sec. 3.2; multiple of 256 */
+} cf_model_desc;
+
+/* One tensor of the block's weight blob: bf16 [rows, cols] row-major at byte `offset`
+ * (256-byte aligned).  Linear weights are [out_features, in_features]. */
+typedef struct {
+    char name[32];
+    uint64_t offset;
+    uint32_t rows, cols;
+} cf_tensor_slot;
+
+/* Device buffers of one block invocation.  Peer buffers stand in for what the two Ulysses
+ * exchanges around attention deliver; send buffers receive what this rank would have sent.
+ * With sp_degree == 1 all peer/send pointers are ignored.  Send pointers may be NULL. */
+typedef struct {
+    const float* x;              /* [n_local, d] (double-stream: the image rows) residual stream in */
+    const float* x_txt;          /* double-stream: [n_txt_local, d] */
+    const float* temb;           /* [d] timestep embedding */
+    const uint16_t* ctx;         /* DiT: [l_ctx, d] bf16 text context */
+    const uint16_t* peer_q;      /* [H/P, N - n_local, hd] q of remote tokens, this rank's heads */
+    const uint16_t* peer_k;
+    const uint16_t* peer_v;
+    const uint16_t* peer_attn;   /* [n_local, H - H/P, hd] attention output of the other heads */
+    float* y;                    /* [n_local, d] (double-stream: image rows) residual stream out */
+    float* y_txt;                /* double-stream: [n_txt_local, d] */
+    uint16_t* send_q;            /* [H - H/P, n_local, hd] */
+    uint16_t* send_k;
+    uint16_t* send_v;
+    uint16_t* send_attn;         /* [H/P, N - n_local, hd] */
+    void* workspace;             /* >= cf_workspace_bytes, 256-byte aligned */
+    uint64_t workspace_bytes;
+} cf_block_io;
+
+typedef struct {
+    uint64_t h2d_bytes;          /* bytes copied by chunked_prefetch_begin since the last reset   */
+    uint64_t h2d_chunks;
+    uint64_t resident_bytes;     /* per block */
+    uint64_t blob_bytes;
+    uint64_t weight_memory_bytes;/* device bytes held for weights: resident buffers + 2 slots     */
+    uint64_t comm_bytes_h2d;     /* emulated collective traffic                                   */
+    uint64_t comm_bytes_d2h;
+    uint64_t pauses;             /* chunk launches that were made to wait for a collective        */
+} cf_stats_t;
+
+/* Per-kernel timing collected while profiling is on (cf_set_profiling). */
+typedef struct {
+    char name[32];
+    uint64_t launches;
+    double total_ms;             /* sum of hipEvent-measured durations */
+    double flops;                /* algorithmic FLOPs summed over those launches (0 if n/a) */
+    double bytes;                /* algorithmic HBM bytes summed over those launches (0 if n/a) */
+} cf_kernel_time;
+
+/* ---- context and layout (Sec. 3.2: a layer's parameters are partitioned into fixed-size chunks).
+ * cf_create validates the description and plans blob layout and chunking; it touches no GPU. */
+int cf_create(const cf_model_desc* desc, cf_ctx** out);
+int cf_destroy(cf_ctx* ctx);                                   /* syncs, frees everything it owns */
+const char* cf_last_error(const cf_ctx* ctx);                  /* ctx may be NULL: last create error */
+int cf_blob_bytes(const cf_ctx* ctx, uint64_t* out);
+int cf_n_chunks(const cf_ctx* ctx, int32_t* out);
+/* tensors in blob order; *n is capacity on entry, count on return (call with out=NULL to query) */
+int cf_blob_layout(const cf_ctx* ctx, cf_tensor_slot* out, int32_t* n);
+int cf_workspace_bytes(const cf_ctx* ctx, uint64_t* out);
+
+/* ---- weights (Sec. 2.2: all layers are placed in pinned host memory at initialisation).
+ * host_blob must be pinned (hipHostMalloc), hold exactly cf_blob_bytes and outlive the context. */
+int cf_register_block(cf_ctx* ctx, int32_t block, const void* host_blob, uint64_t bytes);
+
+/* ---- Sec. 3.3 partial parameter residency: keep floor(r*n_chunks + 0.5) leading chunks of every
+ * block permanently in HBM and prefetch only the rest.  r=0 is full offload, r=1 no offload.
+ * Synchronises the device, re-plans, uploads the resident chunks; *actual (optional) receives
+ * resident_bytes / blob_bytes.  r outside [0,1] is CF_ERR_ARG. */
+int set_resident_fraction(cf_ctx* ctx, double r, double* actual);
+
+/* ---- Sec. 2.2 step 3 + Sec. 3.2: start the asynchronous chunk-by-chunk prefetch of `block`
+ * into staging slot block%2 on copy_stream.  The copy first waits (on the GPU) for the slot's
+ * previous tenant to finish computing.  CF_ERR_STATE if that tenant was prefetched but its
+ * dit_block_fwd has not been issued yet. */
+int chunked_prefetch_begin(cf_ctx* ctx, int32_t block, void* copy_stream);
+
+/* ---- Sec. 2.2 step 1, at chunk granularity: make compute_stream wait (on the GPU) until chunk
+ * `chunk` of `block` (and all earlier ones) has landed; chunk = -1 means the whole block.
+ * Resident chunks need no wait.  CF_ERR_STATE if the block's prefetch was never begun. */
+int chunked_prefetch_wait(cf_ctx* ctx, int32_t block, int32_t chunk, void* compute_stream);
+
+/* ---- Sec. 2.2 step 2: enqueue the forward pass of `block` on compute_stream.  Each kernel that
+ * reads weights is preceded by the wait for the last chunk it needs, and the GEMMs are launched
+ * as panels of output features per chunk, so compute starts before the whole layer has landed.
+ * Marks the staging slot reusable when the block's last kernel finishes (step 4). */
+int dit_block_fwd(cf_ctx* ctx, int32_t block, const cf_block_io* io, void* compute_stream);
+
+/* ---- Sec. 3.2 pause/resume.  cf_set_contention enables, per block forward, four emulated
+ * collectives (q,k,v before attention, o after), each moving `bytes_per_collective` split half
+ * host->device / half device->host on comm_stream through host_pinned / a device buffer the
+ * library owns; the compute stream waits for each.  With pause_resume != 0 a prefetch worker
+ * thread enqueues chunks with at most 2 in flight and, when a collective is in progress, makes
+ * the copy stream wait for its completion event before the next chunk.  comm_stream NULL disables. */
+int cf_set_contention(cf_ctx* ctx, void* comm_stream, void* host_pinned, uint64_t host_bytes,
+                      uint64_t bytes_per_collective, int32_t pause_resume);
+/* The same two hooks for a caller that issues its own collective on comm_stream between them. */
+int cf_comm_begin(cf_ctx* ctx, void* comm_stream, void* compute_stream);
+int cf_comm_end(cf_ctx* ctx, void* comm_stream, void* compute_stream);
+
+/* ---- integrity: 64-bit checksum of every chunk of `block` as it currently sits in HBM (resident
+ * buffer or staging slot); host_out[n_chunks].  Waits for the block's prefetch, then blocks the
+ * host until done.  Word i of the blob (little-endian 64-bit, i from the blob start) contributes
+ * splitmix64_finalise(word XOR (i+1)*0x9E3779B97F4A7C15), summed modulo 2^64. */
+int cf_checksum_block(cf_ctx* ctx, int32_t block, uint64_t* host_out, void* stream);
+/* copy the device image of `block` back to host_out[blob_bytes] (for byte-exact comparison) */
+int cf_read_block(cf_ctx* ctx, int32_t block, void* host_out, void* stream);
+
+int cf_stats(cf_ctx* ctx, cf_stats_t* out);
+int cf_stats_reset(cf_ctx* ctx);
+int cf_set_profiling(cf_ctx* ctx, int32_t on);                 /* hipEvent pair around every kernel */
+int cf_kernel_times(cf_ctx* ctx, cf_kernel_time* out, int32_t* n);   /* syncs; *n capacity/count */
+int cf_kernel_times_reset(cf_ctx* ctx);
+int cf_sync(cf_ctx* ctx);                                      /* hipDeviceSynchronize */
+
+/* ---- single kernels, exposed so that each can be checked against the oracle in isolation.
+ * All pointers are device memory; `blob` holds W (and bias) at the given byte offsets. */
+/* out[m,n] = A[m,:] . W[n,:] + bias[n]; features < n_split stored bf16 to out0[m*ld0+n], the rest
+ * through GELU-tanh to out1[m*ld1 + n - n_split] (App. B linear layers). */
+int cf_op_linear(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off,
+                 int32_t M, int32_t N, int32_t K, int32_t n0, int32_t n1, int32_t n_split,
+                 uint16_t* out0, int32_t ld0, uint16_t* out1, int32_t ld1, void* stream);
+/* y = resid + gate * (A . W^T + bias), fp32 (gate NULL = 1). */
+int cf_op_linear_residual(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off,
+                          int32_t M, int32_t N, int32_t K, const float* resid, const float* gate,
+                          float* y, void* stream);
+/* O[h,q,:] = softmax(Q K^T / sqrt(hd)) V; Q [H,nq,hd], K [H,nk,hd], Vt [H,hd,nk_pad] (pad zero),
+ * O [H,nq,hd] (App. B attention term, no mask). */
+int cf_op_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O,
+                    int32_t H, int32_t nq, int32_t nk, int32_t nk_pad, int32_t hd, void* stream);
+/* xn = LayerNorm(x) * (1 + scale) + shift, bf16 out. */
+int cf_op_ln_modulate(const float* x, const float* shift, const float* scale, uint16_t* xn,
+                      int32_t rows, int32_t d, void* stream);
+/* m = W t + b over a blob holding W [n,K] and b [n]. */
+int cf_op_modvec(const void* blob, uint64_t w_off, uint64_t b_off, const float* t, float* m,
+                 int32_t n, int32_t K, void* stream);
+/* checksum of a device byte range (definition above); host_out[1]; blocks the host. */
+int cf_op_checksum(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* host_out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHUNKFLOW_H */

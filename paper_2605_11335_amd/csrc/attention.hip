@@ -1,0 +1,233 @@
+// Full (non-causal, unmasked) softmax attention for the heads this rank owns, over the whole
+// joint sequence (App. B: the 4*B*S^2*d term; Sec. 2.1: under Ulysses each rank attends over all
+// N tokens for H/P heads).  Flash-style: the nq x nk score matrix is never materialised; keys
+// and values stream through LDS in tiles of 64 keys with an online softmax.
+//
+// The kernel works on the transposed problem so that no data ever changes lanes between the
+// two contractions:
+//   S^T[key, query] = K . Q^T      (MFMA A = key rows from LDS,   B = query fragment in registers)
+//   O^T[d,   query] = V^T . P^T    (MFMA A = V^T rows from LDS,   B = P^T built from S^T registers)
+// With 32x32x16 MFMAs a lane owns ONE query column, so the running max / sum are per-lane
+// scalars and the rescale of O^T is a lane-uniform multiply.  The 32 key rows of each S^T tile
+// are fed in an order that swaps bits 2 and 3 of the row index; the accumulator registers
+// v=8a..8a+7 of lane group g then hold keys 16a+8g .. 16a+8g+7 in order, which is exactly the
+// B-operand layout of the second contraction (8 consecutive k per lane), so P^T is a pure
+// register repack.  V is kept transposed in HBM ([head, d, key]) so that its A-operand rows
+// are contiguous 16-byte reads as well.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+constexpr int BQ = 128;    // queries per workgroup (4 waves x 32)
+constexpr int BKV = 64;    // keys per tile
+
+template <int HD>
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
+    constexpr int KCH = HD / 8;                 // 16-byte chunks per K row
+    constexpr int KROW = HD * 2;                // bytes per K row in LDS
+    constexpr int K_LOADS = BKV * KCH / 256;
+    constexpr int V_LOADS = HD * 8 / 256;
+    constexpr int K_TILE = BKV * KROW, V_TILE = HD * 128;
+    constexpr int DT = HD / 32;                 // 32-row tiles of O^T
+    constexpr int KS = HD / 16;                 // k-steps of the first contraction
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    char* const sK = smem;                      // [2][BKV][KROW]
+    char* const sV = smem + 2 * K_TILE;         // [2][HD][128]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lj = lane & 31, lg = lane >> 5;
+
+    const int nqt = (a.nq + BQ - 1) / BQ;
+    const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int h = lid / nqt, qt = lid % nqt;
+    const int q0 = qt * BQ + wave * 32;
+
+    // K swizzle: 256-byte rows (HD=128) rotate over 16 chunk slots, 128-byte rows over 8
+    auto kswz = [](int key) { return HD == 128 ? (key & 15) : (((key >> 1) & 7) ^ ((key & 1) << 2)); };
+    auto vswz = [](int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); };
+
+    // ---- query fragments (B operand), resident in registers for the whole sweep
+    bf16x8 qf[KS];
+    {
+        const int qr = min(q0 + lj, a.nq - 1);
+        const bf16* qp = a.Q + ((size_t)h * a.nq + qr) * HD + lg * 8;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) qf[kk] = *(const bf16x8*)(qp + kk * 16);
+    }
+
+    // ---- per-thread sources for the tile copies
+    const bf16* k_src[K_LOADS];
+    int k_row[K_LOADS], k_dst[K_LOADS];
+#pragma unroll
+    for (int j = 0; j < K_LOADS; ++j) {
+        const int q = tid + j * 256, key = q / KCH, c = q % KCH;
+        k_row[j] = key;
+        k_src[j] = a.K + (size_t)h * a.nk * HD + c * 8;
+        k_dst[j] = key * KROW + ((c ^ kswz(key)) << 4);
+    }
+    const bf16* v_src[V_LOADS];
+    int v_dst[V_LOADS];
+#pragma unroll
+    for (int j = 0; j < V_LOADS; ++j) {
+        const int q = tid + j * 256, row = q >> 3, c = q & 7;
+        v_src[j] = a.Vt + ((size_t)h * HD + row) * a.nk_pad + c * 8;
+        v_dst[j] = row * 128 + ((c ^ vswz(row)) << 4);
+    }
+
+    uint4 rk[K_LOADS], rv[V_LOADS];
+    auto load_tile = [&](int t) {
+        const int k0 = t * BKV;
+#pragma unroll
+        for (int j = 0; j < K_LOADS; ++j)
+            rk[j] = *(const uint4*)(k_src[j] + (size_t)min(k0 + k_row[j], a.nk - 1) * HD);
+#pragma unroll
+        for (int j = 0; j < V_LOADS; ++j) rv[j] = *(const uint4*)(v_src[j] + k0);
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int j = 0; j < K_LOADS; ++j) *(uint4*)(sK + buf * K_TILE + k_dst[j]) = rk[j];
+#pragma unroll
+        for (int j = 0; j < V_LOADS; ++j) *(uint4*)(sV + buf * V_TILE + v_dst[j]) = rv[j];
+    };
+
+    floatx16 o[DT];
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[d][v] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c2 = a.scale * 1.4426950408889634f;   // logits in base-2 units
+
+    // key row fed to MFMA row i: swap bits 2 and 3 of i
+    const int krow = (lj & 0x13) | ((lj & 4) << 1) | ((lj & 8) >> 1);
+
+    const int NT = (a.nk + BKV - 1) / BKV;
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+
+    for (int t = 0; t < NT; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < NT) load_tile(t + 1);
+        const char* cK = sK + buf * K_TILE;
+        const char* cV = sV + buf * V_TILE;
+
+        // ---- S^T = K . Q^T for 2 x 32 keys
+        floatx16 s[2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[mt][v] = 0.f;
+            const int key = mt * 32 + krow;
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk) {
+                const int c = kk * 2 + lg;
+                const bf16x8 kf = *(const bf16x8*)(cK + key * KROW + ((c ^ kswz(key)) << 4));
+                s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[mt], 0, 0, 0);
+            }
+        }
+
+        // ---- online softmax; register v of tile mt is key k0 + mt*32 + 16*(v/8) + 8*lg + v%8
+        const int k0 = t * BKV;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float x = s[mt][v] * c2;
+                if (k0 + BKV > a.nk) {
+                    const int key = k0 + mt * 32 + 16 * (v >> 3) + 8 * lg + (v & 7);
+                    if (key >= a.nk) x = -INFINITY;
+                }
+                s[mt][v] = x;
+                mx = fmaxf(mx, x);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float p = __builtin_amdgcn_exp2f(s[mt][v] - m_new);
+                s[mt][v] = p;
+                psum += p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[d][v] *= alpha;
+
+        // ---- O^T += V^T . P^T, 4 k-steps of 16 keys
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 pf;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[e] = (bf16)s[ks >> 1][8 * (ks & 1) + e];
+            const int c = ks * 2 + lg;
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+                const int row = d * 32 + lj;
+                const bf16x8 vf = *(const bf16x8*)(cV + row * 128 + ((c ^ vswz(row)) << 4));
+                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+            }
+        }
+
+        if (t + 1 < NT) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- normalise and store: lane = query, register quad = 4 consecutive d
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = 1.0f / l_tot;
+    const int q = q0 + lj;
+    if (q < a.nq) {
+        bf16* op = a.O + (size_t)h * a.o_hs + (size_t)q * a.o_qs;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int vb = 0; vb < 4; ++vb) {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[d][vb * 4 + e] * inv);
+                *(bf16x4*)(op + d * 32 + vb * 8 + lg * 4) = w;
+            }
+    }
+}
+
+template <int HD>
+hipError_t launch(const AttnArgs& a, hipStream_t s) {
+    const size_t smem = 2 * (BKV * HD * 2 + HD * 128);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_kernel<HD>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int nqt = (a.nq + BQ - 1) / BQ;
+    hipLaunchKernelGGL((attn_fwd_kernel<HD>), dim3(nqt * a.H), dim3(256), smem, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+const char* attn_check(const AttnArgs& a) {
+    if (a.hd != 64 && a.hd != 128) return "attention: head_dim must be 64 or 128";
+    if (a.H <= 0 || a.nq <= 0 || a.nk <= 0) return "attention: empty shape";
+    if (a.nk_pad % 64 || a.nk_pad < a.nk) return "attention: nk_pad must be a multiple of 64 covering nk";
+    if (!a.Q || !a.K || !a.Vt || !a.O) return "attention: null operand";
+    if (((uintptr_t)a.Q | (uintptr_t)a.K | (uintptr_t)a.Vt) % 16) return "attention: operands must be 16-byte aligned";
+    if (((uintptr_t)a.O % 8) || (a.o_hs % 4) || (a.o_qs % 4)) return "attention: output must be 8-byte aligned";
+    if ((long)((a.nq + BQ - 1) / BQ) * a.H > 0x7fffffffL) return "attention: grid too large";
+    return nullptr;
+}
+
+hipError_t attn_launch(const AttnArgs& a, hipStream_t s) {
+    return a.hd == 128 ? launch<128>(a, s) : launch<64>(a, s);
+}

@@ -1,0 +1,1035 @@
+// C ABI implementation: layout/chunk planning, residency, chunked prefetch with per-chunk
+// events, the pause/resume worker, emulated collectives, and the block forward that strings the
+// kernels together.  See include/chunkflow.h for the contract of every entry point.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "context.h"
+
+namespace {
+
+std::string g_create_err;
+
+int fail(const cf_ctx* c, int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf; else g_create_err = buf;
+    return code;
+}
+
+#define CF_HIP(c, call)                                                                                  \
+    do {                                                                                                 \
+        hipError_t e_ = (call);                                                                          \
+        if (e_ != hipSuccess) return fail((c), CF_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+#define CF_TRY(expr)                  \
+    do {                              \
+        int rc_ = (expr);             \
+        if (rc_ != CF_OK) return rc_; \
+    } while (0)
+
+inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+// ------------------------------------------------------------------------------------------
+// blob layout: tensors in the order the block consumes them (small vectors ahead of the matrix
+// that needs them), each 256-byte aligned, so a prefix of chunks is a prefix of the computation
+// ------------------------------------------------------------------------------------------
+void add_tensor(cf_ctx* c, const std::string& name, uint32_t rows, uint32_t cols) {
+    TensorDesc t{name, align_up(c->blob_bytes, 256), rows, cols};
+    c->blob_bytes = t.off + t.bytes();
+    c->tensors.push_back(t);
+}
+
+void plan_layout(cf_ctx* c) {
+    const cf_model_desc& m = c->d;
+    const uint32_t d = m.d, f = m.f, hd = m.head_dim;
+    c->tensors.clear();
+    c->blob_bytes = 0;
+    if (m.kind == CF_SINGLE_STREAM) {
+        add_tensor(c, "b_mod", 1, 3 * d);
+        add_tensor(c, "w_mod", 3 * d, d);
+        add_tensor(c, "b1", 1, 3 * d + f);
+        if (m.qk_rmsnorm) { add_tensor(c, "q_norm", 1, hd); add_tensor(c, "k_norm", 1, hd); }
+        add_tensor(c, "w1", 3 * d + f, d);
+        add_tensor(c, "b2", 1, d);
+        add_tensor(c, "w2", d, d + f);
+    } else if (m.kind == CF_DIT_CROSS) {
+        add_tensor(c, "b_mod", 1, 6 * d);
+        add_tensor(c, "w_mod", 6 * d, d);
+        add_tensor(c, "b_qkv", 1, 3 * d);
+        if (m.qk_rmsnorm) { add_tensor(c, "q_norm", 1, hd); add_tensor(c, "k_norm", 1, hd); }
+        add_tensor(c, "w_qkv", 3 * d, d);
+        add_tensor(c, "b_o", 1, d);
+        add_tensor(c, "w_o", d, d);
+        add_tensor(c, "ln_c_w", 1, d);
+        add_tensor(c, "ln_c_b", 1, d);
+        add_tensor(c, "b_cq", 1, d);
+        if (m.qk_rmsnorm) { add_tensor(c, "cq_norm", 1, hd); add_tensor(c, "ck_norm", 1, hd); }
+        add_tensor(c, "w_cq", d, d);
+        add_tensor(c, "b_ckv", 1, 2 * d);
+        add_tensor(c, "w_ckv", 2 * d, d);
+        add_tensor(c, "b_co", 1, d);
+        add_tensor(c, "w_co", d, d);
+        add_tensor(c, "b_up", 1, f);
+        add_tensor(c, "w_up", f, d);
+        add_tensor(c, "b_down", 1, d);
+        add_tensor(c, "w_down", d, f);
+    } else {
+        static const char* st[2] = {"txt", "img"};
+        auto nm = [](const char* s, const char* t) { return std::string(s) + "_" + t; };
+        for (int s = 0; s < 2; ++s) { add_tensor(c, nm(st[s], "b_mod"), 1, 6 * d); add_tensor(c, nm(st[s], "w_mod"), 6 * d, d); }
+        for (int s = 0; s < 2; ++s) {
+            add_tensor(c, nm(st[s], "b_qkv"), 1, 3 * d);
+            if (m.qk_rmsnorm) { add_tensor(c, nm(st[s], "q_norm"), 1, hd); add_tensor(c, nm(st[s], "k_norm"), 1, hd); }
+            add_tensor(c, nm(st[s], "w_qkv"), 3 * d, d);
+        }
+        for (int s = 0; s < 2; ++s) { add_tensor(c, nm(st[s], "b_o"), 1, d); add_tensor(c, nm(st[s], "w_o"), d, d); }
+        for (int s = 0; s < 2; ++s) {
+            add_tensor(c, nm(st[s], "b_up"), 1, f);
+            add_tensor(c, nm(st[s], "w_up"), f, d);
+            add_tensor(c, nm(st[s], "b_down"), 1, d);
+            add_tensor(c, nm(st[s], "w_down"), d, f);
+        }
+    }
+    c->blob_bytes = align_up(c->blob_bytes, 256);
+    c->n_chunks = (int)((c->blob_bytes + c->chunk_bytes - 1) / c->chunk_bytes);
+}
+
+// ------------------------------------------------------------------------------------------
+// workspace carving (same function plans the size and hands out the pointers)
+// ------------------------------------------------------------------------------------------
+struct Ws {
+    float* mod = nullptr;      // modulation vectors (3d | 6d | 2 x 6d)
+    bf16* xn = nullptr;        // [n_local, d]
+    bf16* qkv = nullptr;       // [n_local, 3d]
+    bf16* c = nullptr;         // single: [n_local, d+f]; others: attention rows [n_local, d]
+    bf16 *Q = nullptr, *K = nullptr, *Vt = nullptr, *O = nullptr;
+    float *x1 = nullptr, *x2 = nullptr;
+    bf16* up = nullptr;        // [n_local, f]
+    bf16 *ckv = nullptr, *cQ = nullptr, *cK = nullptr, *cVt = nullptr;
+    uint64_t total = 0;
+};
+
+inline int n_pad_of(int n) { return (n + 63) / 64 * 64; }
+
+Ws carve(const cf_ctx* c, char* base) {
+    const cf_model_desc& m = c->d;
+    Ws w;
+    uint64_t off = 0;
+    auto take = [&](uint64_t bytes) { char* p = base + off; off = align_up(off + bytes, 256); return p; };
+    const uint64_t nl = m.n_total / m.sp_degree, d = m.d, f = m.f, N = m.n_total, hd = m.head_dim;
+    const uint64_t hl = m.n_heads / m.sp_degree;
+    const int nmod = m.kind == CF_SINGLE_STREAM ? 3 : (m.kind == CF_DIT_CROSS ? 6 : 12);
+    w.mod = (float*)take(4ull * nmod * d);
+    w.xn = (bf16*)take(2 * nl * d);
+    w.qkv = (bf16*)take(2 * nl * 3 * d);
+    w.c = (bf16*)take(2 * nl * (m.kind == CF_SINGLE_STREAM ? d + f : d));
+    w.Q = (bf16*)take(2 * hl * N * hd);
+    w.K = (bf16*)take(2 * hl * N * hd);
+    w.Vt = (bf16*)take(2 * hl * hd * n_pad_of(N));
+    if (m.sp_degree > 1) w.O = (bf16*)take(2 * hl * N * hd);
+    if (m.kind != CF_SINGLE_STREAM) {
+        w.x1 = (float*)take(4 * nl * d);
+        w.up = (bf16*)take(2 * nl * f);
+    }
+    if (m.kind == CF_DIT_CROSS) {
+        w.x2 = (float*)take(4 * nl * d);
+        w.ckv = (bf16*)take(2ull * m.l_ctx * 2 * d);
+        w.cQ = (bf16*)take(2 * nl * d);
+        w.cK = (bf16*)take(2ull * m.l_ctx * d);
+        w.cVt = (bf16*)take(2ull * d * n_pad_of(m.l_ctx));
+    }
+    w.total = off;
+    return w;
+}
+
+// ------------------------------------------------------------------------------------------
+// device resources
+// ------------------------------------------------------------------------------------------
+int ensure_device(cf_ctx* c) {
+    if (c->device_ready) return CF_OK;
+    CF_HIP(c, hipGetDevice(&c->device));
+    for (int s = 0; s < 2; ++s) {
+        c->chunk_ev[s].resize(c->n_chunks);
+        for (auto& e : c->chunk_ev[s]) CF_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        CF_HIP(c, hipEventCreateWithFlags(&c->done_ev[s], hipEventDisableTiming));
+    }
+    CF_HIP(c, hipEventCreateWithFlags(&c->comm_ready_ev, hipEventDisableTiming));
+    CF_HIP(c, hipEventCreateWithFlags(&c->comm_done_ev, hipEventDisableTiming));
+    c->device_ready = true;
+    return CF_OK;
+}
+
+void free_weights(cf_ctx* c) {
+    for (auto& p : c->res_buf) { if (p) (void)hipFree(p); p = nullptr; }
+    for (int s = 0; s < 2; ++s) {
+        if (c->slot[s]) (void)hipFree(c->slot[s]);
+        c->slot[s] = nullptr;
+        c->slot_tenant[s] = -1;
+        c->slot_state[s] = SLOT_EMPTY;
+        c->done_valid[s] = false;
+        c->enq_count[s] = 0;
+    }
+    c->next_slot = 0;
+    std::fill(c->block_slot.begin(), c->block_slot.end(), -1);
+}
+
+int upload_resident(cf_ctx* c, int block) {
+    if (!c->res_bytes || !c->host[block]) return CF_OK;
+    if (!c->res_buf[block]) {
+        if (hipMalloc((void**)&c->res_buf[block], c->res_bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(c, CF_ERR_NOMEM, "hipMalloc of %llu resident bytes for block %d failed",
+                        (unsigned long long)c->res_bytes, block);
+        }
+    }
+    CF_HIP(c, hipMemcpy(c->res_buf[block], c->host[block], c->res_bytes, hipMemcpyHostToDevice));
+    return CF_OK;
+}
+
+inline uint64_t chunk_begin(const cf_ctx* c, int k) { return (uint64_t)k * c->chunk_bytes; }
+inline uint64_t chunk_end(const cf_ctx* c, int k) { return std::min(c->blob_bytes, (uint64_t)(k + 1) * c->chunk_bytes); }
+
+WView view_of(const cf_ctx* c, int block) {
+    WView v;
+    v.lo = (const char*)c->res_buf[block];
+    const int sl = c->block_slot[block];
+    v.hi = (sl >= 0 && c->slot[sl]) ? (const char*)c->slot[sl] - c->res_bytes : nullptr;
+    v.split = c->res_bytes;
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// prefetch worker (Sec. 3.2): enqueues chunk copies with at most 2 in flight and, when a
+// collective has been issued, parks the copy stream on that collective's completion event
+// ------------------------------------------------------------------------------------------
+int enqueue_block_copies(cf_ctx* c, int block, int s, hipStream_t copy, bool bounded) {
+    if (c->done_valid[s]) CF_HIP(c, hipStreamWaitEvent(copy, c->done_ev[s], 0));   // slot's last reader
+    for (int k = c->n_res_chunks; k < c->n_chunks; ++k) {
+        if (bounded) {
+            if (k - 2 >= c->n_res_chunks) CF_HIP(c, hipEventSynchronize(c->chunk_ev[s][k - 2]));
+            std::lock_guard<std::mutex> lk(c->mu);
+            if (c->pause_flag) {
+                CF_HIP(c, hipStreamWaitEvent(copy, c->comm_done_ev, 0));
+                c->pause_flag = false;
+                c->stats.pauses++;
+            }
+        }
+        const uint64_t b = chunk_begin(c, k), e = chunk_end(c, k);
+        CF_HIP(c, hipMemcpyAsync(c->slot[s] + (b - c->res_bytes), c->host[block] + b, e - b, hipMemcpyHostToDevice, copy));
+        CF_HIP(c, hipEventRecord(c->chunk_ev[s][k], copy));
+        {
+            std::lock_guard<std::mutex> lk(c->mu);
+            c->enq_count[s] = k + 1;
+            c->stats.h2d_bytes += e - b;
+            c->stats.h2d_chunks++;
+        }
+        c->cv.notify_all();
+    }
+    return CF_OK;
+}
+
+void worker_main(cf_ctx* c) {
+    (void)hipSetDevice(c->device);
+    for (;;) {
+        PrefetchJob job;
+        {
+            std::unique_lock<std::mutex> lk(c->mu);
+            c->cv.wait(lk, [&] { return c->worker_stop || !c->jobs.empty(); });
+            if (c->jobs.empty()) return;
+            job = c->jobs.front();
+            c->jobs.pop_front();
+            c->worker_busy = true;
+        }
+        std::string saved = c->err;
+        int rc = enqueue_block_copies(c, job.block, job.slot, job.copy, true);
+        {
+            std::lock_guard<std::mutex> lk(c->mu);
+            if (rc != CF_OK) {
+                c->worker_err = c->err;
+                c->enq_count[job.slot] = c->n_chunks;   // never leave the consumer waiting
+            }
+            c->err = saved;
+            c->worker_busy = false;
+        }
+        c->cv.notify_all();
+    }
+}
+
+void worker_drain(cf_ctx* c) {
+    if (!c->worker.joinable()) return;
+    std::unique_lock<std::mutex> lk(c->mu);
+    c->cv.wait(lk, [&] { return c->jobs.empty() && !c->worker_busy; });
+}
+
+void worker_stop(cf_ctx* c) {
+    if (!c->worker.joinable()) return;
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        c->worker_stop = true;
+    }
+    c->cv.notify_all();
+    c->worker.join();
+    c->worker_stop = false;
+}
+
+// device-side wait for chunk k of `block` on stream s
+int wait_chunk(cf_ctx* c, int block, int k, hipStream_t s) {
+    if (k < c->n_res_chunks) return CF_OK;
+    const int sl = c->block_slot[block];
+    if (sl < 0 || c->slot_tenant[sl] != block || c->slot_state[sl] == SLOT_EMPTY)
+        return fail(c, CF_ERR_STATE, "block %d: chunk %d awaited but its prefetch was not begun", block, k);
+    if (c->worker.joinable()) {
+        std::unique_lock<std::mutex> lk(c->mu);
+        c->cv.wait(lk, [&] { return c->enq_count[sl] > k; });
+        if (!c->worker_err.empty()) return fail(c, CF_ERR_HIP, "prefetch worker: %s", c->worker_err.c_str());
+    }
+    CF_HIP(c, hipStreamWaitEvent(s, c->chunk_ev[sl][k], 0));
+    return CF_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// profiling: hipEvent pair around each kernel launch, resolved lazily
+// ------------------------------------------------------------------------------------------
+enum Kid {
+    K_MODVEC, K_LN, K_LIN1, K_QKV, K_RELAYOUT, K_PEER, K_ATTN, K_GATHER, K_LIN2, K_OUT, K_UP, K_DOWN,
+    K_CROSS_Q, K_CROSS_KV, K_CROSS_ATTN, K_CROSS_OUT, K_COUNT
+};
+const char* kKidName[K_COUNT] = {"modvec", "ln_modulate", "gemm_lin1", "gemm_qkv", "qk_relayout", "peer_scatter",
+                                 "attention", "attn_gather", "gemm_lin2", "gemm_out", "gemm_up", "gemm_down",
+                                 "gemm_cross_q", "gemm_cross_kv", "cross_attention", "gemm_cross_out"};
+
+hipEvent_t prof_event(cf_ctx* c) {
+    if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
+struct ProfScope {
+    cf_ctx* c; hipStream_t s; ProfEntry pe; bool on;
+    ProfScope(cf_ctx* c_, hipStream_t s_, int kid, double flops, double bytes) : c(c_), s(s_), on(c_->profiling) {
+        if (!on) return;
+        pe = ProfEntry{kid, prof_event(c), prof_event(c), flops, bytes};
+        (void)hipEventRecord(pe.a, s);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(pe.b, s);
+        c->prof_pending.push_back(pe);
+    }
+};
+
+int prof_resolve(cf_ctx* c) {
+    if (c->prof_pending.empty()) return CF_OK;
+    CF_HIP(c, hipDeviceSynchronize());
+    if (c->ktimes.empty()) {
+        c->ktimes.resize(K_COUNT);
+        for (int i = 0; i < K_COUNT; ++i) {
+            memset(&c->ktimes[i], 0, sizeof(cf_kernel_time));
+            snprintf(c->ktimes[i].name, sizeof c->ktimes[i].name, "%s", kKidName[i]);
+        }
+    }
+    for (auto& pe : c->prof_pending) {
+        float ms = 0.f;
+        CF_HIP(c, hipEventElapsedTime(&ms, pe.a, pe.b));
+        cf_kernel_time& k = c->ktimes[pe.kid];
+        k.launches++;
+        k.total_ms += ms;
+        k.flops += pe.flops;
+        k.bytes += pe.bytes;
+        c->ev_pool.push_back(pe.a);
+        c->ev_pool.push_back(pe.b);
+    }
+    c->prof_pending.clear();
+    return CF_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// forward building blocks
+// ------------------------------------------------------------------------------------------
+struct Fwd {
+    cf_ctx* c;
+    int block;
+    hipStream_t s;
+    WView W;
+    const cf_block_io* io;
+    Ws ws;
+};
+
+const TensorDesc& T(const cf_ctx* c, const std::string& name) {
+    for (auto& t : c->tensors)
+        if (t.name == name) return t;
+    static TensorDesc none{"", 0, 0, 0};
+    return none;
+}
+
+// wait for every chunk a (small) tensor touches
+int need(Fwd& F, const TensorDesc& t) {
+    // the copy stream is in order: the last chunk's event covers the earlier ones
+    const int last = (int)((t.off + t.bytes() - 1) / F.c->chunk_bytes);
+    if (last >= F.c->n_res_chunks && last > F.c->waited_upto) {
+        CF_TRY(wait_chunk(F.c, F.block, last, F.s));
+        F.c->waited_upto = last;
+    }
+    return CF_OK;
+}
+
+// Launch `fn(row0, row1)` over the rows of weight matrix t as they become available: before
+// blocking on a chunk that is still streaming, everything whose bytes lie in earlier chunks is
+// launched (rounded down to `granule` rows so that launches stay tile-aligned).
+template <class Fn>
+int panels(Fwd& F, const TensorDesc& t, int granule, Fn&& fn) {
+    cf_ctx* c = F.c;
+    const uint64_t row_bytes = 2ull * t.cols;
+    const int first = (int)(t.off / c->chunk_bytes), last = (int)((t.off + t.bytes() - 1) / c->chunk_bytes);
+    int row0 = 0;
+    for (int k = first; k <= last; ++k) {
+        if (k < c->n_res_chunks || k <= c->waited_upto) continue;
+        const uint64_t lim = chunk_begin(c, k);
+        int avail = lim <= t.off ? 0 : (int)std::min<uint64_t>(t.rows, (lim - t.off) / row_bytes);
+        avail = avail / granule * granule;
+        if (avail > row0) {
+            CF_TRY(fn(row0, avail));
+            row0 = avail;
+        }
+        CF_TRY(wait_chunk(c, F.block, k, F.s));
+        c->waited_upto = k;
+    }
+    if ((int)t.rows > row0) CF_TRY(fn(row0, (int)t.rows));
+    return CF_OK;
+}
+
+int run_modvec(Fwd& F, const std::string& wname, const std::string& bname, const float* t, float* out) {
+    const TensorDesc &w = T(F.c, wname), &b = T(F.c, bname);
+    CF_TRY(need(F, b));
+    return panels(F, w, 8, [&](int r0, int r1) -> int {
+        ProfScope ps(F.c, F.s, K_MODVEC, 2.0 * (r1 - r0) * w.cols, 2.0 * (r1 - r0) * w.cols);
+        CF_HIP(F.c, modvec_launch(F.W, w.off, b.off, t, out, r0, r1, (int)w.cols, F.s));
+        return CF_OK;
+    });
+}
+
+int run_ln_mod(Fwd& F, const float* x, const float* shift, const float* scale, bf16* out, int rows) {
+    if (rows <= 0) return CF_OK;
+    ProfScope ps(F.c, F.s, K_LN, 0, 6.0 * rows * F.c->d.d);
+    CF_HIP(F.c, ln_modulate_launch(x, shift, scale, out, rows, F.c->d.d, F.c->d.d, F.s));
+    return CF_OK;
+}
+
+// out-feature panels of one linear layer; `g` carries everything but the panel and the weights
+int run_linear(Fwd& F, int kid, const std::string& wname, const std::string& bname, GemmArgs g) {
+    if (g.M <= 0) return CF_OK;
+    const TensorDesc &w = T(F.c, wname), &b = T(F.c, bname);
+    CF_TRY(need(F, b));
+    g.W = F.W;
+    g.w_off = w.off;
+    g.bias_off = b.off;
+    g.has_bias = 1;
+    g.N = (int)w.rows;
+    g.K = (int)w.cols;
+    return panels(F, w, 256, [&](int r0, int r1) -> int {
+        GemmArgs p = g;
+        p.n0 = r0;
+        p.n1 = r1;
+        if (const char* msg = gemm_check(p)) return fail(F.c, CF_ERR_ARG, "%s (%s)", msg, wname.c_str());
+        ProfScope ps(F.c, F.s, kid, 2.0 * p.M * (r1 - r0) * p.K, 0);
+        CF_HIP(F.c, gemm_launch(p, F.s));
+        return CF_OK;
+    });
+}
+
+TokenMap token_map(const cf_model_desc& m) {
+    TokenMap t;
+    t.n_total = m.n_total;
+    t.n_local = m.n_total / m.sp_degree;
+    if (m.kind == CF_DOUBLE_STREAM) {
+        const int tl = m.n_txt_total / m.sp_degree, il = t.n_local - tl;
+        t.pos0 = m.sp_rank * tl; t.len0 = tl;
+        t.pos1 = m.n_txt_total + m.sp_rank * il; t.len1 = il;
+    } else {
+        t.pos0 = m.sp_rank * t.n_local; t.len0 = t.n_local;
+        t.pos1 = m.n_total; t.len1 = 0;
+    }
+    return t;
+}
+
+// emulated collectives standing for the Ulysses exchanges (n of them back to back)
+int cf_comm_begin_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute);
+int cf_comm_end_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute);
+
+int emulate_collectives(Fwd& F, int n) {
+    cf_ctx* c = F.c;
+    if (!c->comm_stream || !c->comm_bytes) return CF_OK;
+    CF_TRY(cf_comm_begin_impl(c, c->comm_stream, F.s));
+    const uint64_t half = c->comm_bytes / 2;
+    for (int i = 0; i < n; ++i) {
+        CF_HIP(c, hipMemcpyAsync(c->comm_dev, c->comm_host, half, hipMemcpyHostToDevice, c->comm_stream));
+        CF_HIP(c, hipMemcpyAsync(c->comm_host + half, c->comm_dev + half, half, hipMemcpyDeviceToHost, c->comm_stream));
+        c->stats.comm_bytes_h2d += half;
+        c->stats.comm_bytes_d2h += half;
+    }
+    return cf_comm_end_impl(c, c->comm_stream, F.s);
+}
+
+// q/k/v of the local rows (already in ws.qkv) -> attention over the joint sequence -> rows of all
+// heads for the local tokens in `dst` (leading dimension ld)
+int run_joint_attention(Fwd& F, const RelayoutArgs* parts, int n_parts, bf16* dst, int ld) {
+    cf_ctx* c = F.c;
+    const cf_model_desc& m = c->d;
+    const int P = m.sp_degree, hl = m.n_heads / P, h0 = m.sp_rank * hl, hd = m.head_dim;
+    const TokenMap map = token_map(m);
+    const int npad = n_pad_of(m.n_total);
+    const cf_block_io* io = F.io;
+    for (int i = 0; i < n_parts; ++i) {
+        ProfScope ps(c, F.s, K_RELAYOUT, 0, 2.0 * 2 * parts[i].rows * 3.0 * m.d);
+        CF_HIP(c, relayout_launch(parts[i], F.s));
+    }
+    if (P > 1) {
+        if (!io->peer_q || !io->peer_k || !io->peer_v || !io->peer_attn)
+            return fail(c, CF_ERR_ARG, "sp_degree > 1 needs peer_q, peer_k, peer_v and peer_attn");
+        ProfScope ps(c, F.s, K_PEER, 0, 2.0 * 2 * 3 * hl * (double)(map.n_total - map.n_local) * hd);
+        CF_HIP(c, peer_scatter_launch((const bf16*)io->peer_q, (const bf16*)io->peer_k, (const bf16*)io->peer_v,
+                                      F.ws.Q, F.ws.K, F.ws.Vt, hl, hd, npad, map, F.s));
+    }
+    CF_TRY(emulate_collectives(F, 3));
+    AttnArgs a;
+    a.Q = F.ws.Q; a.K = F.ws.K; a.Vt = F.ws.Vt;
+    a.H = hl; a.nq = m.n_total; a.nk = m.n_total; a.nk_pad = npad; a.hd = hd;
+    a.scale = 1.0f / sqrtf((float)hd);
+    if (P == 1) { a.O = dst; a.o_hs = hd; a.o_qs = ld; }
+    else { a.O = F.ws.O; a.o_hs = (long)m.n_total * hd; a.o_qs = hd; }
+    if (const char* msg = attn_check(a)) return fail(c, CF_ERR_ARG, "%s", msg);
+    {
+        ProfScope ps(c, F.s, K_ATTN, 4.0 * hl * (double)m.n_total * m.n_total * hd, 0);
+        CF_HIP(c, attn_launch(a, F.s));
+    }
+    if (P > 1) {
+        ProfScope ps(c, F.s, K_GATHER, 0, 2.0 * 2 * ((double)hl * m.n_total + (double)map.n_local * (m.n_heads - hl)) * hd);
+        CF_HIP(c, attn_gather_launch(F.ws.O, (const bf16*)io->peer_attn, dst, ld, (bf16*)io->send_attn, m.n_heads, h0,
+                                     hl, hd, map, F.s));
+    }
+    return emulate_collectives(F, 1);
+}
+
+RelayoutArgs relayout_for(Fwd& F, const bf16* src, int rows, int row0, const std::string& qn, const std::string& kn) {
+    const cf_model_desc& m = F.c->d;
+    RelayoutArgs r{};
+    r.src = src; r.ld = 3 * m.d; r.rows = rows;
+    r.col_q = 0; r.col_k = m.d; r.col_v = 2 * m.d;
+    r.n_heads = m.n_heads;
+    r.h_local = m.n_heads / m.sp_degree;
+    r.h0 = m.sp_rank * r.h_local;
+    r.hd = m.head_dim;
+    r.W = F.W;
+    r.has_norm = m.qk_rmsnorm;
+    if (m.qk_rmsnorm) { r.qn_off = T(F.c, qn).off; r.kn_off = T(F.c, kn).off; }
+    r.map = token_map(m);
+    r.row0 = row0;
+    r.Q = F.ws.Q; r.K = F.ws.K; r.Vt = F.ws.Vt;
+    r.n_pad = n_pad_of(m.n_total);
+    r.send_q = (bf16*)F.io->send_q; r.send_k = (bf16*)F.io->send_k; r.send_v = (bf16*)F.io->send_v;
+    return r;
+}
+
+// ---- MM-DiT single-stream block (App. B)
+int fwd_single(Fwd& F) {
+    cf_ctx* c = F.c;
+    const cf_model_desc& m = c->d;
+    const int d = m.d, f = m.f, nl = m.n_total / m.sp_degree;
+    const cf_block_io* io = F.io;
+    CF_TRY(run_modvec(F, "w_mod", "b_mod", io->temb, F.ws.mod));
+    const float *shift = F.ws.mod, *scale = F.ws.mod + d, *gate = F.ws.mod + 2 * d;
+    CF_TRY(run_ln_mod(F, io->x, shift, scale, F.ws.xn, nl));
+    if (m.qk_rmsnorm) { CF_TRY(need(F, T(c, "q_norm"))); CF_TRY(need(F, T(c, "k_norm"))); }
+    GemmArgs g{};
+    g.A = F.ws.xn; g.lda = d; g.M = nl; g.epi = EPI_SPLIT_GELU;
+    g.out0 = F.ws.qkv; g.ld0 = 3 * d; g.n_split = 3 * d;
+    g.out1 = F.ws.c; g.ld1 = d + f; g.col1_off = d;
+    CF_TRY(run_linear(F, K_LIN1, "w1", "b1", g));
+    RelayoutArgs r = relayout_for(F, F.ws.qkv, nl, 0, "q_norm", "k_norm");
+    CF_TRY(run_joint_attention(F, &r, 1, F.ws.c, d + f));
+    GemmArgs h{};
+    h.A = F.ws.c; h.lda = d + f; h.M = nl; h.epi = EPI_GATE_RESID;
+    h.resid = io->x; h.gate = gate; h.y = io->y; h.ldy = d;
+    return run_linear(F, K_LIN2, "w2", "b2", h);
+}
+
+int fwd_dit(Fwd& F);
+int fwd_double(Fwd& F);
+
+int check_desc(const cf_model_desc* m) {
+    if (!m) return fail(nullptr, CF_ERR_ARG, "null description");
+    if (m->kind < 0 || m->kind > 2) return fail(nullptr, CF_ERR_ARG, "unknown block kind %d", m->kind);
+    if (m->n_blocks <= 0) return fail(nullptr, CF_ERR_ARG, "n_blocks must be positive");
+    if (m->head_dim != 64 && m->head_dim != 128) return fail(nullptr, CF_ERR_ARG, "head_dim must be 64 or 128");
+    if (m->n_heads <= 0 || m->d != m->n_heads * m->head_dim) return fail(nullptr, CF_ERR_ARG, "d must equal n_heads * head_dim");
+    if (m->d % 256 || m->d > 4096) return fail(nullptr, CF_ERR_ARG, "d must be a multiple of 256, at most 4096");
+    const int nj = m->d / 256;
+    if (!(nj == 1 || nj == 2 || nj == 3 || nj == 4 || nj == 6 || nj == 8 || nj == 12 || nj == 16))
+        return fail(nullptr, CF_ERR_ARG, "d/256 must be one of 1,2,3,4,6,8,12,16");
+    if (m->f <= 0 || m->f % 64) return fail(nullptr, CF_ERR_ARG, "f must be a positive multiple of 64");
+    if (m->sp_degree <= 0 || m->sp_rank < 0 || m->sp_rank >= m->sp_degree) return fail(nullptr, CF_ERR_ARG, "bad sp_degree/sp_rank");
+    if (m->n_heads % m->sp_degree) return fail(nullptr, CF_ERR_ARG, "sp_degree must divide n_heads");
+    if (m->n_total <= 0 || m->n_total % m->sp_degree) return fail(nullptr, CF_ERR_ARG, "sp_degree must divide n_total");
+    if (m->kind == CF_DOUBLE_STREAM) {
+        if (m->n_txt_total <= 0 || m->n_txt_total >= m->n_total || m->n_txt_total % m->sp_degree)
+            return fail(nullptr, CF_ERR_ARG, "double-stream needs 0 < n_txt_total < n_total, divisible by sp_degree");
+    } else if (m->n_txt_total) {
+        return fail(nullptr, CF_ERR_ARG, "n_txt_total is only meaningful for double-stream blocks");
+    }
+    if (m->kind == CF_DIT_CROSS && m->l_ctx <= 0) return fail(nullptr, CF_ERR_ARG, "DiT block needs l_ctx > 0");
+    if (m->chunk_bytes == 0 || m->chunk_bytes % 256) return fail(nullptr, CF_ERR_ARG, "chunk_bytes must be a positive multiple of 256");
+    return CF_OK;
+}
+
+int check_block(const cf_ctx* c, int block) {
+    if (!c) return CF_ERR_ARG;
+    if (block < 0 || block >= c->d.n_blocks) return fail(c, CF_ERR_ARG, "block %d out of range [0,%d)", block, c->d.n_blocks);
+    return CF_OK;
+}
+
+}  // namespace
+
+// ==========================================================================================
+// ABI
+// ==========================================================================================
+extern "C" {
+
+int cf_create(const cf_model_desc* desc, cf_ctx** out) {
+    if (!out) return fail(nullptr, CF_ERR_ARG, "null out pointer");
+    *out = nullptr;
+    CF_TRY(check_desc(desc));
+    cf_ctx* c = new (std::nothrow) cf_ctx();
+    if (!c) return fail(nullptr, CF_ERR_NOMEM, "out of host memory");
+    c->d = *desc;
+    c->chunk_bytes = desc->chunk_bytes;
+    plan_layout(c);
+    c->ws_bytes = carve(c, nullptr).total;
+    c->host.assign(desc->n_blocks, nullptr);
+    c->res_buf.assign(desc->n_blocks, nullptr);
+    c->block_slot.assign(desc->n_blocks, -1);
+    *out = c;
+    return CF_OK;
+}
+
+int cf_destroy(cf_ctx* c) {
+    if (!c) return CF_ERR_ARG;
+    worker_drain(c);
+    worker_stop(c);
+    if (c->device_ready) {
+        (void)hipDeviceSynchronize();
+        free_weights(c);
+        for (int s = 0; s < 2; ++s) {
+            for (auto e : c->chunk_ev[s]) (void)hipEventDestroy(e);
+            (void)hipEventDestroy(c->done_ev[s]);
+        }
+        (void)hipEventDestroy(c->comm_ready_ev);
+        (void)hipEventDestroy(c->comm_done_ev);
+        for (auto& pe : c->prof_pending) { (void)hipEventDestroy(pe.a); (void)hipEventDestroy(pe.b); }
+        for (auto e : c->ev_pool) (void)hipEventDestroy(e);
+        if (c->comm_dev) (void)hipFree(c->comm_dev);
+    }
+    delete c;
+    return CF_OK;
+}
+
+const char* cf_last_error(const cf_ctx* c) { return c ? c->err.c_str() : g_create_err.c_str(); }
+
+int cf_blob_bytes(const cf_ctx* c, uint64_t* out) {
+    if (!c || !out) return CF_ERR_ARG;
+    *out = c->blob_bytes;
+    return CF_OK;
+}
+
+int cf_n_chunks(const cf_ctx* c, int32_t* out) {
+    if (!c || !out) return CF_ERR_ARG;
+    *out = c->n_chunks;
+    return CF_OK;
+}
+
+int cf_blob_layout(const cf_ctx* c, cf_tensor_slot* out, int32_t* n) {
+    if (!c || !n) return CF_ERR_ARG;
+    const int cnt = (int)c->tensors.size();
+    if (out) {
+        if (*n < cnt) return fail(c, CF_ERR_ARG, "layout needs room for %d tensors", cnt);
+        for (int i = 0; i < cnt; ++i) {
+            memset(&out[i], 0, sizeof out[i]);
+            snprintf(out[i].name, sizeof out[i].name, "%s", c->tensors[i].name.c_str());
+            out[i].offset = c->tensors[i].off;
+            out[i].rows = c->tensors[i].rows;
+            out[i].cols = c->tensors[i].cols;
+        }
+    }
+    *n = cnt;
+    return CF_OK;
+}
+
+int cf_workspace_bytes(const cf_ctx* c, uint64_t* out) {
+    if (!c || !out) return CF_ERR_ARG;
+    *out = c->ws_bytes;
+    return CF_OK;
+}
+
+int cf_register_block(cf_ctx* c, int32_t block, const void* host_blob, uint64_t bytes) {
+    CF_TRY(check_block(c, block));
+    if (!host_blob) return fail(c, CF_ERR_ARG, "null host blob");
+    if (bytes != c->blob_bytes)
+        return fail(c, CF_ERR_ARG, "blob is %llu bytes, layout needs %llu", (unsigned long long)bytes, (unsigned long long)c->blob_bytes);
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, host_blob);
+    if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
+        (void)hipGetLastError();
+        return fail(c, CF_ERR_ARG, "host blob must be pinned host memory (hipHostMalloc)");
+    }
+    CF_TRY(ensure_device(c));
+    worker_drain(c);
+    c->host[block] = (const uint8_t*)host_blob;
+    return upload_resident(c, block);
+}
+
+int set_resident_fraction(cf_ctx* c, double r, double* actual) {
+    if (!c) return CF_ERR_ARG;
+    if (!(r >= 0.0 && r <= 1.0)) return fail(c, CF_ERR_ARG, "resident fraction %g outside [0,1]", r);
+    const int n_res = (int)std::floor(r * c->n_chunks + 0.5);
+    const uint64_t res_bytes = n_res ? chunk_end(c, n_res - 1) : 0;
+    if (actual) *actual = (double)res_bytes / (double)c->blob_bytes;
+    CF_TRY(ensure_device(c));
+    worker_drain(c);
+    CF_HIP(c, hipDeviceSynchronize());
+    free_weights(c);
+    c->n_res_chunks = n_res;
+    c->res_bytes = res_bytes;
+    const uint64_t slot_bytes = c->blob_bytes - res_bytes;
+    if (slot_bytes) {
+        for (int s = 0; s < 2; ++s)
+            if (hipMalloc((void**)&c->slot[s], slot_bytes) != hipSuccess) {
+                (void)hipGetLastError();
+                return fail(c, CF_ERR_NOMEM, "hipMalloc of a %llu-byte staging slot failed", (unsigned long long)slot_bytes);
+            }
+    }
+    for (int b = 0; b < c->d.n_blocks; ++b) CF_TRY(upload_resident(c, b));
+    return CF_OK;
+}
+
+int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
+    CF_TRY(check_block(c, block));
+    if (!c->host[block]) return fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
+    CF_TRY(ensure_device(c));
+    if (c->n_res_chunks == c->n_chunks) return CF_OK;              // 100 % resident: nothing to move
+    if (!c->slot[0]) CF_TRY(set_resident_fraction(c, 0.0, nullptr));
+    if (c->block_slot[block] >= 0 && c->slot_state[c->block_slot[block]] == SLOT_FILLED)
+        return fail(c, CF_ERR_STATE, "block %d is already prefetched and waiting for its forward", block);
+    const int s = c->next_slot;                                    // slots alternate per prefetch
+    if (c->slot_state[s] == SLOT_FILLED)
+        return fail(c, CF_ERR_STATE, "slot %d still holds block %d whose forward has not been issued", s, c->slot_tenant[s]);
+    c->next_slot ^= 1;
+    if (c->slot_tenant[s] >= 0 && c->block_slot[c->slot_tenant[s]] == s) c->block_slot[c->slot_tenant[s]] = -1;
+    c->slot_tenant[s] = block;
+    c->block_slot[block] = s;
+    c->slot_state[s] = SLOT_FILLED;
+    if (c->pause_resume) {
+        if (!c->worker.joinable()) c->worker = std::thread(worker_main, c);
+        {
+            std::lock_guard<std::mutex> lk(c->mu);
+            c->enq_count[s] = c->n_res_chunks;
+            c->jobs.push_back(PrefetchJob{block, s, (hipStream_t)copy_stream});
+        }
+        c->cv.notify_all();
+        return CF_OK;
+    }
+    return enqueue_block_copies(c, block, s, (hipStream_t)copy_stream, false);
+}
+
+int chunked_prefetch_wait(cf_ctx* c, int32_t block, int32_t chunk, void* compute_stream) {
+    CF_TRY(check_block(c, block));
+    if (chunk < -1 || chunk >= c->n_chunks) return fail(c, CF_ERR_ARG, "chunk %d out of range", chunk);
+    const int last = chunk < 0 ? c->n_chunks - 1 : chunk;
+    if (last < c->n_res_chunks) return CF_OK;
+    // the copy stream is in order: waiting for `last` covers every earlier chunk
+    return wait_chunk(c, block, last, (hipStream_t)compute_stream);
+}
+
+int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute_stream) {
+    CF_TRY(check_block(c, block));
+    if (!io) return fail(c, CF_ERR_ARG, "null io");
+    if (!io->x || !io->temb || !io->y) return fail(c, CF_ERR_ARG, "x, temb and y are required");
+    if (!io->workspace || io->workspace_bytes < c->ws_bytes || ((uintptr_t)io->workspace % 256))
+        return fail(c, CF_ERR_ARG, "workspace must be 256-byte aligned and at least %llu bytes", (unsigned long long)c->ws_bytes);
+    if (((uintptr_t)io->x | (uintptr_t)io->y | (uintptr_t)io->temb) % 16) return fail(c, CF_ERR_ARG, "x, y, temb must be 16-byte aligned");
+    if (c->d.kind == CF_DOUBLE_STREAM && (!io->x_txt || !io->y_txt)) return fail(c, CF_ERR_ARG, "double-stream needs x_txt and y_txt");
+    if (c->d.kind == CF_DIT_CROSS && !io->ctx) return fail(c, CF_ERR_ARG, "DiT block needs ctx");
+    if (!c->host[block]) return fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
+    CF_TRY(ensure_device(c));
+    const int s = c->block_slot[block];
+    const bool streamed = c->n_res_chunks < c->n_chunks;
+    if (streamed && (s < 0 || c->slot_tenant[s] != block || c->slot_state[s] != SLOT_FILLED))
+        return fail(c, CF_ERR_STATE, "block %d: chunked_prefetch_begin must precede dit_block_fwd", block);
+
+    Fwd F{c, block, (hipStream_t)compute_stream, view_of(c, block), io, carve(c, (char*)io->workspace)};
+    c->waited_upto = c->n_res_chunks - 1;
+    int rc;
+    switch (c->d.kind) {
+        case CF_SINGLE_STREAM: rc = fwd_single(F); break;
+        case CF_DIT_CROSS: rc = fwd_dit(F); break;
+        default: rc = fwd_double(F); break;
+    }
+    if (rc != CF_OK) return rc;
+    if (streamed) {
+        CF_TRY(chunked_prefetch_wait(c, block, -1, compute_stream));   // no-op unless a tail chunk fed nothing
+        CF_HIP(c, hipEventRecord(c->done_ev[s], (hipStream_t)compute_stream));
+        c->done_valid[s] = true;
+        c->slot_state[s] = SLOT_CONSUMED;
+    }
+    return CF_OK;
+}
+
+int cf_set_contention(cf_ctx* c, void* comm_stream, void* host_pinned, uint64_t host_bytes,
+                      uint64_t bytes_per_collective, int32_t pause_resume) {
+    if (!c) return CF_ERR_ARG;
+    CF_TRY(ensure_device(c));
+    worker_drain(c);
+    CF_HIP(c, hipDeviceSynchronize());
+    if (!comm_stream) {
+        c->comm_stream = nullptr;
+        c->comm_bytes = 0;
+        c->pause_resume = false;
+        worker_stop(c);
+        return CF_OK;
+    }
+    if (bytes_per_collective % 512) return fail(c, CF_ERR_ARG, "bytes_per_collective must be a multiple of 512");
+    if (bytes_per_collective) {
+        if (!host_pinned || host_bytes < bytes_per_collective) return fail(c, CF_ERR_ARG, "pinned host buffer too small");
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, host_pinned) != hipSuccess || attr.type != hipMemoryTypeHost) {
+            (void)hipGetLastError();
+            return fail(c, CF_ERR_ARG, "collective host buffer must be pinned host memory");
+        }
+        if (c->comm_dev) (void)hipFree(c->comm_dev);
+        c->comm_dev = nullptr;
+        if (hipMalloc((void**)&c->comm_dev, bytes_per_collective) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(c, CF_ERR_NOMEM, "hipMalloc of the collective buffer failed");
+        }
+    }
+    c->comm_stream = (hipStream_t)comm_stream;
+    c->comm_host = (uint8_t*)host_pinned;
+    c->comm_bytes = bytes_per_collective;
+    c->pause_resume = pause_resume != 0;
+    if (!c->pause_resume) worker_stop(c);
+    return CF_OK;
+}
+
+int cf_comm_begin(cf_ctx* c, void* comm_stream, void* compute_stream) {
+    if (!c || !comm_stream) return CF_ERR_ARG;
+    CF_TRY(ensure_device(c));
+    return cf_comm_begin_impl(c, (hipStream_t)comm_stream, (hipStream_t)compute_stream);
+}
+
+int cf_comm_end(cf_ctx* c, void* comm_stream, void* compute_stream) {
+    if (!c || !comm_stream) return CF_ERR_ARG;
+    CF_TRY(ensure_device(c));
+    return cf_comm_end_impl(c, (hipStream_t)comm_stream, (hipStream_t)compute_stream);
+}
+
+int cf_checksum_block(cf_ctx* c, int32_t block, uint64_t* host_out, void* stream) {
+    CF_TRY(check_block(c, block));
+    if (!host_out) return fail(c, CF_ERR_ARG, "null output");
+    CF_TRY(ensure_device(c));
+    hipStream_t s = (hipStream_t)stream;
+    if (c->n_res_chunks < c->n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
+    uint64_t* dev = nullptr;
+    if (hipMalloc((void**)&dev, 8ull * c->n_chunks) != hipSuccess) { (void)hipGetLastError(); return fail(c, CF_ERR_NOMEM, "hipMalloc failed"); }
+    const WView v = view_of(c, block);
+    int rc = CF_OK;
+    for (int k = 0; k < c->n_chunks && rc == CF_OK; ++k) {
+        const uint64_t b = chunk_begin(c, k), e = chunk_end(c, k);
+        const char* p = (b < v.split ? v.lo : v.hi) + b;
+        hipError_t he = checksum_launch(p, e - b, b / 8, dev + k, s);
+        if (he != hipSuccess) rc = fail(c, CF_ERR_HIP, "checksum launch failed: %s", hipGetErrorString(he));
+    }
+    if (rc == CF_OK && hipMemcpyAsync(host_out, dev, 8ull * c->n_chunks, hipMemcpyDeviceToHost, s) != hipSuccess) rc = fail(c, CF_ERR_HIP, "checksum copy failed");
+    if (hipStreamSynchronize(s) != hipSuccess && rc == CF_OK) rc = fail(c, CF_ERR_HIP, "checksum sync failed");
+    (void)hipFree(dev);
+    return rc;
+}
+
+int cf_read_block(cf_ctx* c, int32_t block, void* host_out, void* stream) {
+    CF_TRY(check_block(c, block));
+    if (!host_out) return fail(c, CF_ERR_ARG, "null output");
+    CF_TRY(ensure_device(c));
+    hipStream_t s = (hipStream_t)stream;
+    if (c->n_res_chunks < c->n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
+    if (c->res_bytes) {
+        if (!c->res_buf[block]) return fail(c, CF_ERR_STATE, "block %d not registered", block);
+        CF_HIP(c, hipMemcpyAsync(host_out, c->res_buf[block], c->res_bytes, hipMemcpyDeviceToHost, s));
+    }
+    if (c->res_bytes < c->blob_bytes)
+        CF_HIP(c, hipMemcpyAsync((char*)host_out + c->res_bytes, c->slot[c->block_slot[block]], c->blob_bytes - c->res_bytes, hipMemcpyDeviceToHost, s));
+    CF_HIP(c, hipStreamSynchronize(s));
+    return CF_OK;
+}
+
+int cf_stats(cf_ctx* c, cf_stats_t* out) {
+    if (!c || !out) return CF_ERR_ARG;
+    std::lock_guard<std::mutex> lk(c->mu);
+    *out = c->stats;
+    out->resident_bytes = c->res_bytes;
+    out->blob_bytes = c->blob_bytes;
+    out->weight_memory_bytes = c->res_bytes * (uint64_t)c->d.n_blocks + 2 * (c->blob_bytes - c->res_bytes);
+    return CF_OK;
+}
+
+int cf_stats_reset(cf_ctx* c) {
+    if (!c) return CF_ERR_ARG;
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->stats = cf_stats_t{};
+    return CF_OK;
+}
+
+int cf_set_profiling(cf_ctx* c, int32_t on) {
+    if (!c) return CF_ERR_ARG;
+    c->profiling = on != 0;
+    return CF_OK;
+}
+
+int cf_kernel_times(cf_ctx* c, cf_kernel_time* out, int32_t* n) {
+    if (!c || !n) return CF_ERR_ARG;
+    worker_drain(c);
+    CF_TRY(prof_resolve(c));
+    int cnt = 0;
+    for (auto& k : c->ktimes)
+        if (k.launches) ++cnt;
+    if (out) {
+        if (*n < cnt) return fail(c, CF_ERR_ARG, "need room for %d kernel records", cnt);
+        int i = 0;
+        for (auto& k : c->ktimes)
+            if (k.launches) out[i++] = k;
+    }
+    *n = cnt;
+    return CF_OK;
+}
+
+int cf_kernel_times_reset(cf_ctx* c) {
+    if (!c) return CF_ERR_ARG;
+    CF_TRY(prof_resolve(c));
+    c->ktimes.clear();
+    return CF_OK;
+}
+
+int cf_sync(cf_ctx* c) {
+    if (!c) return CF_ERR_ARG;
+    worker_drain(c);
+    CF_HIP(c, hipDeviceSynchronize());
+    if (!c->worker_err.empty()) return fail(c, CF_ERR_HIP, "prefetch worker: %s", c->worker_err.c_str());
+    return CF_OK;
+}
+
+// ---- single kernels -----------------------------------------------------------------------
+static WView flat_view(const void* blob) { return WView{(const char*)blob, (const char*)blob, ~0ull}; }
+
+int cf_op_linear(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off, int32_t M, int32_t N,
+                 int32_t K, int32_t n0, int32_t n1, int32_t n_split, uint16_t* out0, int32_t ld0, uint16_t* out1,
+                 int32_t ld1, void* stream) {
+    if (!A || !blob) return fail(nullptr, CF_ERR_ARG, "null operand");
+    GemmArgs g{};
+    g.A = (const bf16*)A; g.lda = lda; g.W = flat_view(blob); g.w_off = w_off;
+    g.has_bias = bias_off >= 0; g.bias_off = bias_off >= 0 ? (uint64_t)bias_off : 0;
+    g.M = M; g.N = N; g.K = K; g.n0 = n0; g.n1 = n1; g.epi = EPI_SPLIT_GELU;
+    g.out0 = (bf16*)out0; g.ld0 = ld0; g.n_split = n_split; g.out1 = (bf16*)out1; g.ld1 = ld1; g.col1_off = 0;
+    if (const char* msg = gemm_check(g)) return fail(nullptr, CF_ERR_ARG, "%s", msg);
+    hipError_t e = gemm_launch(g, (hipStream_t)stream);
+    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "gemm launch: %s", hipGetErrorString(e));
+}
+
+int cf_op_linear_residual(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off, int32_t M,
+                          int32_t N, int32_t K, const float* resid, const float* gate, float* y, void* stream) {
+    if (!A || !blob) return fail(nullptr, CF_ERR_ARG, "null operand");
+    GemmArgs g{};
+    g.A = (const bf16*)A; g.lda = lda; g.W = flat_view(blob); g.w_off = w_off;
+    g.has_bias = bias_off >= 0; g.bias_off = bias_off >= 0 ? (uint64_t)bias_off : 0;
+    g.M = M; g.N = N; g.K = K; g.n0 = 0; g.n1 = N; g.epi = EPI_GATE_RESID;
+    g.resid = resid; g.gate = gate; g.y = y; g.ldy = N;
+    if (const char* msg = gemm_check(g)) return fail(nullptr, CF_ERR_ARG, "%s", msg);
+    hipError_t e = gemm_launch(g, (hipStream_t)stream);
+    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "gemm launch: %s", hipGetErrorString(e));
+}
+
+int cf_op_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, int32_t H, int32_t nq,
+                    int32_t nk, int32_t nk_pad, int32_t hd, void* stream) {
+    AttnArgs a{};
+    a.Q = (const bf16*)Q; a.K = (const bf16*)K; a.Vt = (const bf16*)Vt; a.O = (bf16*)O;
+    a.o_hs = (long)nq * hd; a.o_qs = hd; a.H = H; a.nq = nq; a.nk = nk; a.nk_pad = nk_pad; a.hd = hd;
+    a.scale = 1.0f / sqrtf((float)hd);
+    if (const char* msg = attn_check(a)) return fail(nullptr, CF_ERR_ARG, "%s", msg);
+    hipError_t e = attn_launch(a, (hipStream_t)stream);
+    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "attention launch: %s", hipGetErrorString(e));
+}
+
+int cf_op_ln_modulate(const float* x, const float* shift, const float* scale, uint16_t* xn, int32_t rows, int32_t d,
+                      void* stream) {
+    if (!x || !shift || !scale || !xn) return fail(nullptr, CF_ERR_ARG, "null operand");
+    hipError_t e = ln_modulate_launch(x, shift, scale, (bf16*)xn, rows, d, d, (hipStream_t)stream);
+    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_ARG, "ln_modulate: %s", hipGetErrorString(e));
+}
+
+int cf_op_modvec(const void* blob, uint64_t w_off, uint64_t b_off, const float* t, float* m, int32_t n, int32_t K,
+                 void* stream) {
+    if (!blob || !t || !m || (w_off % 16) || (K % 8)) return fail(nullptr, CF_ERR_ARG, "bad modvec operands");
+    hipError_t e = modvec_launch(flat_view(blob), w_off, b_off, t, m, 0, n, K, (hipStream_t)stream);
+    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "modvec: %s", hipGetErrorString(e));
+}
+
+int cf_op_checksum(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* host_out, void* stream) {
+    if (!data || !host_out) return fail(nullptr, CF_ERR_ARG, "null operand");
+    uint64_t* dev = nullptr;
+    if (hipMalloc((void**)&dev, 8) != hipSuccess) { (void)hipGetLastError(); return fail(nullptr, CF_ERR_NOMEM, "hipMalloc failed"); }
+    hipError_t e = checksum_launch(data, bytes, first_word, dev, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(host_out, dev, 8, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(dev);
+    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "checksum: %s", hipGetErrorString(e));
+}
+
+}  // extern "C"
+
+namespace {
+
+int cf_comm_begin_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute) {
+    // the collective may start once the compute stream has produced its operands
+    CF_HIP(c, hipEventRecord(c->comm_ready_ev, compute));
+    if (c->pause_resume) {
+        // pause request in GPU time: the host waits until compute has really reached the collective,
+        // so that the flag is not raised while the GPU is still far behind the host
+        CF_HIP(c, hipEventSynchronize(c->comm_ready_ev));
+    }
+    CF_HIP(c, hipStreamWaitEvent(comm, c->comm_ready_ev, 0));
+    return CF_OK;
+}
+
+int cf_comm_end_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute) {
+    {
+        std::lock_guard<std::mutex> lk(c->mu);
+        CF_HIP(c, hipEventRecord(c->comm_done_ev, comm));
+        if (c->pause_resume) c->pause_flag = true;
+    }
+    CF_HIP(c, hipStreamWaitEvent(compute, c->comm_done_ev, 0));
+    return CF_OK;
+}
+
+int fwd_dit(Fwd& F) { return fail(F.c, CF_ERR_UNSUPPORTED, "DiT block forward not built yet"); }
+int fwd_double(Fwd& F) { return fail(F.c, CF_ERR_UNSUPPORTED, "double-stream block forward not built yet"); }
+
+}  // namespace
+
+const TensorDesc* cf_find(const cf_ctx* c, const char* name) {
+    for (auto& t : c->tensors)
+        if (t.name == name) return &t;
+    return nullptr;
+}

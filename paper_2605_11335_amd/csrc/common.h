@@ -1,0 +1,47 @@
+// Shared device-side types for the block kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef __bf16 bf16;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+// A block's weight blob as the kernels see it: bytes [0, split) of the blob live in the
+// block's resident buffer (`lo`), bytes [split, blob) in the staging slot the prefetch fills
+// (`hi`); both pointers are biased so that `ptr + blob_offset` addresses the byte.  `split`
+// is a multiple of 256, so an aligned 16-byte access never straddles the two.
+struct WView {
+    const char* lo;
+    const char* hi;
+    uint64_t split;
+};
+
+__device__ __forceinline__ const char* wv_ptr(const WView& w, uint64_t boff) {
+    return (boff < w.split ? w.lo : w.hi) + boff;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) {
+    return __uint_as_float(((uint32_t)b) << 16);
+}
+
+__device__ __forceinline__ float wv_bf16(const WView& w, uint64_t boff_of_tensor, uint32_t idx) {
+    return bf16_bits_to_float(*(const uint16_t*)wv_ptr(w, boff_of_tensor + 2ull * idx));
+}
+
+// Workgroup id -> logical tile id such that each XCD (workgroups are dealt round-robin to the
+// 8 XCDs) walks one contiguous range of logical ids and so shares operands in its own L2.
+__device__ __forceinline__ uint32_t xcd_contiguous_id(uint32_t bid, uint32_t nb) {
+    const uint32_t q = nb >> 3, r = nb & 7u;
+    const uint32_t xcd = bid & 7u, idx = bid >> 3;
+    return xcd < r ? xcd * (q + 1) + idx : r * (q + 1) + (xcd - r) * q + idx;
+}
+
+// x * sigmoid(2u), u = sqrt(2/pi) (x + 0.044715 x^3): the tanh form of GELU.
+__device__ __forceinline__ float gelu_tanh_f32(float x) {
+    const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
+    const float en = __builtin_amdgcn_exp2f(u * -2.8853900817779268f);  // exp(-2u)
+    return x * __builtin_amdgcn_rcpf(1.0f + en);
+}

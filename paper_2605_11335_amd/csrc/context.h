@@ -1,0 +1,91 @@
+// Library-internal state: blob layout, chunk plan, residency, staging slots, events, the
+// prefetch worker and the per-kernel profiler.  Not part of the ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <condition_variable>
+#include <deque>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "../../include/chunkflow.h"
+#include "kernels.h"
+
+struct TensorDesc {
+    std::string name;
+    uint64_t off;
+    uint32_t rows, cols;
+    uint64_t bytes() const { return 2ull * rows * cols; }
+};
+
+struct ProfEntry {
+    int kid;
+    hipEvent_t a, b;
+    double flops, bytes;
+};
+
+enum { SLOT_EMPTY = 0, SLOT_FILLED = 1, SLOT_CONSUMED = 2 };
+
+struct PrefetchJob {
+    int block;
+    int slot;
+    hipStream_t copy;
+};
+
+struct cf_ctx {
+    cf_model_desc d{};
+    std::vector<TensorDesc> tensors;
+    uint64_t blob_bytes = 0, chunk_bytes = 0;
+    int n_chunks = 0;
+    uint64_t ws_bytes = 0;
+
+    // residency (Sec. 3.3): leading n_res_chunks chunks of every block stay in HBM
+    int n_res_chunks = 0;
+    uint64_t res_bytes = 0;
+    std::vector<const uint8_t*> host;
+    std::vector<uint8_t*> res_buf;
+
+    // staging (Sec. 2.2: two layers live) -- slot s holds blob bytes [res_bytes, blob) of its tenant
+    bool device_ready = false;
+    int device = 0;
+    uint8_t* slot[2] = {nullptr, nullptr};
+    int slot_tenant[2] = {-1, -1};
+    std::vector<int> block_slot;        // slot holding the block's streamed bytes, or -1
+    int next_slot = 0;                  // slots alternate per prefetch
+    int slot_state[2] = {SLOT_EMPTY, SLOT_EMPTY};
+    std::vector<hipEvent_t> chunk_ev[2];
+    hipEvent_t done_ev[2] = {nullptr, nullptr};
+    bool done_valid[2] = {false, false};
+    int waited_upto = -1;               // highest chunk the current forward already waited for
+
+    // emulated collectives + pause/resume (Sec. 3.2)
+    hipStream_t comm_stream = nullptr;
+    uint8_t* comm_host = nullptr;
+    uint8_t* comm_dev = nullptr;
+    uint64_t comm_bytes = 0;
+    bool pause_resume = false;
+    hipEvent_t comm_ready_ev = nullptr, comm_done_ev = nullptr;
+
+    std::thread worker;
+    std::mutex mu;
+    std::condition_variable cv;
+    std::deque<PrefetchJob> jobs;
+    bool worker_stop = false, worker_busy = false;
+    bool pause_flag = false;            // guarded by mu: a collective was issued, done event recorded
+    int enq_count[2] = {0, 0};          // chunks of the slot's tenant whose copy has been enqueued
+    std::string worker_err;
+
+    // statistics / profiling
+    cf_stats_t stats{};
+    bool profiling = false;
+    std::vector<ProfEntry> prof_pending;
+    std::vector<hipEvent_t> ev_pool;
+    std::vector<cf_kernel_time> ktimes;
+
+    mutable std::string err;
+};
+
+const TensorDesc* cf_find(const cf_ctx* c, const char* name);

@@ -1,0 +1,381 @@
+// HBM-bound kernels of the block: adaLN modulation vector, LayerNorm+modulate, q/k RMSNorm
+// with the Ulysses head-major relayout, the stand-ins for the two exchanges around attention
+// (Sec. 2.1), and the streamed-bytes checksum.  All accesses are 8- or 16-byte per lane and
+// consecutive lanes touch consecutive addresses.
+#include "common.h"
+#include "kernels.h"
+
+namespace {
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+__device__ __forceinline__ void unpack8(const uint4& u, float* f) {
+    f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
+    f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
+    f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xffff0000u);
+    f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
+}
+
+__device__ __forceinline__ int local_pos(const TokenMap& m, int i) {
+    return i < m.len0 ? m.pos0 + i : m.pos1 + (i - m.len0);
+}
+// i-th position (ascending) that is NOT local
+__device__ __forceinline__ int remote_pos(const TokenMap& m, int i) {
+    if (i < m.pos0) return i;
+    i += m.len0;
+    if (m.len1 == 0 || i < m.pos1) return i;
+    return i + m.len1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// m[n] = W[n,:] . t + b[n]; one wave per output row
+__global__ __launch_bounds__(256) void modvec_kernel(WView W, uint64_t w_off, uint64_t b_off, const float* __restrict__ t,
+                                                     float* __restrict__ m, int n0, int n1, int K) {
+    const int lane = threadIdx.x & 63;
+    const int n = n0 + blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (n >= n1) return;
+    const uint64_t row = w_off + (uint64_t)n * K * 2;
+    float acc = 0.f;
+    for (int c = lane; c < K / 8; c += 64) {
+        const uint4 u = *(const uint4*)wv_ptr(W, row + (uint64_t)c * 16);
+        float w[8];
+        unpack8(u, w);
+        const float4 t0 = *(const float4*)(t + c * 8), t1 = *(const float4*)(t + c * 8 + 4);
+        acc += w[0] * t0.x + w[1] * t0.y + w[2] * t0.z + w[3] * t0.w + w[4] * t1.x + w[5] * t1.y + w[6] * t1.z + w[7] * t1.w;
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) m[n] = acc + wv_bf16(W, b_off, n);
+}
+
+// ---------------------------------------------------------------------------------------------
+// LayerNorm over d (no affine, biased variance, eps 1e-6) then modulate or affine; wave per row
+template <int NJ, bool AFFINE>
+__global__ __launch_bounds__(256) void ln_kernel(const float* __restrict__ x, const float* __restrict__ shift,
+                                                 const float* __restrict__ scale, WView W, uint64_t w_off,
+                                                 uint64_t b_off, bf16* __restrict__ out, int rows, int d, int ld_out) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const float* xr = x + (size_t)row * d;
+    float4 v[NJ];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        v[j] = *(const float4*)(xr + (lane + 64 * j) * 4);
+        s += v[j].x + v[j].y + v[j].z + v[j].w;
+    }
+    const float mean = wave_sum(s) / d;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        v[j].x -= mean; v[j].y -= mean; v[j].z -= mean; v[j].w -= mean;
+        q += v[j].x * v[j].x + v[j].y * v[j].y + v[j].z * v[j].z + v[j].w * v[j].w;
+    }
+    const float rstd = rsqrtf(wave_sum(q) / d + 1e-6f);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int c = (lane + 64 * j) * 4;
+        float a[4], b[4];
+        if (AFFINE) {
+            const uint2 wa = *(const uint2*)wv_ptr(W, w_off + 2ull * c), wb = *(const uint2*)wv_ptr(W, b_off + 2ull * c);
+            a[0] = __uint_as_float(wa.x << 16); a[1] = __uint_as_float(wa.x & 0xffff0000u);
+            a[2] = __uint_as_float(wa.y << 16); a[3] = __uint_as_float(wa.y & 0xffff0000u);
+            b[0] = __uint_as_float(wb.x << 16); b[1] = __uint_as_float(wb.x & 0xffff0000u);
+            b[2] = __uint_as_float(wb.y << 16); b[3] = __uint_as_float(wb.y & 0xffff0000u);
+        } else {
+            const float4 sc = *(const float4*)(scale + c), sh = *(const float4*)(shift + c);
+            a[0] = 1.f + sc.x; a[1] = 1.f + sc.y; a[2] = 1.f + sc.z; a[3] = 1.f + sc.w;
+            b[0] = sh.x; b[1] = sh.y; b[2] = sh.z; b[3] = sh.w;
+        }
+        bf16x4 o;
+        o[0] = (bf16)(v[j].x * rstd * a[0] + b[0]);
+        o[1] = (bf16)(v[j].y * rstd * a[1] + b[1]);
+        o[2] = (bf16)(v[j].z * rstd * a[2] + b[2]);
+        o[3] = (bf16)(v[j].w * rstd * a[3] + b[3]);
+        *(bf16x4*)(out + (size_t)row * ld_out + c) = o;
+    }
+}
+
+template <bool AFFINE>
+hipError_t ln_dispatch(const float* x, const float* shift, const float* scale, const WView& W, uint64_t w_off,
+                       uint64_t b_off, bf16* out, int rows, int d, int ld_out, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    if (d % 256 || d > 4096) return hipErrorInvalidValue;
+    const dim3 grid((rows + 3) / 4), blk(256);
+#define CF_LN_CASE(NJ) case NJ: hipLaunchKernelGGL((ln_kernel<NJ, AFFINE>), grid, blk, 0, s, x, shift, scale, W, w_off, b_off, out, rows, d, ld_out); break;
+    switch (d / 256) {
+        CF_LN_CASE(1) CF_LN_CASE(2) CF_LN_CASE(3) CF_LN_CASE(4) CF_LN_CASE(6) CF_LN_CASE(8) CF_LN_CASE(12) CF_LN_CASE(16)
+        default: return hipErrorInvalidValue;
+    }
+#undef CF_LN_CASE
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// q,k: optional per-head RMSNorm, then head-major placement (own heads) or send buffers (others).
+// v of other heads: send buffer.  A group of hd/8 lanes owns one (row, tensor, head) vector.
+__global__ __launch_bounds__(256) void qk_relayout_kernel(RelayoutArgs r) {
+    const int lph = r.hd / 8;                       // lanes per head vector
+    const int vec_per_blk = 256 / lph;
+    const long n_vec = (long)r.rows * 3 * r.n_heads;
+    const int sub = threadIdx.x % lph;
+    for (long vi = (long)blockIdx.x * vec_per_blk + threadIdx.x / lph; vi < n_vec; vi += (long)gridDim.x * vec_per_blk) {
+        const int hh = vi % r.n_heads;
+        const int tns = (vi / r.n_heads) % 3;       // 0 q, 1 k, 2 v
+        const int row = vi / (3 * r.n_heads);
+        const int col = tns == 0 ? r.col_q : (tns == 1 ? r.col_k : r.col_v);
+        const bool own = hh >= r.h0 && hh < r.h0 + r.h_local;
+        bf16* dst;
+        const int lrow = r.row0 + row;
+        if (own) {
+            if (tns == 2) continue;                 // own v goes through the transposing kernel
+            bf16* base = tns == 0 ? r.Q : r.K;
+            dst = base + ((size_t)(hh - r.h0) * r.map.n_total + local_pos(r.map, lrow)) * r.hd;
+        } else {
+            bf16* base = tns == 0 ? r.send_q : (tns == 1 ? r.send_k : r.send_v);
+            if (!base) continue;
+            const int ho = hh < r.h0 ? hh : hh - r.h_local;
+            dst = base + ((size_t)ho * r.map.n_local + lrow) * r.hd;
+        }
+        if (col < 0) continue;
+        uint4 u = *(const uint4*)(r.src + (size_t)row * r.ld + col + hh * r.hd + sub * 8);
+        if (r.has_norm && tns < 2) {
+            float f[8];
+            unpack8(u, f);
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+            for (int o = lph >> 1; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+            const float rs = rsqrtf(ss / r.hd + 1e-6f);
+            const uint4 wu = *(const uint4*)wv_ptr(r.W, (tns == 0 ? r.qn_off : r.kn_off) + sub * 16);
+            float w[8];
+            unpack8(wu, w);
+            bf16x8 o8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o8[e] = (bf16)(f[e] * rs * w[e]);
+            *(bf16x8*)(dst + sub * 8) = o8;
+        } else {
+            *(uint4*)(dst + sub * 8) = u;
+        }
+    }
+}
+
+// [token, hd] rows of one head -> Vt[head, d, position] (keys contiguous).  64 tokens per block.
+// src element (h, i, d) at src + h*src_hs + i*src_rs + d; i counts local rows (remote=0) or
+// remote rows (remote=1) and maps to its position in the joint sequence.
+__global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict__ src, long src_hs, long src_rs, int n_rows,
+                                                          int row0, bf16* __restrict__ Vt, int hd, int n_pad, TokenMap map,
+                                                          int remote) {
+    __shared__ uint16_t tile[64 * (128 + 2)];
+    const int h = blockIdx.y;
+    const int i0 = blockIdx.x * 64;
+    const int stride = hd + 2;
+    const int cpr = hd / 8;
+    for (int q = threadIdx.x; q < 64 * cpr; q += 256) {
+        const int tr = q / cpr, c = q % cpr;
+        uint4 u = make_uint4(0, 0, 0, 0);
+        if (i0 + tr < n_rows) u = *(const uint4*)(src + (size_t)h * src_hs + (size_t)(i0 + tr) * src_rs + c * 8);
+        uint32_t* t32 = (uint32_t*)(tile + tr * stride + c * 8);   // stride even: 4-byte aligned
+        t32[0] = u.x; t32[1] = u.y; t32[2] = u.z; t32[3] = u.w;
+    }
+    __syncthreads();
+    // each thread: one d row, 8 consecutive tokens
+    for (int q = threadIdx.x; q < hd * 8; q += 256) {
+        const int dd = q >> 3, tg = (q & 7) * 8;
+        if (i0 + tg >= n_rows) continue;
+        const int i_first = row0 + i0 + tg;
+        const int p_first = remote ? remote_pos(map, i_first) : local_pos(map, i_first);
+        const int cnt = min(8, n_rows - (i0 + tg));
+        const int i_last = i_first + cnt - 1;
+        const int p_last = remote ? remote_pos(map, i_last) : local_pos(map, i_last);
+        bf16* drow = Vt + ((size_t)h * hd + dd) * n_pad;
+        if (cnt == 8 && p_last - p_first == 7 && (p_first & 7) == 0) {
+            uint16_t e[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) e[k] = tile[(tg + k) * stride + dd];
+            uint4 u;
+            u.x = e[0] | ((uint32_t)e[1] << 16); u.y = e[2] | ((uint32_t)e[3] << 16);
+            u.z = e[4] | ((uint32_t)e[5] << 16); u.w = e[6] | ((uint32_t)e[7] << 16);
+            *(uint4*)(drow + p_first) = u;
+        } else {
+            for (int k = 0; k < cnt; ++k) {
+                const int p = remote ? remote_pos(map, i_first + k) : local_pos(map, i_first + k);
+                ((uint16_t*)drow)[p] = tile[(tg + k) * stride + dd];
+            }
+        }
+    }
+    // zero the pad columns once per (head, d) row
+    if (blockIdx.x == 0 && !remote) {
+        for (int q = threadIdx.x; q < hd * (n_pad - map.n_total); q += 256) {
+            const int dd = q / (n_pad - map.n_total), p = map.n_total + q % (n_pad - map.n_total);
+            ((uint16_t*)Vt)[((size_t)h * hd + dd) * n_pad + p] = 0;
+        }
+    }
+}
+
+// peer q/k rows -> head-major operands at the remote positions (16-byte chunk copies)
+__global__ __launch_bounds__(256) void peer_qk_kernel(const bf16* __restrict__ pq, const bf16* __restrict__ pk,
+                                                      bf16* __restrict__ Q, bf16* __restrict__ K, int h_local, int hd, TokenMap map) {
+    const int cpr = hd / 8;
+    const int n_rem = map.n_total - map.n_local;
+    const long total = 2L * h_local * n_rem * cpr;
+    for (long q = (long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long)gridDim.x * 256) {
+        const int c = q % cpr;
+        long rest = q / cpr;
+        const int i = rest % n_rem; rest /= n_rem;
+        const int h = rest % h_local;
+        const int tns = rest / h_local;
+        const bf16* s = (tns ? pk : pq) + ((size_t)h * n_rem + i) * hd + c * 8;
+        bf16* d = (tns ? K : Q) + ((size_t)h * map.n_total + remote_pos(map, i)) * hd + c * 8;
+        *(uint4*)d = *(const uint4*)s;
+    }
+}
+
+// attention output on the full sequence -> projection operand rows + send buffer; peer heads in
+__global__ __launch_bounds__(256) void attn_gather_kernel(const bf16* __restrict__ O, const bf16* __restrict__ peer_attn,
+                                                          bf16* __restrict__ dst, int ld, bf16* __restrict__ send_attn,
+                                                          int n_heads, int h0, int h_local, int hd, TokenMap map) {
+    const int cpr = hd / 8;
+    const int n_rem = map.n_total - map.n_local;
+    const long n_loc = (long)h_local * map.n_local * cpr;
+    const long n_snd = send_attn ? (long)h_local * n_rem * cpr : 0;
+    const long n_peer = (long)map.n_local * (n_heads - h_local) * cpr;
+    for (long q = (long)blockIdx.x * 256 + threadIdx.x; q < n_loc + n_snd + n_peer; q += (long)gridDim.x * 256) {
+        if (q < n_loc) {
+            const int c = q % cpr;
+            long rest = q / cpr;
+            const int h = rest % h_local;
+            const int i = rest / h_local;
+            const bf16* s = O + ((size_t)h * map.n_total + local_pos(map, i)) * hd + c * 8;
+            *(uint4*)(dst + (size_t)i * ld + (h0 + h) * hd + c * 8) = *(const uint4*)s;
+        } else if (q < n_loc + n_snd) {
+            const long qq = q - n_loc;
+            const int c = qq % cpr;
+            long rest = qq / cpr;
+            const int i = rest % n_rem;
+            const int h = rest / n_rem;
+            const bf16* s = O + ((size_t)h * map.n_total + remote_pos(map, i)) * hd + c * 8;
+            *(uint4*)(send_attn + ((size_t)h * n_rem + i) * hd + c * 8) = *(const uint4*)s;
+        } else {
+            const long qq = q - n_loc - n_snd;
+            const int c = qq % cpr;
+            long rest = qq / cpr;
+            const int ho = rest % (n_heads - h_local);
+            const int i = rest / (n_heads - h_local);
+            const int hh = ho < h0 ? ho : ho + h_local;
+            const bf16* s = peer_attn + ((size_t)i * (n_heads - h_local) + ho) * hd + c * 8;
+            *(uint4*)(dst + (size_t)i * ld + hh * hd + c * 8) = *(const uint4*)s;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__global__ __launch_bounds__(256) void zero_u64_kernel(uint64_t* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0; }
+
+// sum over 64-bit words of mix(word ^ (index+1)*GOLDEN), index counted from the blob start
+__global__ __launch_bounds__(256) void checksum_kernel(const uint64_t* __restrict__ w, uint64_t n_words, uint64_t first_word,
+                                                       unsigned long long* __restrict__ out) {
+    uint64_t acc = 0;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (uint64_t)gridDim.x * 256)
+        acc += mix64(w[i] ^ ((first_word + i + 1) * 0x9E3779B97F4A7C15ull));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)acc, o), hi = __shfl_xor((uint32_t)(acc >> 32), o);
+        acc += ((uint64_t)hi << 32) | lo;
+    }
+    if ((threadIdx.x & 63) == 0) atomicAdd(out, (unsigned long long)acc);
+}
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ s, bf16* __restrict__ d, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) d[i] = (bf16)s[i];
+}
+
+inline int grid_for(long items, int per_block, int cap = 256 * 16) {
+    long b = (items + per_block - 1) / per_block;
+    return (int)(b < 1 ? 1 : (b > cap ? cap : b));
+}
+
+}  // namespace
+
+hipError_t modvec_launch(const WView& W, uint64_t w_off, uint64_t b_off, const float* t, float* m, int n0, int n1,
+                         int K, hipStream_t s) {
+    if (n1 <= n0) return hipSuccess;
+    if (K % 8) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(modvec_kernel, dim3((n1 - n0 + 3) / 4), dim3(256), 0, s, W, w_off, b_off, t, m, n0, n1, K);
+    return hipGetLastError();
+}
+
+hipError_t ln_modulate_launch(const float* x, const float* shift, const float* scale, bf16* xn, int rows, int d,
+                              int ld_out, hipStream_t s) {
+    WView none{nullptr, nullptr, 0};
+    return ln_dispatch<false>(x, shift, scale, none, 0, 0, xn, rows, d, ld_out, s);
+}
+
+hipError_t ln_affine_launch(const float* x, const WView& W, uint64_t w_off, uint64_t b_off, bf16* xn, int rows, int d,
+                            hipStream_t s) {
+    return ln_dispatch<true>(x, nullptr, nullptr, W, w_off, b_off, xn, rows, d, d, s);
+}
+
+hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s) {
+    if (r.rows <= 0) return hipSuccess;
+    if (r.hd != 64 && r.hd != 128) return hipErrorInvalidValue;
+    const long n_vec = (long)r.rows * 3 * r.n_heads;
+    hipLaunchKernelGGL(qk_relayout_kernel, dim3(grid_for(n_vec, 256 / (r.hd / 8))), dim3(256), 0, s, r);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (r.col_v >= 0 && r.Vt) {
+        // own heads of v, transposed
+        hipLaunchKernelGGL(v_transpose_kernel, dim3((r.rows + 63) / 64, r.h_local), dim3(256), 0, s,
+                           r.src + r.col_v + (size_t)r.h0 * r.hd, (long)r.hd, (long)r.ld, r.rows, r.row0, r.Vt, r.hd,
+                           r.n_pad, r.map, 0);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+hipError_t peer_scatter_launch(const bf16* peer_q, const bf16* peer_k, const bf16* peer_v, bf16* Q, bf16* K, bf16* Vt,
+                               int h_local, int hd, int n_pad, TokenMap map, hipStream_t s) {
+    const int n_rem = map.n_total - map.n_local;
+    if (n_rem <= 0) return hipSuccess;
+    const long total = 2L * h_local * n_rem * (hd / 8);
+    hipLaunchKernelGGL(peer_qk_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, peer_q, peer_k, Q, K, h_local, hd, map);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(v_transpose_kernel, dim3((n_rem + 63) / 64, h_local), dim3(256), 0, s, peer_v,
+                       (long)n_rem * hd, (long)hd, n_rem, 0, Vt, hd, n_pad, map, 1);
+    return hipGetLastError();
+}
+
+hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, int ld, bf16* send_attn,
+                              int n_heads, int h0, int h_local, int hd, TokenMap map, hipStream_t s) {
+    const int cpr = hd / 8;
+    const long total = (long)h_local * map.n_total * cpr + (long)map.n_local * (n_heads - h_local) * cpr;
+    hipLaunchKernelGGL(attn_gather_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, O_full, peer_attn, dst, ld,
+                       send_attn, n_heads, h0, h_local, hd, map);
+    return hipGetLastError();
+}
+
+hipError_t checksum_launch(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* out, hipStream_t s) {
+    if (bytes % 8 || ((uintptr_t)data % 8)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(zero_u64_kernel, dim3(1), dim3(64), 0, s, out);
+    if (bytes)
+        hipLaunchKernelGGL(checksum_kernel, dim3(grid_for((long)(bytes / 8), 256 * 8, 2048)), dim3(256), 0, s,
+                           (const uint64_t*)data, bytes / 8, first_word, (unsigned long long*)out);
+    return hipGetLastError();
+}
+
+hipError_t f32_to_bf16_launch(const float* src, bf16* dst, size_t n, hipStream_t s) {
+    if (!n) return hipSuccess;
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(grid_for((long)n, 256 * 4)), dim3(256), 0, s, src, dst, n);
+    return hipGetLastError();
+}

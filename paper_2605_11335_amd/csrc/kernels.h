@@ -1,0 +1,86 @@
+// Host-visible launchers of the block kernels.  Every launcher validates shapes against
+// what its kernel assumes (`*_check` returns a message or nullptr) before anything runs.
+#pragma once
+#include "common.h"
+
+enum { EPI_SPLIT_GELU = 0, EPI_GATE_RESID = 1 };
+
+struct GemmArgs {
+    const bf16* A;      // [M, lda] activations
+    int lda;
+    WView W;            // weight blob view
+    uint64_t w_off;     // blob offset of W[0][0]; W is [N, K] bf16 row-major
+    uint64_t bias_off;  // blob offset of bias[N] (bf16)
+    int has_bias;
+    int M, N, K;
+    int n0, n1;         // output-feature panel covered by this launch
+    int epi;
+    // EPI_SPLIT_GELU: features [0, n_split) -> out0[m*ld0 + n] (bf16);
+    //                 features [n_split, N) -> gelu_tanh -> out1[m*ld1 + col1_off + n - n_split]
+    bf16* out0; int ld0; int n_split;
+    bf16* out1; int ld1; int col1_off;
+    // EPI_GATE_RESID: y[m*ldy + n] = resid[m*ldy + n] + gate[n] * (acc + bias)   (fp32; gate NULL = 1)
+    const float* resid; const float* gate; float* y; int ldy;
+};
+const char* gemm_check(const GemmArgs& g);
+hipError_t gemm_launch(const GemmArgs& g, hipStream_t s);
+
+// Positions of this rank's tokens in the joint sequence: up to two contiguous segments
+// (text rows, image rows).  Local row i < len0 sits at pos0 + i, else at pos1 + (i - len0).
+struct TokenMap {
+    int n_total, n_local;
+    int pos0, len0, pos1, len1;
+};
+
+struct AttnArgs {
+    const bf16* Q;      // [H, nq, hd] head-major
+    const bf16* K;      // [H, nk, hd]
+    const bf16* Vt;     // [H, hd, nk_pad] keys contiguous, pad columns zero
+    bf16* O;            // element (h, q, :) at O + h*o_hs + q*o_qs
+    long o_hs, o_qs;
+    int H, nq, nk, nk_pad, hd;
+    float scale;        // 1/sqrt(hd)
+};
+const char* attn_check(const AttnArgs& a);
+hipError_t attn_launch(const AttnArgs& a, hipStream_t s);
+
+// m[n] = sum_k W[n,k] t[k] + b[n]  (fp32 out), rows [n0, n1)
+hipError_t modvec_launch(const WView& W, uint64_t w_off, uint64_t b_off, const float* t, float* m,
+                         int n0, int n1, int K, hipStream_t s);
+
+// xn = LN(x) * (1 + scale) + shift  (fp32 in, bf16 out); with ln_w/ln_b (blob offsets, has_affine)
+// instead: xn = LN(x) * w + b.
+hipError_t ln_modulate_launch(const float* x, const float* shift, const float* scale, bf16* xn,
+                              int rows, int d, int ld_out, hipStream_t s);
+hipError_t ln_affine_launch(const float* x, const WView& W, uint64_t w_off, uint64_t b_off, bf16* xn,
+                            int rows, int d, hipStream_t s);
+
+// Split a projection output into head-major attention operands, with optional per-head RMSNorm.
+struct RelayoutArgs {
+    const bf16* src;        // [rows, ld] ; head h of tensor t at column col0[t] + h*hd
+    int ld, rows;
+    int col_q, col_k, col_v;          // -1 = tensor absent
+    int n_heads;                      // heads present in src (H)
+    int h0, h_local;                  // heads kept for attention: [h0, h0 + h_local)
+    int hd;
+    WView W; uint64_t qn_off, kn_off; int has_norm;
+    TokenMap map; int row0;           // src row i is local row row0 + i
+    bf16 *Q, *K, *Vt;                 // [h_local, n_total, hd] x2, [h_local, hd, n_pad]
+    int n_pad;
+    bf16 *send_q, *send_k, *send_v;   // [n_heads - h_local, n_local, hd] (may be NULL)
+};
+hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s);
+
+// Peer rows (what the exchange delivers) into the head-major operands at the remote positions.
+hipError_t peer_scatter_launch(const bf16* peer_q, const bf16* peer_k, const bf16* peer_v,
+                               bf16* Q, bf16* K, bf16* Vt, int h_local, int hd, int n_pad,
+                               TokenMap map, hipStream_t s);
+
+// After attention on the full sequence: local rows of the local heads and peer_attn (other heads)
+// into the [n_local, ld] operand of the output projection; remote rows into send_attn.
+hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, int ld,
+                              bf16* send_attn, int n_heads, int h0, int h_local, int hd,
+                              TokenMap map, hipStream_t s);
+
+hipError_t checksum_launch(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* out, hipStream_t s);
+hipError_t f32_to_bf16_launch(const float* src, bf16* dst, size_t n, hipStream_t s);

@@ -1,0 +1,101 @@
+"""CPU-side checks of the C ABI: the library loads, exports what the header declares, and the
+planning calls (which touch no GPU) behave: layout, chunking, argument errors."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import workload as wl
+from oracle import chunks as och
+from oracle import overlap_model as om
+from paper_2605_11335_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "chunkflow.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"^\s*(?:int|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_functions()
+    assert len(names) >= 25 and "dit_block_fwd" in names and "set_resident_fraction" in names
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(names) == sorted(B.EXPORTS)
+
+
+def ctx_for(cfg, chunk):
+    return B.Context(B.desc_from_config(cfg, chunk))
+
+
+def test_blob_bytes_follow_app_b_formulas():
+    flux = wl.CONFIGS["flux"]
+    c = ctx_for(flux, 16 << 20)
+    extra = c.cf_blob_bytes() - om.bytes_single(flux.d, flux.f)       # biases + norm weights + padding
+    assert 0 < extra < 100_000
+    hy = wl.CONFIGS["hunyuan"]
+    c2 = ctx_for(hy, 16 << 20)
+    extra = c2.cf_blob_bytes() - om.bytes_double(hy.d, hy.f)
+    assert 0 < extra < 300_000
+    wan = wl.CONFIGS["wan"]
+    c3 = ctx_for(wan, 16 << 20)
+    d, f = wan.d, wan.f
+    assert 0 < c3.cf_blob_bytes() - 2 * (6 * d * d + 4 * d * d + 4 * d * d + 2 * d * f) < 300_000
+
+
+@pytest.mark.parametrize("name", ["toy", "flux", "wan", "hunyuan"])
+def test_layout_is_aligned_ordered_and_complete(name):
+    cfg = wl.CONFIGS[name]
+    c = ctx_for(cfg, 1 << 20)
+    lay = c.cf_blob_layout()
+    specs = {n: shape for n, shape, _, _ in wl.param_specs(cfg)}
+    assert {t["name"] for t in lay} == set(specs)
+    end = 0
+    for t in lay:
+        assert t["offset"] % 256 == 0 and t["offset"] >= end
+        shape = specs[t["name"]]
+        assert t["rows"] * t["cols"] == int(__import__("numpy").prod(shape))
+        if len(shape) == 2:
+            assert (t["rows"], t["cols"]) == shape
+        end = t["offset"] + 2 * t["rows"] * t["cols"]
+    assert end <= c.cf_blob_bytes() < end + 256
+    assert c.cf_workspace_bytes() > 0
+
+
+def test_chunk_count_matches_oracle_arithmetic():
+    cfg = wl.CONFIGS["flux"]
+    for chunk in (16 << 20, 64 << 20, 256 << 20, 1 << 20):
+        c = ctx_for(cfg, chunk)
+        assert c.cf_n_chunks() == len(och.chunk_bounds(c.cf_blob_bytes(), chunk))
+
+
+def test_toy_config_is_four_chunks():
+    from paper_2605_11335_amd.runner import chunk_bytes_for
+    cfg = wl.CONFIGS["toy"]
+    cb = chunk_bytes_for(cfg)
+    assert cb % 256 == 0
+    assert ctx_for(cfg, cb).cf_n_chunks() == 4
+    assert ctx_for(wl.CONFIGS["flux"], chunk_bytes_for(wl.CONFIGS["flux"])).cf_n_chunks() == 8
+
+
+@pytest.mark.parametrize("field,value", [("chunk_bytes", 0), ("chunk_bytes", 1000), ("head_dim", 96), ("sp_degree", 5),
+                                         ("n_total", 4607), ("d", 3000), ("kind", 7), ("n_blocks", 0), ("f", 100),
+                                         ("sp_rank", 2)])
+def test_create_rejects_bad_descriptions(field, value):
+    d = B.desc_from_config(wl.CONFIGS["flux"], 16 << 20)
+    setattr(d, field, value)
+    with pytest.raises(B.ChunkflowError) as e:
+        B.Context(d)
+    assert e.value.code == B.CF_ERR_ARG and str(e.value)
+
+
+def test_block_range_is_checked_without_a_gpu():
+    c = ctx_for(wl.CONFIGS["toy"], 1 << 20)
+    with pytest.raises(B.ChunkflowError) as e:
+        c.chunked_prefetch_begin(5, None)
+    assert e.value.code == B.CF_ERR_ARG

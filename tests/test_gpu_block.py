@@ -1,0 +1,172 @@
+"""Block-level parity (HIP path vs float64 oracle on the same seeded inputs) and the streaming
+invariants: bit-exact weights in HBM, offloaded == resident bit for bit, I/O volume unchanged."""
+import numpy as np
+import pytest
+import torch
+
+import workload as wl
+from oracle import block as ob
+from oracle import chunks as och
+from paper_2605_11335_amd import binding as B
+from paper_2605_11335_amd.runner import BlockRunner, bits_of, chunk_bytes_for
+from tests.util import bits_to_f64, max_abs, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+REL_L2_TOL = 1e-2      # per block output
+MAX_ABS_TOL = 5e-2
+
+
+def check_outputs(cfg, tensors, ref, rows=None, send_rows=None):
+    y = tensors["y"].cpu().numpy()
+    if rows is not None:
+        y = y[rows]
+    x = tensors["x"].cpu().numpy() if rows is None else tensors["x"].cpu().numpy()[rows]
+    r, m = rel_l2(y, ref["y"]), max_abs(y, ref["y"])
+    rb = rel_l2(y - x, ref["y"] - x)
+    print(f"[{cfg.name}] y rel_l2={r:.3e} max_abs={m:.3e} branch rel_l2={rb:.3e}")
+    assert r <= REL_L2_TOL and m <= MAX_ABS_TOL
+    assert rb <= 2e-2
+    if cfg.sp_degree > 1:
+        for k in ("send_q", "send_k", "send_v"):
+            got = bits_to_f64(bits_of(tensors[k]))
+            if rows is not None and k == "send_q":
+                got = got[:, rows]
+            assert rel_l2(got, ref[k]) <= REL_L2_TOL and max_abs(got, ref[k]) <= MAX_ABS_TOL, k
+        got = bits_to_f64(bits_of(tensors["send_attn"]))
+        if send_rows is not None:
+            got = got[:, send_rows]
+        assert rel_l2(got, ref["send_attn"]) <= REL_L2_TOL and max_abs(got, ref["send_attn"]) <= MAX_ABS_TOL
+
+
+def run_and_check(cfg, n_blocks, chunk_bytes=None, r=0.0, rows=None, send_rows=None):
+    run = BlockRunner(cfg, chunk_bytes=chunk_bytes, n_blocks=n_blocks)
+    run.ctx.set_resident_fraction(r)
+    try:
+        for blk in range(n_blocks):
+            params = wl.gen_block_params(cfg, blk)
+            inputs = wl.gen_block_inputs(cfg, blk)
+            run.register_params(blk, params)
+            t = run.make_io(inputs)
+            run.run_block(blk, t)
+            ref = ob.block_forward(cfg, params, inputs, rows=rows, send_rows=send_rows)
+            check_outputs(cfg, t, ref, rows, send_rows)
+    finally:
+        run.close()
+
+
+def test_toy_config_parity():
+    """C1: 2 single-stream blocks, d=512, 8x64 heads, seq 512, 4 chunks per block."""
+    run_and_check(wl.CONFIGS["toy"], 2)
+
+
+@pytest.mark.parametrize("rank", [0, 1])
+def test_small_ulysses_share_parity(rank):
+    """A P=2 share with ragged sizes: 2 ranks' worth of 370 tokens, q/k RMSNorm, 128-wide heads."""
+    cfg = wl.BlockConfig("mini_sp2", wl.KIND_SINGLE, n_blocks=1, d=512, n_heads=4, head_dim=128, f=1024,
+                         n_total=740, sp_degree=2, sp_rank=rank, qk_rmsnorm=True, n_chunks=5, temb_std=1.0)
+    run_and_check(cfg, 1)
+    run_and_check(cfg, 1, r=0.5)
+
+
+def test_flux_share_parity_full_size():
+    """C2 at full size (one block): GEMMs on 2304 tokens, attention over 4608 for 12 heads."""
+    run_and_check(wl.CONFIGS["flux"], 1)
+
+
+def _outputs(run, t):
+    keys = ["y"] + [k for k in ("send_q", "send_k", "send_v", "send_attn") if k in t]
+    return {k: t[k].clone() for k in keys}
+
+
+@pytest.mark.parametrize("cfg_name,n_chunks", [("toy", 4), ("toy", 1), ("toy", 13)])
+def test_offloaded_equals_resident_bit_for_bit(cfg_name, n_chunks):
+    cfg = wl.CONFIGS[cfg_name]
+    cb = chunk_bytes_for(cfg, n_chunks)
+    run = BlockRunner(cfg, chunk_bytes=cb, n_blocks=2)
+    try:
+        ios = []
+        for blk in range(2):
+            run.register_params(blk, wl.gen_block_params(cfg, blk))
+            ios.append(run.make_io(wl.gen_block_inputs(cfg, blk)))
+        structs = [run.io_struct(t) for t in ios]
+        base = None
+        for r in (1.0, 0.0, 0.25, 0.5, 0.75):
+            actual = run.ctx.set_resident_fraction(r)
+            assert actual == och.resident_bytes(run.blob_bytes, cb, r) / run.blob_bytes
+            run.ctx.cf_stats_reset()
+            for t in ios:
+                t["y"].zero_()
+            run.step(structs, first_begun=False)      # begins 0, then (1, fwd 0), (0, fwd 1)
+            run.ctx.cf_sync()
+            outs = [t["y"].clone() for t in ios]
+            st = run.ctx.cf_stats()
+            # chunking never changes the volume: 3 prefetches of the non-resident bytes (Sec. 3.2)
+            assert st["h2d_bytes"] == 3 * (run.blob_bytes - st["resident_bytes"])
+            assert st["weight_memory_bytes"] == 2 * st["resident_bytes"] + 2 * (run.blob_bytes - st["resident_bytes"])
+            if r == 1.0:
+                assert st["h2d_bytes"] == 0
+                base = outs
+            else:
+                for a, b in zip(outs, base):
+                    assert torch.equal(a, b), f"r={r}"
+            # drain the pending prefetch of block 0 so that the next plan starts clean
+            run.fwd(0, structs[0])
+            run.ctx.cf_sync()
+    finally:
+        run.close()
+
+
+def test_streamed_weights_are_bit_exact():
+    cfg = wl.CONFIGS["toy"]
+    cb = chunk_bytes_for(cfg, 7)
+    run = BlockRunner(cfg, chunk_bytes=cb, n_blocks=2)
+    try:
+        blobs = [run.register_params(b, wl.gen_block_params(cfg, b)) for b in range(2)]
+        for r in (0.0, 0.4, 1.0):
+            run.ctx.set_resident_fraction(r)
+            for b in range(2):
+                run.begin(b)
+            for b in range(2):
+                host = blobs[b].numpy()
+                assert run.ctx.cf_checksum_block(b, run.compute) == och.chunk_checksums(host, cb)
+                assert np.array_equal(run.ctx.cf_read_block(b, run.compute), host)
+            t = run.make_io(wl.gen_block_inputs(cfg, 0))
+            for b in range(2):
+                run.fwd(b, run.io_struct(t))
+            run.ctx.cf_sync()
+    finally:
+        run.close()
+
+
+def test_call_order_errors():
+    cfg = wl.CONFIGS["toy"]
+    run = BlockRunner(cfg, n_blocks=2)
+    try:
+        for b in range(2):
+            run.register_params(b, wl.gen_block_params(cfg, b))
+        t = run.make_io(wl.gen_block_inputs(cfg, 0))
+        io = run.io_struct(t)
+        with pytest.raises(B.ChunkflowError) as e:
+            run.fwd(0, io)                              # forward before its prefetch
+        assert e.value.code == B.CF_ERR_STATE
+        with pytest.raises(B.ChunkflowError) as e:
+            run.ctx.chunked_prefetch_wait(0, -1, run.compute)
+        assert e.value.code == B.CF_ERR_STATE
+        run.begin(0)
+        run.begin(1)
+        with pytest.raises(B.ChunkflowError) as e:
+            run.begin(0)                                # both slots hold unconsumed blocks
+        assert e.value.code == B.CF_ERR_STATE
+        with pytest.raises(B.ChunkflowError) as e:
+            run.ctx.set_resident_fraction(1.5)
+        assert e.value.code == B.CF_ERR_ARG
+        unpinned = torch.empty(run.blob_bytes, dtype=torch.uint8)
+        with pytest.raises(B.ChunkflowError) as e:
+            run.ctx.cf_register_block(0, unpinned)
+        assert e.value.code == B.CF_ERR_ARG
+        run.fwd(0, io)
+        run.fwd(1, io)
+        run.ctx.cf_sync()
+    finally:
+        run.close()

@@ -1,0 +1,172 @@
+"""Element-by-element parity of each HIP kernel against the float64 oracle, through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import block as ob
+from oracle import chunks as och
+from paper_2605_11335_amd import binding as B
+from tests.util import (assert_bf16_close, bf16_round, bits_to_f64, dev_bits, host_bits, max_abs, rel_l2)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def make_blob(rng, N, K, bias=True, pad_front=512):
+    """W [N,K] and bias [N] (bf16) in one byte buffer at 256-aligned offsets."""
+    w, wb = bf16_round(rng.normal(size=(N, K)) * 0.05)
+    b, bb = bf16_round(rng.normal(size=N) * 0.5)
+    w_off = pad_front
+    b_off = (w_off + 2 * N * K + 255) // 256 * 256
+    buf = np.zeros(b_off + 2 * N + 256, dtype=np.uint8)
+    buf[w_off:w_off + 2 * N * K] = wb.reshape(-1).view(np.uint8)
+    buf[b_off:b_off + 2 * N] = bb.view(np.uint8)
+    return buf, w.astype(np.float64), b.astype(np.float64), w_off, (b_off if bias else -1)
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 512, 512), (300, 520, 192), (1000, 1304, 256), (2304, 2048, 3072), (37, 8, 64)])
+def test_linear_plain(M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    a, ab = bf16_round(rng.normal(size=(M, K)))
+    buf, w, b, w_off, b_off = make_blob(rng, N, K)
+    A, blob = dev_bits(ab), torch.from_numpy(buf).to(DEV)
+    out = torch.zeros((M, N), dtype=torch.int16, device=DEV)
+    B.cf_op_linear(A, blob, w_off, b_off, M, N, K, out)
+    torch.cuda.synchronize()
+    ref = a.astype(np.float64) @ w.T + b
+    assert_bf16_close(host_bits(out), ref, extra_abs=2e-5 * math.sqrt(K))
+
+
+def test_linear_panels_split_gelu_and_strides():
+    """Feature panels launched separately, GELU half into a wider destination, strided A."""
+    M, N, K, n_split = 700, 1024, 320, 512
+    rng = np.random.default_rng(5)
+    lda = K + 64
+    a_full, ab = bf16_round(rng.normal(size=(M, lda)))
+    a = a_full[:, :K]
+    buf, w, b, w_off, b_off = make_blob(rng, N, K)
+    A, blob = dev_bits(ab), torch.from_numpy(buf).to(DEV)
+    out0 = torch.zeros((M, n_split), dtype=torch.int16, device=DEV)
+    ld1 = 100 + (N - n_split)
+    out1 = torch.zeros((M, ld1), dtype=torch.int16, device=DEV)
+    out1_view = out1[:, 100:]
+    for n0, n1 in [(0, 256), (256, 768), (768, 1024)]:
+        B.cf_op_linear(A, blob, w_off, b_off, M, N, K, out0, out1_view, n_split=n_split, n0=n0, n1=n1, lda=lda,
+                       ld0=n_split, ld1=ld1)
+    torch.cuda.synchronize()
+    z = a.astype(np.float64) @ w.T + b
+    assert_bf16_close(host_bits(out0), z[:, :n_split], extra_abs=1e-4)
+    assert_bf16_close(host_bits(out1)[:, 100:], ob.gelu_tanh(z[:, n_split:]), extra_abs=2e-4)
+    assert (host_bits(out1)[:, :100] == 0).all()
+    # panel decomposition does not change a single bit
+    whole = torch.zeros_like(out0)
+    whole1 = torch.zeros_like(out1)
+    B.cf_op_linear(A, blob, w_off, b_off, M, N, K, whole, whole1[:, 100:], n_split=n_split, lda=lda, ld0=n_split, ld1=ld1)
+    torch.cuda.synchronize()
+    assert torch.equal(whole, out0) and torch.equal(whole1, out1)
+
+
+@pytest.mark.parametrize("M,N,K,gate", [(512, 512, 2560, True), (333, 264, 128, False)])
+def test_linear_gated_residual(M, N, K, gate):
+    rng = np.random.default_rng(9)
+    a, ab = bf16_round(rng.normal(size=(M, K)))
+    buf, w, b, w_off, b_off = make_blob(rng, N, K)
+    resid = rng.normal(size=(M, N)).astype(np.float32)
+    g = rng.normal(size=N).astype(np.float32)
+    y = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    B.cf_op_linear_residual(dev_bits(ab), torch.from_numpy(buf).to(DEV), w_off, b_off, M, N, K,
+                            torch.from_numpy(resid).to(DEV), torch.from_numpy(g).to(DEV) if gate else None, y)
+    torch.cuda.synchronize()
+    ref = resid.astype(np.float64) + (g.astype(np.float64) if gate else 1.0) * (a.astype(np.float64) @ w.T + b)
+    assert max_abs(y.cpu().numpy(), ref) < 5e-5 * math.sqrt(K) and rel_l2(y.cpu().numpy(), ref) < 1e-5
+
+
+def run_attention(q, k, v, hd):
+    H, nq, _ = q.shape
+    nk = k.shape[1]
+    nk_pad = (nk + 63) // 64 * 64
+    _, qb = bf16_round(q)
+    _, kb = bf16_round(k)
+    _, vb = bf16_round(v)
+    vt = np.zeros((H, hd, nk_pad), dtype=np.uint16)
+    vt[:, :, :nk] = vb.transpose(0, 2, 1)
+    O = torch.zeros((H, nq, hd), dtype=torch.int16, device=DEV)
+    B.cf_op_attention(dev_bits(qb), dev_bits(kb), dev_bits(vt), O, H, nq, nk, nk_pad, hd)
+    torch.cuda.synchronize()
+    ref = ob.attention(bits_to_f64(qb), bits_to_f64(kb), bits_to_f64(vb))
+    return bits_to_f64(host_bits(O)), ref
+
+
+@pytest.mark.parametrize("H,nq,nk,hd,sharp", [(2, 256, 256, 128, 1.0), (3, 200, 333, 128, 1.0), (2, 512, 512, 64, 1.0),
+                                              (1, 129, 65, 64, 1.0), (2, 300, 1000, 128, 4.0), (1, 1, 1, 128, 1.0),
+                                              (2, 384, 777, 64, 4.0)])
+def test_attention(H, nq, nk, hd, sharp):
+    rng = np.random.default_rng(H * 1000 + nq + nk + hd)
+    q = rng.normal(size=(H, nq, hd)) * sharp
+    k = rng.normal(size=(H, nk, hd)) * sharp
+    v = rng.normal(size=(H, nk, hd))
+    got, ref = run_attention(q, k, v, hd)
+    # P is rounded to bf16 before the second contraction and O is stored in bf16
+    assert rel_l2(got, ref) < 6e-3, rel_l2(got, ref)
+    assert max_abs(got, ref) < 2e-2 * max(1.0, np.abs(ref).max()), max_abs(got, ref)
+
+
+def test_attention_uniform_values_and_dominant_key():
+    rng = np.random.default_rng(77)
+    H, n, hd = 1, 200, 128
+    q, k = rng.normal(size=(H, n, hd)), rng.normal(size=(H, n, hd))
+    v = np.tile(rng.normal(size=(H, 1, hd)), (1, n, 1))
+    got, ref = run_attention(q, k, v, hd)
+    assert max_abs(got, ref) < 2e-2
+    k2 = k.copy()
+    k2[0, 150] = q[0, 3] * 50
+    v2 = rng.normal(size=(H, n, hd))
+    got, ref = run_attention(q, k2, v2, hd)
+    assert np.abs(got[0, 3] - bf16_round(v2[0, 150])[0]).max() < 1e-2
+
+
+@pytest.mark.parametrize("rows,d", [(100, 512), (37, 3072), (5, 256)])
+def test_ln_modulate(rows, d):
+    rng = np.random.default_rng(rows + d)
+    x = (rng.normal(size=(rows, d)) * 2 + 0.5).astype(np.float32)
+    shift, scale = rng.normal(size=d).astype(np.float32), rng.normal(size=d).astype(np.float32)
+    out = torch.zeros((rows, d), dtype=torch.int16, device=DEV)
+    B.cf_op_ln_modulate(torch.from_numpy(x).to(DEV), torch.from_numpy(shift).to(DEV), torch.from_numpy(scale).to(DEV),
+                        out, rows, d)
+    torch.cuda.synchronize()
+    ref = ob.modulate(ob.layernorm(x.astype(np.float64)), shift.astype(np.float64), scale.astype(np.float64))
+    assert_bf16_close(host_bits(out), ref, extra_abs=1e-5)
+
+
+def test_modvec():
+    n, K = 1536, 512
+    rng = np.random.default_rng(3)
+    buf, w, b, w_off, b_off = make_blob(rng, n, K)
+    t = rng.normal(size=K).astype(np.float32)
+    m = torch.zeros(n, dtype=torch.float32, device=DEV)
+    B.cf_op_modvec(torch.from_numpy(buf).to(DEV), w_off, b_off, torch.from_numpy(t).to(DEV), m, n, K)
+    torch.cuda.synchronize()
+    ref = w @ t.astype(np.float64) + b
+    assert max_abs(m.cpu().numpy(), ref) < 1e-4
+
+
+@pytest.mark.parametrize("nbytes,first", [(8, 0), (4096, 17), (1 << 20, 12345), (8 * 1001, 3)])
+def test_checksum_bit_exact(nbytes, first):
+    rng = np.random.default_rng(nbytes)
+    data = rng.integers(0, 256, size=nbytes, dtype=np.uint8)
+    got = B.cf_op_checksum(torch.from_numpy(data).to(DEV), nbytes, first)
+    assert got == och.checksum_words(data, first)
+
+
+def test_launch_checks_reject_bad_shapes():
+    z = torch.zeros(1024, dtype=torch.int16, device=DEV)
+    with pytest.raises(B.ChunkflowError):
+        B.cf_op_linear(z, z, 0, -1, 4, 8, 48, z)          # K not a multiple of 64
+    with pytest.raises(B.ChunkflowError):
+        B.cf_op_linear(z, z, 0, -1, 4, 12, 64, z)         # N not a multiple of 8
+    with pytest.raises(B.ChunkflowError):
+        B.cf_op_attention(z, z, z, z, 1, 4, 4, 4, 128)    # nk_pad not a multiple of 64
+    with pytest.raises(B.ChunkflowError):
+        B.cf_op_attention(z, z, z, z, 1, 4, 4, 64, 96)    # head_dim
