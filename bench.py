@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the layerwise-offloaded DiT block path on one MI355X.
+
+A "step" is one denoising step of the workload: one pass of the whole hot path (prefetch issue,
+per-chunk waits, modulation, LayerNorm, GEMMs, relayout, attention, gated residual) over all
+blocks of the configuration, in steady state (the prefetch of block 0 for the next step is issued
+during the last block).  Two arms are timed with the same kernels: fully resident (r = 1) and
+chunked offload (r = --resident, default 0 = every weight byte streamed from pinned host memory).
+
+Prints ONE JSON line: the offloaded step time as `value`, the resident step time beside it, the
+roofline of the dominant kernel (measured with HIP events on the compute stream, per launch) and
+the CPU oracle timed on this host's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+PEAK_LINK_GBS = 64.0           # PCIe Gen5 x16, one direction
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", default="flux", choices=["toy", "flux", "wan", "hunyuan"])
+    ap.add_argument("--blocks", type=int, default=0, help="override the number of blocks (0 = the config's)")
+    ap.add_argument("--resident", type=float, default=0.0, help="resident fraction of the offloaded arm")
+    ap.add_argument("--chunk-mib", type=float, default=0.0, help="chunk size in MiB (0 = the config's chunk count)")
+    ap.add_argument("--contention", choices=["off", "on", "pause"], default="off",
+                    help="emulated all-to-all traffic on a third stream; 'pause' adds pause/resume")
+    ap.add_argument("--sweep", action="store_true", help="memory-latency grid (r x chunk x contention) to stderr")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", choices=["both", "resident", "offload"], default="both")
+    return ap.parse_args()
+
+
+def time_steps(run, ios, steps, warmup, torch):
+    for _ in range(warmup):
+        run.step(ios)
+    run.ctx.cf_sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run.step(ios)
+    run.ctx.cf_sync()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import workload as wl
+    from paper_2605_11335_amd.runner import BlockRunner, chunk_bytes_for
+
+    cfg = wl.CONFIGS[args.config]
+    if args.blocks:
+        cfg = cfg.with_(n_blocks=args.blocks)
+    L = cfg.n_blocks
+    chunk_bytes = int(args.chunk_mib * (1 << 20)) if args.chunk_mib else chunk_bytes_for(cfg)
+
+    t_setup = time.perf_counter()
+    run = BlockRunner(cfg, chunk_bytes=chunk_bytes)
+    for b in range(L):
+        run.register_params(b, wl.gen_block_params(cfg, b))
+    # chained residual stream: block l writes the buffer block l+1 reads
+    tens = [run.make_io(wl.gen_block_inputs(cfg, b)) for b in range(L)]
+    for b in range(1, L):
+        tens[b]["x"] = tens[b - 1]["y"]
+        if "x_txt" in tens[b]:
+            tens[b]["x_txt"] = tens[b - 1]["y_txt"]
+    ios = [run.io_struct(t) for t in tens]
+    print(f"[bench] {cfg.name}: {L} blocks, blob {run.blob_bytes/1e6:.1f} MB, {run.n_chunks} chunks of "
+          f"{chunk_bytes/1e6:.2f} MB, setup {time.perf_counter()-t_setup:.1f}s", file=sys.stderr)
+
+    comm_host = None
+    def set_contention(mode):
+        nonlocal comm_host
+        if mode == "off":
+            run.ctx.cf_set_contention(None, None, 0, False)
+            return
+        nbytes = cfg.n_local * cfg.d * 2          # one [n_local, d] bf16 tensor per all-to-all
+        nbytes = nbytes // 512 * 512
+        if comm_host is None:
+            comm_host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        run.ctx.cf_set_contention(run.comm, comm_host, nbytes, mode == "pause")
+
+    def arm(r, steps, warmup, profile=False):
+        actual = run.ctx.set_resident_fraction(r)
+        run.ctx.cf_stats_reset()
+        run.begin(0)
+        if profile:
+            run.ctx.cf_kernel_times_reset()
+            run.ctx.cf_set_profiling(True)
+        ms = time_steps(run, ios, steps, warmup, torch)
+        st = run.ctx.cf_stats()
+        kt = run.ctx.cf_kernel_times() if profile else None
+        run.ctx.cf_set_profiling(False)
+        run.fwd(0, ios[0])                         # consume the pending prefetch
+        run.ctx.cf_sync()
+        return ms, actual, st, kt
+
+    set_contention(args.contention)
+    out = {}
+    flops_block = None
+    # ---- resident arm (also the per-kernel profile: same kernels, no waits)
+    res_ms, _, _, _ = arm(1.0, args.steps, args.warmup)
+    prof_ms, _, _, ktimes = arm(1.0, args.steps, args.warmup, profile=True)
+    # ---- offloaded arm
+    off_ms, actual_r, st, _ = arm(args.resident, args.steps, args.warmup)
+    total_steps = args.steps + args.warmup
+    h2d_per_step = L * (run.blob_bytes - st["resident_bytes"])
+    assert st["h2d_bytes"] == (total_steps * L + 1) * (run.blob_bytes - st["resident_bytes"]), "I/O volume changed"
+    h2d_gbs = h2d_per_step / (off_ms * 1e-3) / 1e9 if off_ms > 0 else 0.0
+
+    kern = {k["name"]: k for k in ktimes}
+    mfma = [k for k in ktimes if k["flops"] > 0 and k["name"] != "modvec"]
+    total_flops = sum(k["flops"] for k in mfma) / total_steps
+    dom = max(mfma, key=lambda k: k["total_ms"])
+    dom_ms = dom["total_ms"] / dom["launches"]
+    dom_flops = dom["flops"] / dom["launches"]
+    kernels = {}
+    for k in ktimes:
+        e = {"launches_per_step": k["launches"] / total_steps, "avg_ms": k["total_ms"] / k["launches"]}
+        if k["flops"] > 0 and k["name"] != "modvec":
+            e["tflops"] = k["flops"] / k["total_ms"] / 1e9
+            e["frac_mfma_peak"] = e["tflops"] / PEAK_BF16_TFLOPS
+        elif k["bytes"] > 0:
+            e["gbs"] = k["bytes"] / k["total_ms"] / 1e6
+            e["frac_hbm_peak"] = e["gbs"] / PEAK_HBM_GBS
+        kernels[k["name"]] = e
+
+    result = {
+        "metric": "denoise step ms (chunked offload vs resident)",
+        "value": off_ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": off_ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {L} blocks, d={cfg.d}, H={cfg.n_heads}x{cfg.head_dim}, f={cfg.f}, "
+                               f"N={cfg.n_total}, Ulysses P={cfg.sp_degree} share (GEMMs on {cfg.n_local} tokens, "
+                               f"attention {cfg.h_local} heads over {cfg.n_total})",
+                   "chunk_bytes": chunk_bytes, "chunks_per_block": run.n_chunks, "blob_bytes": run.blob_bytes,
+                   "resident_fraction": actual_r, "contention": args.contention},
+        "resident_ms": res_ms, "resident_ms_profiled": prof_ms,
+        "offload_over_resident": off_ms / res_ms,
+        "step_tflops_resident": total_flops / (res_ms * 1e-3) / 1e12,
+        "eta_comp_measured": total_flops / (res_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "h2d_gbs": h2d_gbs, "h2d_frac_link_peak": h2d_gbs / PEAK_LINK_GBS,
+        "h2d_bytes_per_step": h2d_per_step,
+        "exposed_prefetch_ms": off_ms - res_ms,
+        "weight_memory_bytes": st["weight_memory_bytes"],
+        "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": dom_flops / dom_ms / 1e9,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom_flops / dom_ms / 1e9 / PEAK_BF16_TFLOPS,
+                     "avg_launch_ms": dom_ms, "flops_per_launch": dom_flops, "traffic": None},
+        "kernels": kernels,
+    }
+
+    # ---- overlap-model view of this machine (Eq. 1-4 with the measured eta's)
+    blob = run.blob_bytes
+    t_comp_blk = res_ms / L
+    t_pref_blk = (blob / (h2d_gbs * 1e9) * 1e3) if h2d_gbs > 0 else None
+    result["model"] = {"t_comp_block_ms": t_comp_blk, "t_pref_block_ms": t_pref_blk,
+                       "hidden": (t_pref_blk is not None and t_comp_blk >= t_pref_blk),
+                       "i_block_flop_per_byte": total_flops / L / blob,
+                       "i_star_flop_per_byte": (total_flops / L / (t_comp_blk * 1e-3)) / (h2d_gbs * 1e9) if h2d_gbs else None}
+
+    if args.sweep:
+        grid = []
+        for mode in ("off", "on", "pause"):
+            set_contention(mode)
+            for r in (0.0, 0.25, 0.5, 0.75, 1.0):
+                ms, act, s2, _ = arm(r, max(3, args.steps // 2), 1)
+                grid.append({"contention": mode, "r": r, "actual_r": act, "step_ms": ms,
+                             "weight_memory_bytes": s2["weight_memory_bytes"],
+                             "h2d_gbs": L * (run.blob_bytes - s2["resident_bytes"]) / (ms * 1e-3) / 1e9,
+                             "pauses": s2["pauses"]})
+                print("[sweep] " + json.dumps(grid[-1]), file=sys.stderr)
+        set_contention("off")
+        result["sweep"] = grid
+
+    # ---- CPU oracle on this host, bounded sample: one full-size block
+    if not args.no_cpu_baseline:
+        from oracle import block as ob
+        import threadpoolctl
+        params, inputs = wl.gen_block_params(cfg, 0), wl.gen_block_inputs(cfg, 0)
+        rows = None
+        sample = "1 full block"
+        if cfg.n_total > 8192:                    # exact row sample: attention would take hours
+            rng = np.random.default_rng(1)
+            rows = np.sort(rng.choice(cfg.n_local, 256, replace=False))
+            sample = "256 of %d local rows of 1 block (all keys), scaled by rows" % cfg.n_local
+        t0 = time.perf_counter()
+        ob.block_forward(cfg, params, inputs, rows=rows, send_rows=(None if rows is None else np.arange(0)))
+        dt = time.perf_counter() - t0
+        scale = 1.0 if rows is None else cfg.n_local / 256.0
+        threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+        result["cpu_baseline"] = {"value": dt * 1e3 * L * scale, "unit": "ms", "cores": threads, "kind": "oracle",
+                                  "sample": f"{sample}, float64 NumPy, x{L} blocks per step"
+                                            + ("" if rows is None else " (linear extrapolation)")}
+    run.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -72,6 +72,9 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2605_11335_amd/build.py` "
                               "(there is no CPU or PyTorch fallback for the block path)")
+        # PyTorch ships its own HIP runtime; load it first so that this library binds to the same
+        # one (two runtimes in one process do not share the device)
+        import torch  # noqa: F401
         _lib = C.CDLL(LIB_PATH)
         _lib.cf_last_error.restype = C.c_char_p
         _lib.cf_last_error.argtypes = [C.c_void_p]

@@ -23,7 +23,7 @@ def header_functions():
 def test_library_exports_every_declared_symbol():
     names = header_functions()
     assert len(names) >= 25 and "dit_block_fwd" in names and "set_resident_fraction" in names
-    lib = C.CDLL(B.LIB_PATH)
+    lib = B.lib()
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(names) == sorted(B.EXPORTS)
