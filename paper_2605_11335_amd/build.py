@@ -12,7 +12,26 @@ SOURCES = ["chunkflow.hip", "gemm.hip", "attention.hip", "elementwise.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-pthread",
          # packed-fp32 VALU forms are kept out of every kernel
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument", "-Rpass-analysis=kernel-resource-usage"]
+
+
+def _resource_usage(lines):
+    """Parse hipcc's kernel-resource-usage remarks: {kernel: {field: int}}."""
+    usage, cur = {}, None
+    for l in lines:
+        if "kernel-resource-usage" not in l or "remark:" not in l:
+            continue
+        body = l.split("remark:", 1)[1].replace("[-Rpass-analysis=kernel-resource-usage]", "").strip()
+        if body.startswith("Function Name:"):
+            cur = body.split(":", 1)[1].strip()
+            usage[cur] = {}
+        elif cur is not None and ":" in body:
+            k, v = body.rsplit(":", 1)
+            try:
+                usage[cur][k.strip()] = int(v)
+            except ValueError:
+                pass
+    return usage
 
 
 def build_library(verbose: bool = True) -> str:
@@ -28,9 +47,15 @@ def build_library(verbose: bool = True) -> str:
         objs.append(obj)
     for src, p in procs:
         out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        lines = out.splitlines()
+        usage = _resource_usage(lines)
+        out = "\n".join(l for l in lines if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l)
         if p.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+        for kname, u in usage.items():
+            # a kernel that touches scratch memory has lost its register arrays: treat as a build error
+            if u.get("ScratchSize [bytes/lane]", 0) or u.get("VGPRs Spill", 0):
+                raise RuntimeError(f"{src}: kernel {kname} uses scratch memory: {u}")
         if verbose and out.strip():
             print(out, file=sys.stderr)
     link = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-pthread", "-o", LIB] + objs

@@ -19,6 +19,11 @@
 
 namespace {
 
+__device__ __forceinline__ void lds_load16(const void* gptr, void* lds) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
+                                     (void __attribute__((address_space(3)))*)lds, 16, 0, 0);
+}
+
 constexpr int BQ = 128;    // queries per workgroup (4 waves x 32)
 constexpr int BKV = 64;    // keys per tile
 
@@ -57,39 +62,36 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
         for (int kk = 0; kk < KS; ++kk) qf[kk] = *(const bf16x8*)(qp + kk * 16);
     }
 
-    // ---- per-thread sources for the tile copies
+    // ---- tile copies go global -> LDS directly: one load writes the wave's 64 x 16 bytes to
+    // consecutive LDS addresses (1 KiB = 1024/KROW key rows, or 8 V^T rows); the 16-byte chunk a
+    // lane fetches is the one whose swizzled slot it fills.
+    const int uw = __builtin_amdgcn_readfirstlane(wave);
+    constexpr int K_RPL = 1024 / KROW;          // key rows per wave-load
     const bf16* k_src[K_LOADS];
-    int k_row[K_LOADS], k_dst[K_LOADS];
+    int k_row[K_LOADS];
 #pragma unroll
     for (int j = 0; j < K_LOADS; ++j) {
-        const int q = tid + j * 256, key = q / KCH, c = q % KCH;
+        const int key = (j * 4 + uw) * K_RPL + lane / KCH;
+        const int c = (lane % KCH) ^ kswz(key);
         k_row[j] = key;
         k_src[j] = a.K + (size_t)h * a.nk * HD + c * 8;
-        k_dst[j] = key * KROW + ((c ^ kswz(key)) << 4);
     }
     const bf16* v_src[V_LOADS];
-    int v_dst[V_LOADS];
 #pragma unroll
     for (int j = 0; j < V_LOADS; ++j) {
-        const int q = tid + j * 256, row = q >> 3, c = q & 7;
+        const int row = (j * 4 + uw) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ vswz(row);
         v_src[j] = a.Vt + ((size_t)h * HD + row) * a.nk_pad + c * 8;
-        v_dst[j] = row * 128 + ((c ^ vswz(row)) << 4);
     }
-
-    uint4 rk[K_LOADS], rv[V_LOADS];
-    auto load_tile = [&](int t) {
+    auto issue_tile = [&](int t, int buf) {
         const int k0 = t * BKV;
+        char* dK = sK + buf * K_TILE + uw * 1024;
+        char* dV = sV + buf * V_TILE + uw * 1024;
 #pragma unroll
         for (int j = 0; j < K_LOADS; ++j)
-            rk[j] = *(const uint4*)(k_src[j] + (size_t)min(k0 + k_row[j], a.nk - 1) * HD);
+            lds_load16(k_src[j] + (size_t)min(k0 + k_row[j], a.nk - 1) * HD, dK + j * 4096);
 #pragma unroll
-        for (int j = 0; j < V_LOADS; ++j) rv[j] = *(const uint4*)(v_src[j] + k0);
-    };
-    auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < K_LOADS; ++j) *(uint4*)(sK + buf * K_TILE + k_dst[j]) = rk[j];
-#pragma unroll
-        for (int j = 0; j < V_LOADS; ++j) *(uint4*)(sV + buf * V_TILE + v_dst[j]) = rv[j];
+        for (int j = 0; j < V_LOADS; ++j) lds_load16(v_src[j] + k0, dV + j * 4096);
     };
 
     floatx16 o[DT];
@@ -104,13 +106,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
     const int krow = (lj & 0x13) | ((lj & 4) << 1) | ((lj & 8) >> 1);
 
     const int NT = (a.nk + BKV - 1) / BKV;
-    load_tile(0);
-    store_tile(0);
-    __syncthreads();
+    issue_tile(0, 0);
+    __syncthreads();                            // (waits for the LDS-DMA, then the barrier)
 
     for (int t = 0; t < NT; ++t) {
         const int buf = t & 1;
-        if (t + 1 < NT) load_tile(t + 1);
+        if (t + 1 < NT) issue_tile(t + 1, buf ^ 1);
         const char* cK = sK + buf * K_TILE;
         const char* cV = sV + buf * V_TILE;
 
@@ -178,8 +179,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
             }
         }
 
-        if (t + 1 < NT) store_tile(buf ^ 1);
-        __syncthreads();
+        __syncthreads();                        // tile t+1 has landed, tile t may be overwritten
     }
 
     // ---- normalise and store: lane = query, register quad = 4 consecutive d

@@ -9,9 +9,10 @@
 // (BM/2) x (BN/2) quadrant built from 32x32x16 bf16 MFMAs.  The MFMA "A" operand is the
 // weight fragment and the "B" operand the activation fragment, so an accumulator lane holds
 // one token row and 4 consecutive output features per register quad: epilogues then load
-// bias/gate and store results 4 features at a time.  K is consumed in slabs of 64 staged in
-// LDS, double-buffered; 16-byte chunks of each 128-byte LDS row are XOR-swizzled so that the
-// fragment reads of 16..32 consecutive rows spread over all banks.
+// bias/gate and store results 4 features at a time.  K is consumed in slabs of 64 that are
+// copied global -> LDS directly (no register staging), double-buffered; 16-byte chunks of each
+// 128-byte LDS row are XOR-swizzled so that the fragment reads of 16..32 consecutive rows
+// spread over all banks.
 #include "common.h"
 #include "kernels.h"
 
@@ -21,6 +22,13 @@ constexpr int BK = 64;                 // K slab (bf16 elements) = 128 bytes per
 constexpr int CHUNKS = BK / 8;         // 16-byte chunks per LDS row
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
+
+// 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds + 16*l
+// (`lds` must be wave-uniform).
+__device__ __forceinline__ void lds_load16(const void* gptr, void* lds) {
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
+                                     (void __attribute__((address_space(3)))*)lds, 16, 0, 0);
+}
 
 template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
@@ -52,23 +60,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     const int m0 = tm * BM;
     const int n0 = g.n0 + tn * BN;
 
-    // per-thread global sources for the slab copies (rows clamped: tails read valid memory)
+    // Slab copies go global -> LDS directly (no register staging).  One such load writes the
+    // wave's 64 x 16 bytes to consecutive LDS addresses, i.e. 8 rows of 128 bytes; which 16-byte
+    // chunk of its row a lane fetches is chosen so that the chunk lands in its swizzled slot.
+    const int uw = __builtin_amdgcn_readfirstlane(wave);
     const bf16* a_src[A_LOADS];
     uint64_t w_src[W_LOADS];
-    int a_dst[A_LOADS], w_dst[W_LOADS];
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
-        const int q = tid + j * 256, row = q >> 3, c = q & 7;
-        const int gr = min(m0 + row, g.M - 1);
-        a_src[j] = g.A + (size_t)gr * g.lda + c * 8;
-        a_dst[j] = row * 128 + ((c ^ swz(row)) << 4);
+        const int row = (j * 4 + uw) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ swz(row);
+        a_src[j] = g.A + (size_t)min(m0 + row, g.M - 1) * g.lda + c * 8;
     }
 #pragma unroll
     for (int j = 0; j < W_LOADS; ++j) {
-        const int q = tid + j * 256, row = q >> 3, c = q & 7;
-        const int gr = min(n0 + row, g.N - 1);
-        w_src[j] = g.w_off + ((uint64_t)gr * g.K + c * 8) * 2;
-        w_dst[j] = row * 128 + ((c ^ swz(row)) << 4);
+        const int row = (j * 4 + uw) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ swz(row);
+        w_src[j] = g.w_off + ((uint64_t)min(n0 + row, g.N - 1) * g.K + c * 8) * 2;
     }
 
     floatx16 acc[NT][MT];
@@ -79,29 +87,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    uint4 ra[A_LOADS], rw[W_LOADS];
-    auto load_slab = [&](int kt) {
+    auto issue_slab = [&](int kt, int buf) {
         const int k0 = kt * BK;
+        char* dA = sA + buf * BM * 128 + uw * 1024;
+        char* dW = sW + buf * BN * 128 + uw * 1024;
 #pragma unroll
-        for (int j = 0; j < A_LOADS; ++j) ra[j] = *(const uint4*)(a_src[j] + k0);
+        for (int j = 0; j < A_LOADS; ++j) lds_load16(a_src[j] + k0, dA + j * 4096);
 #pragma unroll
-        for (int j = 0; j < W_LOADS; ++j) rw[j] = *(const uint4*)wv_ptr(g.W, w_src[j] + (uint64_t)k0 * 2);
-    };
-    auto store_slab = [&](int buf) {
-#pragma unroll
-        for (int j = 0; j < A_LOADS; ++j) *(uint4*)(sA + buf * BM * 128 + a_dst[j]) = ra[j];
-#pragma unroll
-        for (int j = 0; j < W_LOADS; ++j) *(uint4*)(sW + buf * BN * 128 + w_dst[j]) = rw[j];
+        for (int j = 0; j < W_LOADS; ++j) lds_load16(wv_ptr(g.W, w_src[j] + (uint64_t)k0 * 2), dW + j * 4096);
     };
 
     const int KT = g.K / BK;
-    load_slab(0);
-    store_slab(0);
-    __syncthreads();
+    issue_slab(0, 0);
+    __syncthreads();                     // (the compiler waits for the LDS-DMA before the barrier)
 
     for (int kt = 0; kt < KT; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < KT) load_slab(kt + 1);
+        if (kt + 1 < KT) issue_slab(kt + 1, buf ^ 1);
         const char* cA = sA + buf * BM * 128;
         const char* cW = sW + buf * BN * 128;
 #pragma unroll
@@ -124,8 +126,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                 for (int j = 0; j < MT; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < KT) store_slab(buf ^ 1);
-        __syncthreads();
+        __syncthreads();                 // slab kt+1 has landed and slab kt is free to overwrite
     }
 
     // ---- epilogue: lane = token row li, register quad = 4 consecutive features
