@@ -49,9 +49,9 @@ def build_library(verbose: bool = True) -> str:
         out, _ = p.communicate()
         lines = out.splitlines()
         usage = _resource_usage(lines)
-        out = "\n".join(l for l in lines if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l)
+        out = "\n".join(l for l in lines if "warning:" in l or "error:" in l)
         if p.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+            raise RuntimeError(f"hipcc failed on {src}:\n" + "\n".join(lines))
         for kname, u in usage.items():
             # a kernel that touches scratch memory has lost its register arrays: treat as a build error
             if u.get("ScratchSize [bytes/lane]", 0) or u.get("VGPRs Spill", 0):

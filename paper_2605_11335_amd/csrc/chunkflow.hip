@@ -312,11 +312,13 @@ hipEvent_t prof_event(cf_ctx* c) {
     return e;
 }
 
+// kid + K_COUNT * variant; variant 1 = the 128x128-tile instantiation of a GEMM
 struct ProfScope {
     cf_ctx* c; hipStream_t s; ProfEntry pe; bool on;
-    ProfScope(cf_ctx* c_, hipStream_t s_, int kid, double flops, double bytes) : c(c_), s(s_), on(c_->profiling) {
+    ProfScope(cf_ctx* c_, hipStream_t s_, int kid, double flops, double bytes, int variant = 0)
+        : c(c_), s(s_), on(c_->profiling) {
         if (!on) return;
-        pe = ProfEntry{kid, prof_event(c), prof_event(c), flops, bytes};
+        pe = ProfEntry{kid + K_COUNT * variant, prof_event(c), prof_event(c), flops, bytes};
         (void)hipEventRecord(pe.a, s);
     }
     ~ProfScope() {
@@ -330,10 +332,12 @@ int prof_resolve(cf_ctx* c) {
     if (c->prof_pending.empty()) return CF_OK;
     CF_HIP(c, hipDeviceSynchronize());
     if (c->ktimes.empty()) {
-        c->ktimes.resize(K_COUNT);
-        for (int i = 0; i < K_COUNT; ++i) {
+        c->ktimes.resize(2 * K_COUNT);
+        for (int i = 0; i < 2 * K_COUNT; ++i) {
             memset(&c->ktimes[i], 0, sizeof(cf_kernel_time));
-            snprintf(c->ktimes[i].name, sizeof c->ktimes[i].name, "%s", kKidName[i]);
+            const bool gemm = strncmp(kKidName[i % K_COUNT], "gemm_", 5) == 0;
+            snprintf(c->ktimes[i].name, sizeof c->ktimes[i].name, "%s%s", kKidName[i % K_COUNT],
+                     gemm ? (i < K_COUNT ? "/256x256" : "/128x128") : "");
         }
     }
     for (auto& pe : c->prof_pending) {
@@ -434,12 +438,13 @@ int run_linear(Fwd& F, int kid, const std::string& wname, const std::string& bna
     g.has_bias = 1;
     g.N = (int)w.rows;
     g.K = (int)w.cols;
+    if (g.epi == EPI_SPLIT_GELU && g.n_split > g.N) g.n_split = g.N;
     return panels(F, w, 256, [&](int r0, int r1) -> int {
         GemmArgs p = g;
         p.n0 = r0;
         p.n1 = r1;
         if (const char* msg = gemm_check(p)) return fail(F.c, CF_ERR_ARG, "%s (%s)", msg, wname.c_str());
-        ProfScope ps(F.c, F.s, kid, 2.0 * p.M * (r1 - r0) * p.K, 0);
+        ProfScope ps(F.c, F.s, kid, 2.0 * p.M * (r1 - r0) * p.K, 0, gemm_tile(p) == 256 ? 0 : 1);
         CF_HIP(F.c, gemm_launch(p, F.s));
         return CF_OK;
     });
@@ -1023,8 +1028,119 @@ int cf_comm_end_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute) {
     return CF_OK;
 }
 
-int fwd_dit(Fwd& F) { return fail(F.c, CF_ERR_UNSUPPORTED, "DiT block forward not built yet"); }
-int fwd_double(Fwd& F) { return fail(F.c, CF_ERR_UNSUPPORTED, "double-stream block forward not built yet"); }
+TokenMap identity_map(int rows) { return TokenMap{rows, rows, 0, rows, rows, 0}; }
+
+GemmArgs plain_linear(const bf16* A, int lda, int M, bf16* out, int ld) {
+    GemmArgs g{};
+    g.A = A; g.lda = lda; g.M = M; g.epi = EPI_SPLIT_GELU;
+    g.out0 = out; g.ld0 = ld; g.n_split = 1 << 30;      // clamped to N below: no GELU half
+    return g;
+}
+GemmArgs gelu_linear(const bf16* A, int lda, int M, bf16* out, int ld) {
+    GemmArgs g{};
+    g.A = A; g.lda = lda; g.M = M; g.epi = EPI_SPLIT_GELU;
+    g.n_split = 0; g.out1 = out; g.ld1 = ld; g.col1_off = 0;
+    return g;
+}
+GemmArgs resid_linear(const bf16* A, int lda, int M, const float* resid, const float* gate, float* y, int ld) {
+    GemmArgs g{};
+    g.A = A; g.lda = lda; g.M = M; g.epi = EPI_GATE_RESID;
+    g.resid = resid; g.gate = gate; g.y = y; g.ldy = ld;
+    return g;
+}
+
+// ---- DiT block (App. B): modulated self-attention, cross-attention to the text context
+// (affine pre-norm, no gate, text K/V computed by every rank), modulated FFN
+int fwd_dit(Fwd& F) {
+    cf_ctx* c = F.c;
+    const cf_model_desc& m = c->d;
+    const int d = m.d, f = m.f, nl = m.n_total / m.sp_degree, H = m.n_heads, hd = m.head_dim, lc = m.l_ctx;
+    const cf_block_io* io = F.io;
+    Ws& w = F.ws;
+    CF_TRY(run_modvec(F, "w_mod", "b_mod", io->temb, w.mod));
+    const float *sh1 = w.mod, *sc1 = w.mod + d, *g1 = w.mod + 2 * d, *sh2 = w.mod + 3 * d, *sc2 = w.mod + 4 * d,
+                *g2 = w.mod + 5 * d;
+    // self-attention
+    CF_TRY(run_ln_mod(F, io->x, sh1, sc1, w.xn, nl));
+    if (m.qk_rmsnorm) { CF_TRY(need(F, T(c, "q_norm"))); CF_TRY(need(F, T(c, "k_norm"))); }
+    CF_TRY(run_linear(F, K_QKV, "w_qkv", "b_qkv", plain_linear(w.xn, d, nl, w.qkv, 3 * d)));
+    RelayoutArgs r = relayout_for(F, w.qkv, nl, 0, "q_norm", "k_norm");
+    CF_TRY(run_joint_attention(F, &r, 1, w.c, d));
+    CF_TRY(run_linear(F, K_OUT, "w_o", "b_o", resid_linear(w.c, d, nl, io->x, g1, w.x1, d)));
+    // cross-attention: queries from the local tokens (all heads), keys/values from the context
+    CF_TRY(need(F, T(c, "ln_c_w")));
+    CF_TRY(need(F, T(c, "ln_c_b")));
+    {
+        ProfScope ps(c, F.s, K_LN, 0, 6.0 * nl * d);
+        CF_HIP(c, ln_affine_launch(w.x1, F.W, T(c, "ln_c_w").off, T(c, "ln_c_b").off, w.xn, nl, d, F.s));
+    }
+    if (m.qk_rmsnorm) { CF_TRY(need(F, T(c, "cq_norm"))); CF_TRY(need(F, T(c, "ck_norm"))); }
+    CF_TRY(run_linear(F, K_CROSS_Q, "w_cq", "b_cq", plain_linear(w.xn, d, nl, w.qkv, d)));
+    CF_TRY(run_linear(F, K_CROSS_KV, "w_ckv", "b_ckv", plain_linear((const bf16*)io->ctx, d, lc, w.ckv, 2 * d)));
+    {
+        RelayoutArgs rq{};
+        rq.src = w.qkv; rq.ld = d; rq.rows = nl; rq.col_q = 0; rq.col_k = -1; rq.col_v = -1;
+        rq.n_heads = H; rq.h0 = 0; rq.h_local = H; rq.hd = hd; rq.W = F.W; rq.has_norm = m.qk_rmsnorm;
+        if (m.qk_rmsnorm) { rq.qn_off = T(c, "cq_norm").off; rq.kn_off = T(c, "ck_norm").off; }
+        rq.map = identity_map(nl); rq.row0 = 0; rq.Q = w.cQ; rq.K = nullptr; rq.Vt = nullptr; rq.n_pad = 0;
+        RelayoutArgs rk = rq;
+        rk.src = w.ckv; rk.ld = 2 * d; rk.rows = lc; rk.col_q = -1; rk.col_k = 0; rk.col_v = d;
+        rk.map = identity_map(lc); rk.Q = nullptr; rk.K = w.cK; rk.Vt = w.cVt; rk.n_pad = n_pad_of(lc);
+        ProfScope ps(c, F.s, K_RELAYOUT, 0, 2.0 * 2 * ((double)nl * d + 2.0 * lc * d));
+        CF_HIP(c, relayout_launch(rq, F.s));
+        CF_HIP(c, relayout_launch(rk, F.s));
+    }
+    {
+        AttnArgs a{};
+        a.Q = w.cQ; a.K = w.cK; a.Vt = w.cVt; a.O = w.c; a.o_hs = hd; a.o_qs = d;
+        a.H = H; a.nq = nl; a.nk = lc; a.nk_pad = n_pad_of(lc); a.hd = hd; a.scale = 1.0f / sqrtf((float)hd);
+        if (const char* msg = attn_check(a)) return fail(c, CF_ERR_ARG, "%s", msg);
+        ProfScope ps(c, F.s, K_CROSS_ATTN, 4.0 * H * (double)nl * lc * hd, 0);
+        CF_HIP(c, attn_launch(a, F.s));
+    }
+    CF_TRY(run_linear(F, K_CROSS_OUT, "w_co", "b_co", resid_linear(w.c, d, nl, w.x1, nullptr, w.x2, d)));
+    // FFN
+    CF_TRY(run_ln_mod(F, w.x2, sh2, sc2, w.xn, nl));
+    CF_TRY(run_linear(F, K_UP, "w_up", "b_up", gelu_linear(w.xn, d, nl, w.up, f)));
+    return run_linear(F, K_DOWN, "w_down", "b_down", resid_linear(w.up, f, nl, w.x2, g2, io->y, d));
+}
+
+// ---- MM-DiT double-stream block (App. B): per-stream weights, joint attention over the
+// concatenation (text rows, then image rows).  Local rows: this rank's text rows, then image rows.
+int fwd_double(Fwd& F) {
+    cf_ctx* c = F.c;
+    const cf_model_desc& m = c->d;
+    const int d = m.d, f = m.f, nl = m.n_total / m.sp_degree, tl = m.n_txt_total / m.sp_degree;
+    const cf_block_io* io = F.io;
+    Ws& w = F.ws;
+    static const char* st[2] = {"txt", "img"};
+    auto nm = [](const char* s, const char* t) { return std::string(s) + "_" + t; };
+    const int row0[2] = {0, tl}, rows[2] = {tl, nl - tl};
+    const float* xin[2] = {io->x_txt, io->x};
+    float* yout[2] = {io->y_txt, io->y};
+    for (int s = 0; s < 2; ++s) CF_TRY(run_modvec(F, nm(st[s], "w_mod"), nm(st[s], "b_mod"), io->temb, w.mod + 6 * d * s));
+    auto mod = [&](int s, int i) { return w.mod + 6 * d * s + i * d; };
+    for (int s = 0; s < 2; ++s) CF_TRY(run_ln_mod(F, xin[s], mod(s, 0), mod(s, 1), w.xn + (size_t)row0[s] * d, rows[s]));
+    RelayoutArgs parts[2];
+    for (int s = 0; s < 2; ++s) {
+        if (m.qk_rmsnorm) { CF_TRY(need(F, T(c, nm(st[s], "q_norm")))); CF_TRY(need(F, T(c, nm(st[s], "k_norm")))); }
+        CF_TRY(run_linear(F, K_QKV, nm(st[s], "w_qkv"), nm(st[s], "b_qkv"),
+                          plain_linear(w.xn + (size_t)row0[s] * d, d, rows[s], w.qkv + (size_t)row0[s] * 3 * d, 3 * d)));
+        parts[s] = relayout_for(F, w.qkv + (size_t)row0[s] * 3 * d, rows[s], row0[s], nm(st[s], "q_norm"), nm(st[s], "k_norm"));
+    }
+    CF_TRY(run_joint_attention(F, parts, 2, w.c, d));
+    for (int s = 0; s < 2; ++s)
+        CF_TRY(run_linear(F, K_OUT, nm(st[s], "w_o"), nm(st[s], "b_o"),
+                          resid_linear(w.c + (size_t)row0[s] * d, d, rows[s], xin[s], mod(s, 2), w.x1 + (size_t)row0[s] * d, d)));
+    for (int s = 0; s < 2; ++s) {
+        CF_TRY(run_ln_mod(F, w.x1 + (size_t)row0[s] * d, mod(s, 3), mod(s, 4), w.xn + (size_t)row0[s] * d, rows[s]));
+        CF_TRY(run_linear(F, K_UP, nm(st[s], "w_up"), nm(st[s], "b_up"),
+                          gelu_linear(w.xn + (size_t)row0[s] * d, d, rows[s], w.up + (size_t)row0[s] * f, f)));
+        CF_TRY(run_linear(F, K_DOWN, nm(st[s], "w_down"), nm(st[s], "b_down"),
+                          resid_linear(w.up + (size_t)row0[s] * f, f, rows[s], w.x1 + (size_t)row0[s] * d, mod(s, 5), yout[s], d)));
+    }
+    return CF_OK;
+}
 
 }  // namespace
 

@@ -222,10 +222,14 @@ const char* gemm_check(const GemmArgs& g) {
     return nullptr;
 }
 
-hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
+int gemm_tile(const GemmArgs& g) {
     // Small problems take 128x128 tiles so that the grid still covers the chip.
     const long tiles256 = (long)((g.M + 255) / 256) * ((g.n1 - g.n0 + 255) / 256);
-    const bool big = tiles256 >= 128;
+    return tiles256 >= 128 ? 256 : 128;
+}
+
+hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
+    const bool big = gemm_tile(g) == 256;
     if (g.epi == EPI_SPLIT_GELU)
         return big ? launch<256, 256, EPI_SPLIT_GELU>(g, s) : launch<128, 128, EPI_SPLIT_GELU>(g, s);
     return big ? launch<256, 256, EPI_GATE_RESID>(g, s) : launch<128, 128, EPI_GATE_RESID>(g, s);
