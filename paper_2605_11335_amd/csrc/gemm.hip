@@ -11,16 +11,22 @@
 // one token row and 4 consecutive output features per register quad: epilogues then load
 // bias/gate and store results 4 features at a time.  K is consumed in slabs of 64 that are
 // copied global -> LDS directly (no register staging), double-buffered; 16-byte chunks of each
-// 128-byte LDS row are XOR-swizzled so that the fragment reads of 16..32 consecutive rows
-// spread over all banks.
+// 128-byte LDS row are XOR-swizzled so that the fragment reads of consecutive rows spread over
+// all banks.  The k-steps are software-pipelined: LDS fragment reads of step s+1 and the
+// slab hand-over barrier run behind the MFMAs of step s.
 #include "common.h"
 #include "kernels.h"
 
 namespace {
 
 constexpr int BK = 64;                 // K slab (bf16 elements) = 128 bytes per LDS row
+constexpr int STAGES = 2;              // slabs resident in LDS: one being multiplied, one in flight
+constexpr int ROWB = BK * 2;           // bytes per LDS row
 constexpr int CHUNKS = BK / 8;         // 16-byte chunks per LDS row
+constexpr int KSTEPS = BK / 16;        // MFMA k-steps per slab
 
+// slot of chunk c in row `row` is c ^ swz(row): conflict-free for 16-byte fragment reads of
+// consecutive rows on a 32-bank (8 lanes per phase) as well as a 64-bank (16 lanes) LDS
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
 
 // 16 bytes per lane from global memory straight into LDS: lane l's data lands at lds + 16*l
@@ -30,17 +36,29 @@ __device__ __forceinline__ void lds_load16(const void* gptr, void* lds) {
                                      (void __attribute__((address_space(3)))*)lds, 16, 0, 0);
 }
 
+// Slab hand-over: this wave's global->LDS loads (the next slab) have landed and its LDS reads
+// (the last fragments of the current slab) have returned; after the barrier that holds for the
+// whole workgroup, so the next slab may be read and the current one overwritten.
+__device__ __forceinline__ void slab_handover() {
+#ifndef CF_DBG_NOBARRIER
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+#else
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+#endif
+}
+
 template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     constexpr int WM = BM / 2, WN = BN / 2;        // wave quadrant
     constexpr int MT = WM / 32, NT = WN / 32;      // 32x32 MFMA tiles per wave
     constexpr int A_LOADS = BM * CHUNKS / 256;     // 16-byte global loads per thread per slab
     constexpr int W_LOADS = BN * CHUNKS / 256;
+    constexpr int RPL = 1024 / ROWB;               // LDS rows written by one wave-load
+    constexpr int A_STAGE = BM * ROWB, W_STAGE = BN * ROWB;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    // [2][BM][128 B] activations, then [2][BN][128 B] weights
-    char* const sA = smem;
-    char* const sW = smem + 2 * BM * 128;
+    char* const sA = smem;                         // [STAGES][BM][ROWB] activations
+    char* const sW = smem + STAGES * A_STAGE;      // [STAGES][BN][ROWB] weights
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -61,21 +79,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     const int n0 = g.n0 + tn * BN;
 
     // Slab copies go global -> LDS directly (no register staging).  One such load writes the
-    // wave's 64 x 16 bytes to consecutive LDS addresses, i.e. 8 rows of 128 bytes; which 16-byte
-    // chunk of its row a lane fetches is chosen so that the chunk lands in its swizzled slot.
+    // wave's 64 x 16 bytes to consecutive LDS addresses, i.e. RPL rows; which 16-byte chunk of
+    // its row a lane fetches is chosen so that the chunk lands in its swizzled slot.
     const int uw = __builtin_amdgcn_readfirstlane(wave);
     const bf16* a_src[A_LOADS];
     uint64_t w_src[W_LOADS];
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
-        const int row = (j * 4 + uw) * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ swz(row);
+        const int row = (j * 4 + uw) * RPL + lane / CHUNKS;
+        const int c = (lane % CHUNKS) ^ swz(row);
         a_src[j] = g.A + (size_t)min(m0 + row, g.M - 1) * g.lda + c * 8;
     }
 #pragma unroll
     for (int j = 0; j < W_LOADS; ++j) {
-        const int row = (j * 4 + uw) * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ swz(row);
+        const int row = (j * 4 + uw) * RPL + lane / CHUNKS;
+        const int c = (lane % CHUNKS) ^ swz(row);
         w_src[j] = g.w_off + ((uint64_t)min(n0 + row, g.N - 1) * g.K + c * 8) * 2;
     }
 
@@ -87,95 +105,162 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    auto issue_slab = [&](int kt, int buf) {
-        const int k0 = kt * BK;
-        char* dA = sA + buf * BM * 128 + uw * 1024;
-        char* dW = sW + buf * BN * 128 + uw * 1024;
+    // LDS byte offsets of this lane's fragment rows (row*ROWB) and their swizzle keys
+    int a_off[MT], a_key[MT], w_off[NT], w_key[NT];
 #pragma unroll
-        for (int j = 0; j < A_LOADS; ++j) lds_load16(a_src[j] + k0, dA + j * 4096);
+    for (int j = 0; j < MT; ++j) { const int row = wm0 + j * 32 + li; a_off[j] = row * ROWB; a_key[j] = swz(row); }
 #pragma unroll
-        for (int j = 0; j < W_LOADS; ++j) lds_load16(wv_ptr(g.W, w_src[j] + (uint64_t)k0 * 2), dW + j * 4096);
-    };
+    for (int i = 0; i < NT; ++i) { const int row = wn0 + i * 32 + li; w_off[i] = row * ROWB; w_key[i] = swz(row); }
+
+#define CF_ISSUE_SLAB(KT_)                                                                              \
+    do {                                                                                                \
+        const int k0_ = (KT_) * BK, st_ = (KT_) & 1;                                                    \
+        char* dA_ = sA + st_ * A_STAGE + uw * 1024;                                                     \
+        char* dW_ = sW + st_ * W_STAGE + uw * 1024;                                                     \
+        _Pragma("unroll") for (int j = 0; j < A_LOADS; ++j) lds_load16(a_src[j] + k0_, dA_ + j * 4096); \
+        _Pragma("unroll") for (int j = 0; j < W_LOADS; ++j)                                             \
+            lds_load16(wv_ptr(g.W, w_src[j] + (uint64_t)k0_ * 2), dW_ + j * 4096);                      \
+    } while (0)
+#define CF_LOAD_FRAGS(BUF_, CA_, CW_, KK_)                                                              \
+    do {                                                                                                \
+        const int c_ = (KK_) * 2 + lg;                                                                  \
+        _Pragma("unroll") for (int j = 0; j < MT; ++j)                                                  \
+            fa[BUF_][j] = *(const bf16x8*)((CA_) + a_off[j] + ((c_ ^ a_key[j]) << 4));                  \
+        _Pragma("unroll") for (int i = 0; i < NT; ++i)                                                  \
+            fw[BUF_][i] = *(const bf16x8*)((CW_) + w_off[i] + ((c_ ^ w_key[i]) << 4));                  \
+    } while (0)
 
     const int KT = g.K / BK;
-    issue_slab(0, 0);
-    __syncthreads();                     // (the compiler waits for the LDS-DMA before the barrier)
+    bf16x8 fa[2][MT], fw[2][NT];
+    CF_ISSUE_SLAB(0);
+    slab_handover();
+    if (KT > 1) CF_ISSUE_SLAB(1);
+    CF_LOAD_FRAGS(0, sA, sW, 0);
 
+    // Software pipeline over k-steps of 16: the fragments of step s+1 are read from LDS while the
+    // MFMAs of step s run; the hand-over to the next slab sits before the last step of a slab, so
+    // its barrier and the first fragment reads of the next slab hide behind that step's MFMAs.
     for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) issue_slab(kt + 1, buf ^ 1);
-        const char* cA = sA + buf * BM * 128;
-        const char* cW = sW + buf * BN * 128;
+        const char* cA = sA + (kt & 1) * A_STAGE;
+        const char* cW = sW + (kt & 1) * W_STAGE;
+        const char* nA = sA + ((kt + 1) & 1) * A_STAGE;
+        const char* nW = sW + ((kt + 1) & 1) * W_STAGE;
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 fa[MT], fw[NT];
-            const int c = kk * 2 + lg;
-#pragma unroll
-            for (int j = 0; j < MT; ++j) {
-                const int row = wm0 + j * 32 + li;
-                fa[j] = *(const bf16x8*)(cA + row * 128 + ((c ^ swz(row)) << 4));
-            }
-#pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                const int row = wn0 + i * 32 + li;
-                fw[i] = *(const bf16x8*)(cW + row * 128 + ((c ^ swz(row)) << 4));
+        for (int kk = 0; kk < KSTEPS; ++kk) {
+            const int cur = kk & 1, nxt = cur ^ 1;
+#ifdef CF_DBG_NOFRAG
+            if (false) {
+#else
+            if (kk + 1 < KSTEPS) {
+                CF_LOAD_FRAGS(nxt, cA, cW, kk + 1);
+#endif
+            } else if (kt + 1 < KT) {
+                slab_handover();                       // slab kt+1 landed; slab kt fully read
+#ifndef CF_DBG_NOLOAD
+                if (kt + 2 < KT) CF_ISSUE_SLAB(kt + 2);
+#endif
+#ifndef CF_DBG_NOFRAG
+                CF_LOAD_FRAGS(nxt, nA, nW, 0);
+#endif
             }
 #pragma unroll
             for (int i = 0; i < NT; ++i)
 #pragma unroll
                 for (int j = 0; j < MT; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[i], fa[j], acc[i][j], 0, 0, 0);
+#ifndef CF_DBG_NOMFMA
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][i], fa[cur][j], acc[i][j], 0, 0, 0);
+#else
+                    acc[i][j][0] += (float)fw[cur][i][0] * (float)fa[cur][j][0];
+#endif
+            // interleave: one LDS fragment read behind each of the first MFMAs of the step
+#pragma unroll
+            for (int q = 0; q < MT + NT; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT), 0);
         }
-        __syncthreads();                 // slab kt+1 has landed and slab kt is free to overwrite
     }
+#undef CF_ISSUE_SLAB
+#undef CF_LOAD_FRAGS
 
-    // ---- epilogue: lane = token row li, register quad = 4 consecutive features
+    // ---- epilogue.  In the accumulators a lane owns one token row and 4 consecutive features per
+    // register quad.  Bias / GELU / gate are applied there, then each wave transposes its quadrant
+    // through its own slice of LDS so that global stores are 16 bytes per lane with 16 (or 8)
+    // consecutive lanes covering one contiguous row segment.
+    constexpr bool OUT_BF16 = (EPI == EPI_SPLIT_GELU);
+    constexpr int PASSES = OUT_BF16 ? 1 : 2;               // fp32 rows are staged in two column halves
+    constexpr int NTP = NT / PASSES;                       // 32-column tiles per pass
+    constexpr int ELT = OUT_BF16 ? 2 : 4;
+    constexpr int RB = NTP * 32 * ELT;                     // staged row bytes (= WN * 2 either way)
+    constexpr int PITCH = RB + (OUT_BF16 ? 16 : 32);       // padded: conflict-free quad writes
+    constexpr int CPR = RB / 16, RPI = 64 / CPR;           // 16-byte chunks per row, rows per store
+    static_assert(4 * WM * PITCH <= 160 * 1024, "staging exceeds LDS");
+    slab_handover();                                       // every wave is done reading the slabs
+    char* const stg = smem + wave * (WM * PITCH);
 #pragma unroll
-    for (int i = 0; i < NT; ++i) {
+    for (int p = 0; p < PASSES; ++p) {
 #pragma unroll
-        for (int vb = 0; vb < 4; ++vb) {
-            const int n = n0 + wn0 + i * 32 + vb * 8 + lg * 4;
-            if (n >= g.n1) continue;                 // N and panel ends are multiples of 8
-            float b[4] = {0.f, 0.f, 0.f, 0.f};
-            if (g.has_bias) {
-                const uint2 bb = *(const uint2*)wv_ptr(g.W, g.bias_off + 2ull * n);
-                b[0] = __uint_as_float(bb.x << 16);
-                b[1] = __uint_as_float(bb.x & 0xffff0000u);
-                b[2] = __uint_as_float(bb.y << 16);
-                b[3] = __uint_as_float(bb.y & 0xffff0000u);
-            }
-            float gt[4] = {1.f, 1.f, 1.f, 1.f};
-            if (EPI == EPI_GATE_RESID && g.gate) {
-                const float4 t = *(const float4*)(g.gate + n);
-                gt[0] = t.x; gt[1] = t.y; gt[2] = t.z; gt[3] = t.w;
-            }
+        for (int ii = 0; ii < NTP; ++ii) {
+            const int i = p * NTP + ii;
 #pragma unroll
-            for (int j = 0; j < MT; ++j) {
-                const int m = m0 + wm0 + j * 32 + li;
-                if (m >= g.M) continue;
-                float v[4];
+            for (int vb = 0; vb < 4; ++vb) {
+                const int n = min(n0 + wn0 + i * 32 + vb * 8 + lg * 4, g.N - 4);
+                float b[4] = {0.f, 0.f, 0.f, 0.f};
+                if (g.has_bias) {
+                    const uint2 bb = *(const uint2*)wv_ptr(g.W, g.bias_off + 2ull * n);
+                    b[0] = __uint_as_float(bb.x << 16);
+                    b[1] = __uint_as_float(bb.x & 0xffff0000u);
+                    b[2] = __uint_as_float(bb.y << 16);
+                    b[3] = __uint_as_float(bb.y & 0xffff0000u);
+                }
+                float gt[4] = {1.f, 1.f, 1.f, 1.f};
+                if (!OUT_BF16 && g.gate) {
+                    const float4 t = *(const float4*)(g.gate + n);
+                    gt[0] = t.x; gt[1] = t.y; gt[2] = t.z; gt[3] = t.w;
+                }
+                const bool act = OUT_BF16 && n >= g.n_split;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = acc[i][j][vb * 4 + e] + b[e];
-                if (EPI == EPI_SPLIT_GELU) {
-                    bf16* dst;
-                    if (n < g.n_split) {
-                        dst = g.out0 + (size_t)m * g.ld0 + n;
+                for (int j = 0; j < MT; ++j) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][vb * 4 + e] + b[e];
+                    char* dst = stg + (j * 32 + li) * PITCH + (ii * 32 + vb * 8 + lg * 4) * ELT;
+                    if (OUT_BF16) {
+                        if (act) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f32(v[e]);
+                        }
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+                        *(bf16x4*)dst = o;
                     } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f32(v[e]);
-                        dst = g.out1 + (size_t)m * g.ld1 + g.col1_off + (n - g.n_split);
+                        float4 o;
+                        o.x = gt[0] * v[0]; o.y = gt[1] * v[1]; o.z = gt[2] * v[2]; o.w = gt[3] * v[3];
+                        *(float4*)dst = o;
                     }
-                    bf16x4 o;
+                }
+            }
+        }
+        // coalesced write-out of this pass
+        const int col = (lane % CPR) * (16 / ELT);                         // first column of the lane's chunk
+        const int n = n0 + wn0 + p * (NTP * 32) + col;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-                    *(bf16x4*)dst = o;
+        for (int r = 0; r < WM / RPI; ++r) {
+            const int row = r * RPI + lane / CPR;
+            const int m = m0 + wm0 + row;
+            const uint4 val = *(const uint4*)(stg + row * PITCH + (lane % CPR) * 16);
+            if (m < g.M && n < g.n1) {
+                if (OUT_BF16) {
+                    bf16* dst = n < g.n_split ? g.out0 + (size_t)m * g.ld0 + n
+                                              : g.out1 + (size_t)m * g.ld1 + g.col1_off + (n - g.n_split);
+                    *(uint4*)dst = val;
                 } else {
-                    const float4 r = *(const float4*)(g.resid + (size_t)m * g.ldy + n);
+                    const float4 rr = *(const float4*)(g.resid + (size_t)m * g.ldy + n);
                     float4 o;
-                    o.x = r.x + gt[0] * v[0];
-                    o.y = r.y + gt[1] * v[1];
-                    o.z = r.z + gt[2] * v[2];
-                    o.w = r.w + gt[3] * v[3];
+                    o.x = rr.x + __uint_as_float(val.x); o.y = rr.y + __uint_as_float(val.y);
+                    o.z = rr.z + __uint_as_float(val.z); o.w = rr.w + __uint_as_float(val.w);
                     *(float4*)(g.y + (size_t)m * g.ldy + n) = o;
                 }
             }
@@ -187,7 +272,9 @@ template <int BM, int BN, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s) {
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.n1 - g.n0 + BN - 1) / BN;
-    const size_t smem = 2 * (BM + BN) * 128;
+    const size_t stage_bytes = (size_t)STAGES * (BM + BN) * ROWB;
+    const size_t epi_bytes = 4ull * (BM / 2) * (BN + (EPI == EPI_SPLIT_GELU ? 16 : 32));   // 4 x WM x PITCH
+    const size_t smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<BM, BN, EPI>,
@@ -203,7 +290,7 @@ hipError_t launch(const GemmArgs& g, hipStream_t s) {
 
 const char* gemm_check(const GemmArgs& g) {
     if (g.M <= 0 || g.N <= 0 || g.K <= 0) return "gemm: empty shape";
-    if (g.K % BK) return "gemm: K must be a multiple of 64";
+    if (g.K % 64) return "gemm: K must be a multiple of 64";
     if (g.N % 8) return "gemm: N must be a multiple of 8";
     if (g.n0 < 0 || g.n1 > g.N || g.n0 >= g.n1 || (g.n0 % 8) || (g.n1 % 8)) return "gemm: bad feature panel";
     if (g.lda < g.K || (g.lda % 8)) return "gemm: lda must be >= K and a multiple of 8";
@@ -211,8 +298,9 @@ const char* gemm_check(const GemmArgs& g) {
     if (((uintptr_t)g.A) % 16) return "gemm: A must be 16-byte aligned";
     if (g.epi == EPI_SPLIT_GELU) {
         if (g.n_split % 8) return "gemm: n_split must be a multiple of 8";
-        if (g.n_split > 0 && (!g.out0 || (g.ld0 % 4) || ((uintptr_t)g.out0 % 8))) return "gemm: bad out0";
-        if (g.n_split < g.N && (!g.out1 || (g.ld1 % 4) || (g.col1_off % 4) || ((uintptr_t)g.out1 % 8))) return "gemm: bad out1";
+        if (g.n_split > 0 && (!g.out0 || (g.ld0 % 8) || ((uintptr_t)g.out0 % 16))) return "gemm: out0 must be 16-byte aligned with ld0 a multiple of 8";
+        if (g.n_split < g.N && (!g.out1 || (g.ld1 % 8) || (g.col1_off % 8) || ((uintptr_t)g.out1 % 16)))
+            return "gemm: out1 must be 16-byte aligned with ld1 and col1_off multiples of 8";
     } else if (g.epi == EPI_GATE_RESID) {
         if (!g.resid || !g.y || (g.ldy % 4) || ((uintptr_t)g.y % 16) || ((uintptr_t)g.resid % 16)) return "gemm: bad residual/output";
         if (g.gate && ((uintptr_t)g.gate % 16)) return "gemm: gate must be 16-byte aligned";

@@ -49,21 +49,21 @@ def test_linear_panels_split_gelu_and_strides():
     buf, w, b, w_off, b_off = make_blob(rng, N, K)
     A, blob = dev_bits(ab), torch.from_numpy(buf).to(DEV)
     out0 = torch.zeros((M, n_split), dtype=torch.int16, device=DEV)
-    ld1 = 100 + (N - n_split)
+    ld1 = 104 + (N - n_split)
     out1 = torch.zeros((M, ld1), dtype=torch.int16, device=DEV)
-    out1_view = out1[:, 100:]
+    out1_view = out1[:, 104:]
     for n0, n1 in [(0, 256), (256, 768), (768, 1024)]:
         B.cf_op_linear(A, blob, w_off, b_off, M, N, K, out0, out1_view, n_split=n_split, n0=n0, n1=n1, lda=lda,
                        ld0=n_split, ld1=ld1)
     torch.cuda.synchronize()
     z = a.astype(np.float64) @ w.T + b
     assert_bf16_close(host_bits(out0), z[:, :n_split], extra_abs=1e-4)
-    assert_bf16_close(host_bits(out1)[:, 100:], ob.gelu_tanh(z[:, n_split:]), extra_abs=2e-4)
-    assert (host_bits(out1)[:, :100] == 0).all()
+    assert_bf16_close(host_bits(out1)[:, 104:], ob.gelu_tanh(z[:, n_split:]), extra_abs=2e-4)
+    assert (host_bits(out1)[:, :104] == 0).all()
     # panel decomposition does not change a single bit
     whole = torch.zeros_like(out0)
     whole1 = torch.zeros_like(out1)
-    B.cf_op_linear(A, blob, w_off, b_off, M, N, K, whole, whole1[:, 100:], n_split=n_split, lda=lda, ld0=n_split, ld1=ld1)
+    B.cf_op_linear(A, blob, w_off, b_off, M, N, K, whole, whole1[:, 104:], n_split=n_split, lda=lda, ld0=n_split, ld1=ld1)
     torch.cuda.synchronize()
     assert torch.equal(whole, out0) and torch.equal(whole1, out1)
 
