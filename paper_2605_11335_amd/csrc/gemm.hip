@@ -14,6 +14,8 @@
 // 128-byte LDS row are XOR-swizzled so that the fragment reads of consecutive rows spread over
 // all banks.  The k-steps are software-pipelined: LDS fragment reads of step s+1 and the
 // slab hand-over barrier run behind the MFMAs of step s.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -82,20 +84,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // wave's 64 x 16 bytes to consecutive LDS addresses, i.e. RPL rows; which 16-byte chunk of
     // its row a lane fetches is chosen so that the chunk lands in its swizzled slot.
     const int uw = __builtin_amdgcn_readfirstlane(wave);
-    const bf16* a_src[A_LOADS];
-    uint64_t w_src[W_LOADS];
+    const char* a_ptr[A_LOADS];
+    const char* w_ptr[W_LOADS];      // fast path: the row's bytes all live in one buffer
+    uint64_t w_src[W_LOADS];         // blob offsets, for the tile that holds the resident/streamed split
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
         const int row = (j * 4 + uw) * RPL + lane / CHUNKS;
         const int c = (lane % CHUNKS) ^ swz(row);
-        a_src[j] = g.A + (size_t)min(m0 + row, g.M - 1) * g.lda + c * 8;
+        a_ptr[j] = (const char*)(g.A + (size_t)min(m0 + row, g.M - 1) * g.lda + c * 8);
     }
 #pragma unroll
     for (int j = 0; j < W_LOADS; ++j) {
         const int row = (j * 4 + uw) * RPL + lane / CHUNKS;
         const int c = (lane % CHUNKS) ^ swz(row);
         w_src[j] = g.w_off + ((uint64_t)min(n0 + row, g.N - 1) * g.K + c * 8) * 2;
+        w_ptr[j] = wv_ptr(g.W, w_src[j]);
     }
+    // does the byte where the blob switches buffers fall inside this tile's weight rows?
+    const uint64_t t_begin = g.w_off + (uint64_t)n0 * g.K * 2, t_end = g.w_off + (uint64_t)min(n0 + BN, g.N) * g.K * 2;
+    const bool straddle = g.W.split > t_begin && g.W.split < t_end;
 
     floatx16 acc[NT][MT];
 #pragma unroll
@@ -112,35 +119,42 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < NT; ++i) { const int row = wn0 + i * 32 + li; w_off[i] = row * ROWB; w_key[i] = swz(row); }
 
-#define CF_ISSUE_SLAB(KT_)                                                                              \
-    do {                                                                                                \
-        const int k0_ = (KT_) * BK, st_ = (KT_) & 1;                                                    \
-        char* dA_ = sA + st_ * A_STAGE + uw * 1024;                                                     \
-        char* dW_ = sW + st_ * W_STAGE + uw * 1024;                                                     \
-        _Pragma("unroll") for (int j = 0; j < A_LOADS; ++j) lds_load16(a_src[j] + k0_, dA_ + j * 4096); \
-        _Pragma("unroll") for (int j = 0; j < W_LOADS; ++j)                                             \
-            lds_load16(wv_ptr(g.W, w_src[j] + (uint64_t)k0_ * 2), dW_ + j * 4096);                      \
-    } while (0)
-#define CF_LOAD_FRAGS(BUF_, CA_, CW_, KK_)                                                              \
-    do {                                                                                                \
-        const int c_ = (KK_) * 2 + lg;                                                                  \
-        _Pragma("unroll") for (int j = 0; j < MT; ++j)                                                  \
-            fa[BUF_][j] = *(const bf16x8*)((CA_) + a_off[j] + ((c_ ^ a_key[j]) << 4));                  \
-        _Pragma("unroll") for (int i = 0; i < NT; ++i)                                                  \
-            fw[BUF_][i] = *(const bf16x8*)((CW_) + w_off[i] + ((c_ ^ w_key[i]) << 4));                  \
-    } while (0)
-
     const int KT = g.K / BK;
     bf16x8 fa[2][MT], fw[2][NT];
-    CF_ISSUE_SLAB(0);
-    slab_handover();
-    if (KT > 1) CF_ISSUE_SLAB(1);
-    CF_LOAD_FRAGS(0, sA, sW, 0);
 
-    // Software pipeline over k-steps of 16: the fragments of step s+1 are read from LDS while the
-    // MFMAs of step s run; the hand-over to the next slab sits before the last step of a slab, so
-    // its barrier and the first fragment reads of the next slab hide behind that step's MFMAs.
-    for (int kt = 0; kt < KT; ++kt) {
+    // slab kt_ -> stage kt_&1
+    auto issue_slab = [&](auto slow, int kt_) {
+        const int k0 = kt_ * BK * 2, st = kt_ & 1;
+        char* dA = sA + st * A_STAGE + uw * 1024;
+        char* dW = sW + st * W_STAGE + uw * 1024;
+#pragma unroll
+        for (int j = 0; j < A_LOADS; ++j) lds_load16(a_ptr[j] + k0, dA + j * 4096);
+#pragma unroll
+        for (int j = 0; j < W_LOADS; ++j)
+            lds_load16(decltype(slow)::value ? wv_ptr(g.W, w_src[j] + k0) : w_ptr[j] + k0, dW + j * 4096);
+    };
+    auto issue_one = [&](auto slow, int kt_, int q) {        // q-th load of slab kt_ (A loads first)
+        const int k0 = kt_ * BK * 2, st = kt_ & 1;
+        if (q < A_LOADS) {
+            lds_load16(a_ptr[q] + k0, sA + st * A_STAGE + uw * 1024 + q * 4096);
+        } else if (q < A_LOADS + W_LOADS) {
+            const int j = q - A_LOADS;
+            lds_load16(decltype(slow)::value ? wv_ptr(g.W, w_src[j] + k0) : w_ptr[j] + k0,
+                       sW + st * W_STAGE + uw * 1024 + j * 4096);
+        }
+    };
+    auto load_frags = [&](int buf, const char* cA, const char* cW, int kk) {
+        const int c = kk * 2 + lg;
+#pragma unroll
+        for (int j = 0; j < MT; ++j) fa[buf][j] = *(const bf16x8*)(cA + a_off[j] + ((c ^ a_key[j]) << 4));
+#pragma unroll
+        for (int i = 0; i < NT; ++i) fw[buf][i] = *(const bf16x8*)(cW + w_off[i] + ((c ^ w_key[i]) << 4));
+    };
+    // One slab = KSTEPS k-steps, software-pipelined: the fragments of step s+1 are read from LDS
+    // while the MFMAs of step s run.  The hand-over to the next slab sits before the slab's last
+    // step: its barrier, the first fragment reads of the next slab and the issue of the slab after
+    // that all hide behind that step's MFMAs.
+    auto slab = [&](auto slow, auto handover, auto issue, int kt) {
         const char* cA = sA + (kt & 1) * A_STAGE;
         const char* cW = sW + (kt & 1) * W_STAGE;
         const char* nA = sA + ((kt + 1) & 1) * A_STAGE;
@@ -148,41 +162,58 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
             const int cur = kk & 1, nxt = cur ^ 1;
-#ifdef CF_DBG_NOFRAG
-            if (false) {
-#else
-            if (kk + 1 < KSTEPS) {
-                CF_LOAD_FRAGS(nxt, cA, cW, kk + 1);
-#endif
-            } else if (kt + 1 < KT) {
+            const bool last = kk + 1 == KSTEPS;
+            if (!last) {
+                load_frags(nxt, cA, cW, kk + 1);
+            } else if (decltype(handover)::value) {
+                __builtin_amdgcn_sched_barrier(0);     // keep the previous step's MFMAs above the barrier
                 slab_handover();                       // slab kt+1 landed; slab kt fully read
-#ifndef CF_DBG_NOLOAD
-                if (kt + 2 < KT) CF_ISSUE_SLAB(kt + 2);
-#endif
-#ifndef CF_DBG_NOFRAG
-                CF_LOAD_FRAGS(nxt, nA, nW, 0);
-#endif
+                __builtin_amdgcn_sched_barrier(0);
+                load_frags(nxt, nA, nW, 0);
             }
+            if (last && decltype(issue)::value) {
+                // the loads of slab kt+2 go out between this step's MFMAs, in this order
+                constexpr int LPM = (A_LOADS + W_LOADS + MT * NT - 1) / (MT * NT);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < NT; ++i)
+                for (int q = 0; q < MT * NT; ++q) {
+                    acc[q / MT][q % MT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][q / MT], fa[cur][q % MT],
+                                                                                  acc[q / MT][q % MT], 0, 0, 0);
 #pragma unroll
-                for (int j = 0; j < MT; ++j)
-#ifndef CF_DBG_NOMFMA
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][i], fa[cur][j], acc[i][j], 0, 0, 0);
-#else
-                    acc[i][j][0] += (float)fw[cur][i][0] * (float)fa[cur][j][0];
-#endif
-            // interleave: one LDS fragment read behind each of the first MFMAs of the step
+                    for (int u = 0; u < LPM; ++u) issue_one(slow, kt + 2, q * LPM + u);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
 #pragma unroll
-            for (int q = 0; q < MT + NT; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                for (int i = 0; i < NT; ++i)
+#pragma unroll
+                    for (int j = 0; j < MT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[cur][i], fa[cur][j], acc[i][j], 0, 0, 0);
+                if (!last || decltype(handover)::value) {
+                    // fragment reads go out two per MFMA at the head of the step
+#pragma unroll
+                    for (int q = 0; q < (MT + NT) / 2; ++q) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT) / 2, 0);
+                }
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, MT * NT - (MT + NT), 0);
         }
-    }
-#undef CF_ISSUE_SLAB
-#undef CF_LOAD_FRAGS
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    auto run = [&](auto slow) {
+        issue_slab(slow, 0);
+        slab_handover();
+        if (KT > 1) issue_slab(slow, 1);
+        load_frags(0, sA, sW, 0);
+        int kt = 0;
+        for (; kt + 2 < KT; ++kt) slab(slow, T_{}, T_{}, kt);
+        if (kt + 1 < KT) { slab(slow, T_{}, F_{}, kt); ++kt; }
+        slab(slow, F_{}, F_{}, kt);
+    };
+    if (straddle) run(T_{}); else run(F_{});
 
     // ---- epilogue.  In the accumulators a lane owns one token row and 4 consecutive features per
     // register quad.  Bias / GELU / gate are applied there, then each wave transposes its quadrant
