@@ -27,6 +27,10 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 PEAK_LINK_GBS = 64.0           # PCIe Gen5 x16, one direction
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# scaled by a copy kernel of known size (see profiles/); None until measured for a workload.
+TRAFFIC = {}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -126,57 +130,71 @@ def main():
 
     set_contention(args.contention)
     total_steps = args.steps + args.warmup
-    # ---- resident arm, unprofiled (reference for the cost of the event pairs)
-    res_plain_ms, _, _ = arm(1.0, args.steps, args.warmup)
-    # every launch from here on (warm-up included, both arms) is timed with a hipEvent pair on
-    # the compute stream, so the per-kernel averages cover exactly what a kernel trace of this
-    # command sees after this point
-    run.ctx.cf_kernel_times_reset()
-    run.ctx.cf_set_profiling(True)
-    res_ms, _, _ = arm(1.0, args.steps, args.warmup)
-    kt_res = run.ctx.cf_kernel_times()
-    off_ms, actual_r, st = arm(args.resident, args.steps, args.warmup)
-    kt_all = run.ctx.cf_kernel_times()
-    run.ctx.cf_set_profiling(False)
-    h2d_per_step = L * (run.blob_bytes - st["resident_bytes"])
-    assert st["h2d_bytes"] == (total_steps * L + 1) * (run.blob_bytes - st["resident_bytes"]), "I/O volume changed"
-    h2d_gbs = h2d_per_step / (off_ms * 1e-3) / 1e9 if off_ms > 0 else 0.0
+    do_res, do_off = args.only in ("both", "resident"), args.only in ("both", "offload")
+    res_ms = off_ms = None
+    kt_res, kt_off, st, actual_r = [], [], None, None
+    if do_res:
+        # resident arm: timed without event pairs, then once more with a hipEvent pair around
+        # every kernel launch on the compute stream (the per-kernel table and the roofline)
+        res_ms, _, _ = arm(1.0, args.steps, args.warmup)
+        run.ctx.cf_kernel_times_reset()
+        run.ctx.cf_set_profiling(True)
+        res_prof_ms, _, _ = arm(1.0, args.steps, args.warmup)
+        kt_res = run.ctx.cf_kernel_times()
+        run.ctx.cf_set_profiling(False)
+    if do_off:
+        off_ms, actual_r, st = arm(args.resident, args.steps, args.warmup)
+        run.ctx.cf_kernel_times_reset()
+        run.ctx.cf_set_profiling(True)
+        off_prof_ms, _, _ = arm(args.resident, args.steps, args.warmup)
+        kt_off = run.ctx.cf_kernel_times()
+        run.ctx.cf_set_profiling(False)
+        h2d_per_step = L * (run.blob_bytes - st["resident_bytes"])
+        assert st["h2d_bytes"] == (total_steps * L + 1) * (run.blob_bytes - st["resident_bytes"]), "I/O volume changed"
+        h2d_gbs = h2d_per_step / (off_ms * 1e-3) / 1e9
+    else:
+        h2d_per_step, h2d_gbs = 0, 0.0
 
     is_mfma = lambda k: k["flops"] > 0 and not k["name"].startswith("modvec")
-    # the resident arm ran (total_steps + 1 drain block) forwards; FLOPs per step from its counters
-    total_flops = sum(k["flops"] for k in kt_res if is_mfma(k)) * L / (total_steps * L + 1)
-    dom = max([k for k in kt_all if is_mfma(k)], key=lambda k: k["total_ms"])
+    kt_main = kt_res if do_res else kt_off
+    arm_name = "resident" if do_res else "offload"
+    # each arm ran total_steps steps plus one drain block: FLOPs per step from the counters
+    total_flops = sum(k["flops"] for k in kt_main if is_mfma(k)) * L / (total_steps * L + 1)
+    dom = max([k for k in kt_main if is_mfma(k)], key=lambda k: k["total_ms"])
     dom_ms = dom["total_ms"] / dom["launches"]
     dom_flops = dom["flops"] / dom["launches"]
+    value = off_ms if do_off else res_ms
 
     result = {
         "metric": "denoise step ms (chunked offload vs resident)",
-        "value": off_ms, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": off_ms, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "value": value, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": value, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {L} blocks, d={cfg.d}, H={cfg.n_heads}x{cfg.head_dim}, f={cfg.f}, "
                                f"N={cfg.n_total}, Ulysses P={cfg.sp_degree} share (GEMMs on {cfg.n_local} tokens, "
                                f"attention {cfg.h_local} heads over {cfg.n_total})",
+                   "arm": "chunked offload" if do_off else "resident",
                    "chunk_bytes": chunk_bytes, "chunks_per_block": run.n_chunks, "blob_bytes": run.blob_bytes,
-                   "resident_fraction": actual_r, "contention": args.contention},
-        "resident_ms": res_ms, "resident_ms_without_event_pairs": res_plain_ms,
-        "offload_over_resident": off_ms / res_ms,
-        "step_tflops_resident": total_flops / (res_ms * 1e-3) / 1e12,
-        "eta_comp_measured": total_flops / (res_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                   "resident_fraction": actual_r if do_off else 1.0, "contention": args.contention},
+        "offload_ms": off_ms, "resident_ms": res_ms,
+        "offload_over_resident": (off_ms / res_ms) if (do_res and do_off) else None,
+        "step_tflops": total_flops / ((res_ms if do_res else off_ms) * 1e-3) / 1e12,
+        "eta_comp_measured": (total_flops / (res_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if do_res else None,
         "h2d_gbs": h2d_gbs, "h2d_frac_link_peak": h2d_gbs / PEAK_LINK_GBS,
         "h2d_bytes_per_step": h2d_per_step,
-        "exposed_prefetch_ms": off_ms - res_ms,
-        "weight_memory_bytes": st["weight_memory_bytes"],
-        "roofline": {"bound": "mfma", "kernel": dom["name"], "achieved": dom_flops / dom_ms / 1e9,
+        "exposed_prefetch_ms": (off_ms - res_ms) if (do_res and do_off) else None,
+        "weight_memory_bytes": st["weight_memory_bytes"] if st else L * run.blob_bytes,
+        "roofline": {"bound": "mfma", "kernel": dom["name"], "arm": arm_name,
+                     "achieved": dom_flops / dom_ms / 1e9,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom_flops / dom_ms / 1e9 / PEAK_BF16_TFLOPS,
                      "avg_launch_ms": dom_ms, "flops_per_launch": dom_flops, "launches": dom["launches"],
-                     "traffic": None},
-        "kernels_all_arms": table(kt_all, 2 * total_steps), "kernels_resident_arm": table(kt_res, total_steps),
+                     "traffic": TRAFFIC.get((cfg.name, dom["name"]))},
+        "kernels_resident_arm": table(kt_res, total_steps), "kernels_offload_arm": table(kt_off, total_steps),
     }
 
     # ---- overlap-model view of this machine (Eq. 1-4 with the measured eta's)
     blob = run.blob_bytes
-    t_comp_blk = res_ms / L
+    t_comp_blk = (res_ms if do_res else off_ms) / L
     t_pref_blk = (blob / (h2d_gbs * 1e9) * 1e3) if h2d_gbs > 0 else None
     result["model"] = {"t_comp_block_ms": t_comp_blk, "t_pref_block_ms": t_pref_blk,
                        "hidden": (t_pref_blk is not None and t_comp_blk >= t_pref_blk),

@@ -170,3 +170,52 @@ def test_call_order_errors():
         run.ctx.cf_sync()
     finally:
         run.close()
+
+
+@pytest.mark.parametrize("n_chunks,r", [(6, 0.0), (3, 0.34)])
+def test_contention_and_pause_resume_keep_results_and_volume(n_chunks, r):
+    """Emulated collectives on a third stream, with and without the pause/resume worker
+    (Sec. 3.2): outputs stay bit-identical, the prefetch volume is unchanged, and the collective
+    traffic is 4 transfers per block forward, half in each direction."""
+    cfg = wl.CONFIGS["toy"]
+    cb = chunk_bytes_for(cfg, n_chunks)
+    run = BlockRunner(cfg, chunk_bytes=cb, n_blocks=2)
+    try:
+        ios = []
+        for blk in range(2):
+            run.register_params(blk, wl.gen_block_params(cfg, blk))
+            ios.append(run.make_io(wl.gen_block_inputs(cfg, blk)))
+        structs = [run.io_struct(t) for t in ios]
+        nbytes = cfg.n_local * cfg.d * 2
+        host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        base = None
+        for mode in ("off", "on", "pause", "off"):
+            if mode == "off":
+                run.ctx.cf_set_contention(None, None, 0, False)
+            else:
+                run.ctx.cf_set_contention(run.comm, host, nbytes, mode == "pause")
+            run.ctx.set_resident_fraction(r)
+            run.ctx.cf_stats_reset()
+            for t in ios:
+                t["y"].zero_()
+            run.begin(0)
+            for _ in range(3):
+                run.step(structs)
+            run.fwd(0, structs[0])
+            run.ctx.cf_sync()
+            st = run.ctx.cf_stats()
+            outs = [t["y"].clone() for t in ios]
+            assert st["h2d_bytes"] == 7 * (run.blob_bytes - st["resident_bytes"])
+            if mode == "off":
+                assert st["comm_bytes_h2d"] == 0 and st["pauses"] == 0
+            else:
+                assert st["comm_bytes_h2d"] == st["comm_bytes_d2h"] == 7 * 4 * (nbytes // 2)
+            if mode != "pause":
+                assert st["pauses"] == 0
+            if base is None:
+                base = outs
+            else:
+                for a, b in zip(outs, base):
+                    assert torch.equal(a, b), mode
+    finally:
+        run.close()
