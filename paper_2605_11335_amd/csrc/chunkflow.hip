@@ -734,6 +734,11 @@ int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
     const int s = c->next_slot;                                    // slots alternate per prefetch
     if (c->slot_state[s] == SLOT_FILLED)
         return fail(c, CF_ERR_STATE, "slot %d still holds block %d whose forward has not been issued", s, c->slot_tenant[s]);
+    // Bound how far the host runs ahead of the GPU: the block that last finished in the OTHER slot
+    // (two forwards back) must be done before more work is queued.  The GPU still has one whole
+    // block of queued work, so it never starves, and the runtime's queues never fill up -- a host
+    // that is blocked inside the runtime mid-step would leave the copy stream idle.
+    if (c->done_valid[s ^ 1]) CF_HIP(c, hipEventSynchronize(c->done_ev[s ^ 1]));
     c->next_slot ^= 1;
     if (c->slot_tenant[s] >= 0 && c->block_slot[c->slot_tenant[s]] == s) c->block_slot[c->slot_tenant[s]] = -1;
     c->slot_tenant[s] = block;
