@@ -1,0 +1,74 @@
+"""Single-kernel microbenchmarks through the C ABI (linear layers, attention) plus a plain
+device-to-device copy of known size, used to calibrate hardware byte counters.
+
+    python -m paper_2605_11335_amd.kernel_bench linear 2304x21504x3072 [iters]
+    python -m paper_2605_11335_amd.kernel_bench linear_residual 2304x3072x15360 [iters]
+    python -m paper_2605_11335_amd.kernel_bench attention 12x4608x128 [iters]
+    python -m paper_2605_11335_amd.kernel_bench copy 536870912 [iters]      # bytes
+
+Timing uses events on the current stream; inputs are seeded N(0,1) activations and N(0,0.02)
+weights in bf16.
+"""
+from __future__ import annotations
+
+import sys
+
+import torch
+
+from . import binding as B
+
+DEV = "cuda:0"
+
+
+def timeit(fn, iters):
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(iters):
+        fn()
+    e.record()
+    torch.cuda.synchronize()
+    return s.elapsed_time(e) / iters
+
+
+def main(argv):
+    which, shape = argv[1], argv[2]
+    iters = int(argv[3]) if len(argv) > 3 else 20
+    torch.manual_seed(0)
+    if which in ("linear", "linear_residual"):
+        M, N, K = (int(v) for v in shape.split("x"))
+        A = torch.randn(M, K, device=DEV).to(torch.bfloat16)
+        W = (torch.randn(N, K, device=DEV) * 0.02).to(torch.bfloat16)
+        if which == "linear":
+            out = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
+            ms = timeit(lambda: B.cf_op_linear(A, W, 0, -1, M, N, K, out), iters)
+        else:
+            resid = torch.randn(M, N, device=DEV)
+            gate = torch.randn(N, device=DEV)
+            y = torch.empty(M, N, device=DEV)
+            ms = timeit(lambda: B.cf_op_linear_residual(A, W, 0, -1, M, N, K, resid, gate, y), iters)
+        print(f"{which} {M}x{N}x{K}: {ms:.4f} ms  {2 * M * N * K / ms / 1e9:.1f} TFLOP/s")
+    elif which == "attention":
+        H, N, hd = (int(v) for v in shape.split("x"))
+        npad = (N + 63) // 64 * 64
+        Q = torch.randn(H, N, hd, device=DEV).to(torch.bfloat16)
+        K_ = torch.randn(H, N, hd, device=DEV).to(torch.bfloat16)
+        Vt = torch.zeros(H, hd, npad, device=DEV, dtype=torch.bfloat16)
+        Vt[:, :, :N] = torch.randn(H, hd, N, device=DEV).to(torch.bfloat16)
+        O = torch.empty(H, N, hd, dtype=torch.bfloat16, device=DEV)
+        ms = timeit(lambda: B.cf_op_attention(Q, K_, Vt, O, H, N, N, npad, hd), iters)
+        print(f"attention H={H} N={N} hd={hd}: {ms:.4f} ms  {4 * H * N * N * hd / ms / 1e9:.1f} TFLOP/s")
+    elif which == "copy":
+        n = int(shape)
+        src = torch.empty(n, dtype=torch.uint8, device=DEV).random_(0, 255)
+        dst = torch.empty_like(src)
+        ms = timeit(lambda: dst.copy_(src), iters)
+        print(f"copy {n} bytes: {ms:.4f} ms  {2 * n / ms / 1e6:.1f} GB/s (read + write)")
+    else:
+        raise SystemExit(__doc__)
+
+
+if __name__ == "__main__":
+    main(sys.argv)
