@@ -130,39 +130,47 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
             }
         }
 
-        // ---- online softmax; register v of tile mt is key k0 + mt*32 + 16*(v/8) + 8*lg + v%8
+        // ---- online softmax; register v of tile mt is key k0 + mt*32 + 16*(v/8) + 8*lg + v%8.
+        // The max is taken on raw scores (the scale is positive); scale and max-subtraction are one
+        // FMA per element in front of exp2.
         const int k0 = t * BKV;
-        float mx = -INFINITY;
+        if (k0 + BKV > a.nk) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = k0 + mt * 32 + 16 * (v >> 3) + 8 * lg + (v & 7);
+                    if (key >= a.nk) s[mt][v] = -INFINITY;
+                }
+        }
+        float mx = s[0][0];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float x = s[mt][v] * c2;
-                if (k0 + BKV > a.nk) {
-                    const int key = k0 + mt * 32 + 16 * (v >> 3) + 8 * lg + (v & 7);
-                    if (key >= a.nk) x = -INFINITY;
-                }
-                s[mt][v] = x;
-                mx = fmaxf(mx, x);
-            }
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mt][v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
+        // rescale the accumulators only when some query of this wave saw a new maximum
+        if (__any(m_new > m_run)) {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+            l_run *= alpha;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[d][v] *= alpha;
+            m_run = m_new;
+        }
+        const float mc = m_run * c2;
         float psum = 0.f;
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float p = __builtin_amdgcn_exp2f(s[mt][v] - m_new);
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[mt][v], c2, -mc));
                 s[mt][v] = p;
                 psum += p;
             }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int d = 0; d < DT; ++d)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[d][v] *= alpha;
+        l_run += psum;
 
         // ---- O^T += V^T . P^T, 4 k-steps of 16 keys
 #pragma unroll
