@@ -115,20 +115,45 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
         const char* cK = sK + buf * K_TILE;
         const char* cV = sV + buf * V_TILE;
 
-        // ---- S^T = K . Q^T for 2 x 32 keys
+        // ---- S^T = K . Q^T for 2 x 32 keys.  MFMA i handles key half (i & 1) and k-step (i >> 1), so
+        // consecutive MFMAs hit different accumulators; K fragments run 4 reads ahead in a ring.
         floatx16 s[2];
+        {
+            bf16x8 kf[4];
+            auto kfrag = [&](int i) {
+                const int key = (i & 1) * 32 + krow, c = (i >> 1) * 2 + lg;
+                return *(const bf16x8*)(cK + key * KROW + ((c ^ kswz(key)) << 4));
+            };
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt) {
+            for (int i = 0; i < 4; ++i) kf[i] = kfrag(i);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s[mt][v] = 0.f;
-            const int key = mt * 32 + krow;
+            for (int i = 0; i < 2 * KS; ++i) {
+                if (i < 2) {
+                    floatx16 z;
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-                const int c = kk * 2 + lg;
-                const bf16x8 kf = *(const bf16x8*)(cK + key * KROW + ((c ^ kswz(key)) << 4));
-                s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s[mt], 0, 0, 0);
+                    for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                    s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[i >> 1], z, 0, 0, 0);
+                } else {
+                    s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[i >> 1], s[i & 1], 0, 0, 0);
+                }
+                if (i + 4 < 2 * KS) kf[i & 3] = kfrag(i + 4);
             }
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int i = 0; i < 2 * KS - 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
         }
+        // first V^T fragments: issued now so that they land while the softmax runs
+        bf16x8 vf[4];
+        auto vfrag = [&](int i) {                   // i = ks * DT + d
+            const int row = (i % DT) * 32 + lj, c = (i / DT) * 2 + lg;
+            return *(const bf16x8*)(cV + row * 128 + ((c ^ vswz(row)) << 4));
+        };
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vf[i] = vfrag(i);
 
         // ---- online softmax; register v of tile mt is key k0 + mt*32 + 16*(v/8) + 8*lg + v%8.
         // The max is taken on raw scores (the scale is positive); scale and max-subtraction are one
@@ -172,19 +197,25 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
             }
         l_run += psum;
 
-        // ---- O^T += V^T . P^T, 4 k-steps of 16 keys
+        // ---- O^T += V^T . P^T: MFMA i handles k-step (i / DT) of 16 keys and d-tile (i % DT);
+        // V^T fragments keep running 4 reads ahead
+        {
+            bf16x8 pf[4];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 pf;
+            for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[e] = (bf16)s[ks >> 1][8 * (ks & 1) + e];
-            const int c = ks * 2 + lg;
+                for (int e = 0; e < 8; ++e) pf[ks][e] = (bf16)s[ks >> 1][8 * (ks & 1) + e];
 #pragma unroll
-            for (int d = 0; d < DT; ++d) {
-                const int row = d * 32 + lj;
-                const bf16x8 vf = *(const bf16x8*)(cV + row * 128 + ((c ^ vswz(row)) << 4));
-                o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, o[d], 0, 0, 0);
+            for (int i = 0; i < 4 * DT; ++i) {
+                o[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i & 3], pf[i / DT], o[i % DT], 0, 0, 0);
+                if (i + 4 < 4 * DT) vf[i & 3] = vfrag(i + 4);
             }
+#pragma unroll
+            for (int i = 0; i < 4 * DT - 4; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
         }
 
         __syncthreads();                        // tile t+1 has landed, tile t may be overwritten
