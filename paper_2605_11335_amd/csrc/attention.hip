@@ -174,9 +174,11 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mt][v]);
         mx = fmaxf(mx, __shfl_xor(mx, 32));
+        // Rescale lazily: the reference maximum only moves when some query of this wave exceeds it by
+        // more than 2^8 (softmax is invariant to the reference as long as numerator and denominator
+        // share it; P then stays below 256, comfortably inside bf16 and fp32 range).
         const float m_new = fmaxf(m_run, mx);
-        // rescale the accumulators only when some query of this wave saw a new maximum
-        if (__any(m_new > m_run)) {
+        if (__any((m_new - m_run) * c2 > 8.0f)) {
             const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
             l_run *= alpha;
 #pragma unroll
