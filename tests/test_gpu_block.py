@@ -219,3 +219,65 @@ def test_contention_and_pause_resume_keep_results_and_volume(n_chunks, r):
                     assert torch.equal(a, b), mode
     finally:
         run.close()
+
+
+def test_resident_split_anywhere_in_the_blob_is_bit_identical():
+    """The resident/streamed boundary is swept through every tensor of the blob (modulation
+    matrix, biases, norm weights, both GEMM weights, mid-row): outputs never change by a bit."""
+    cfg = wl.BlockConfig("mini_split", wl.KIND_SINGLE, n_blocks=1, d=256, n_heads=2, head_dim=128, f=512,
+                         n_total=200, sp_degree=1, qk_rmsnorm=True, n_chunks=1)
+    probe = BlockRunner(cfg, chunk_bytes=256 * 1024, n_blocks=1)
+    blob = probe.blob_bytes
+    probe.close()
+    cb = 256 * 37                                   # 9472-byte chunks: boundaries fall mid-row everywhere
+    run = BlockRunner(cfg, chunk_bytes=cb, n_blocks=1)
+    try:
+        assert run.n_chunks == -(-blob // cb) and run.n_chunks > 100
+        params, inputs = wl.gen_block_params(cfg, 0), wl.gen_block_inputs(cfg, 0)
+        run.register_params(0, params)
+        t = run.make_io(inputs)
+        base = None
+        for r in np.linspace(1.0, 0.0, 23):
+            run.ctx.set_resident_fraction(float(r))
+            t["y"].zero_()
+            run.run_block(0, t)
+            y = t["y"].clone()
+            if base is None:
+                base = y
+                ref = ob.block_forward(cfg, params, inputs)["y"]
+                assert rel_l2(y.cpu().numpy(), ref) <= REL_L2_TOL and max_abs(y.cpu().numpy(), ref) <= MAX_ABS_TOL
+            else:
+                assert torch.equal(y, base), f"r={r}"
+    finally:
+        run.close()
+
+
+def test_single_block_model_and_odd_block_counts():
+    """Slots alternate per prefetch: a 1-block and a 3-block stack step correctly."""
+    for L in (1, 3):
+        cfg = wl.CONFIGS["toy"].with_(n_blocks=L)
+        run = BlockRunner(cfg, chunk_bytes=chunk_bytes_for(cfg, 3))
+        try:
+            ios, refs = [], []
+            for b in range(L):
+                params, inputs = wl.gen_block_params(cfg, b), wl.gen_block_inputs(cfg, b)
+                run.register_params(b, params)
+                ios.append(run.make_io(inputs))
+                refs.append(ob.block_forward(cfg, params, inputs)["y"])
+            structs = [run.io_struct(t) for t in ios]
+            if L > 1:
+                run.begin(0)
+            else:
+                run.begin(0)
+            for _ in range(3):
+                run.step(structs)
+            if L > 1:
+                run.fwd(0, structs[0])
+            else:
+                run.fwd(0, structs[0])
+            run.ctx.cf_sync()
+            for t, ref in zip(ios, refs):
+                y = t["y"].cpu().numpy()
+                assert rel_l2(y, ref) <= REL_L2_TOL and max_abs(y, ref) <= MAX_ABS_TOL
+        finally:
+            run.close()

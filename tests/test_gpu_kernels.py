@@ -170,3 +170,21 @@ def test_launch_checks_reject_bad_shapes():
         B.cf_op_attention(z, z, z, z, 1, 4, 4, 4, 128)    # nk_pad not a multiple of 64
     with pytest.raises(B.ChunkflowError):
         B.cf_op_attention(z, z, z, z, 1, 4, 4, 64, 96)    # head_dim
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 8, 64), (257, 264, 64), (3, 4096, 128), (4097, 16, 192)])
+def test_linear_degenerate_shapes(M, N, K):
+    rng = np.random.default_rng(M * 7 + N + K)
+    a, ab = bf16_round(rng.normal(size=(M, K)))
+    buf, w, b, w_off, b_off = make_blob(rng, N, K)
+    out = torch.zeros((M, N), dtype=torch.int16, device=DEV)
+    B.cf_op_linear(dev_bits(ab), torch.from_numpy(buf).to(DEV), w_off, b_off, M, N, K, out)
+    torch.cuda.synchronize()
+    assert_bf16_close(host_bits(out), a.astype(np.float64) @ w.T + b, extra_abs=1e-4)
+
+
+@pytest.mark.parametrize("H,nq,nk,hd", [(1, 5, 64, 128), (1, 130, 129, 128), (2, 1, 4097, 64), (1, 4100, 3, 128)])
+def test_attention_ragged_extremes(H, nq, nk, hd):
+    rng = np.random.default_rng(nq * 13 + nk)
+    got, ref = run_attention(rng.normal(size=(H, nq, hd)), rng.normal(size=(H, nk, hd)), rng.normal(size=(H, nk, hd)), hd)
+    assert rel_l2(got, ref) < 6e-3 and max_abs(got, ref) < 2e-2 * max(1.0, np.abs(ref).max())
