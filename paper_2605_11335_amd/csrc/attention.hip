@@ -24,15 +24,17 @@ __device__ __forceinline__ void lds_load16(const void* gptr, void* lds) {
                                      (void __attribute__((address_space(3)))*)lds, 16, 0, 0);
 }
 
-constexpr int BQ = 128;    // queries per workgroup (4 waves x 32)
 constexpr int BKV = 64;    // keys per tile
 
-template <int HD>
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
+// NW waves of 32 queries each per workgroup.  NW = 4 runs two workgroups per CU; NW = 5..8 run one,
+// which lets the launcher pick the query-tile height whose grid fills the last round best.
+template <int HD, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
+    constexpr int BQ = 32 * NW;
     constexpr int KCH = HD / 8;                 // 16-byte chunks per K row
     constexpr int KROW = HD * 2;                // bytes per K row in LDS
-    constexpr int K_LOADS = BKV * KCH / 256;
-    constexpr int V_LOADS = HD * 8 / 256;
+    constexpr int KL = BKV * KCH / 64, VL = HD * 8 / 64;   // wave-loads (1 KiB each) per K / V^T tile
+    constexpr int LPW = (KL + VL + NW - 1) / NW;           // wave-loads per wave per tile (round robin)
     constexpr int K_TILE = BKV * KROW, V_TILE = HD * 128;
     constexpr int DT = HD / 32;                 // 32-row tiles of O^T
     constexpr int KS = HD / 16;                 // k-steps of the first contraction
@@ -67,31 +69,31 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
     // lane fetches is the one whose swizzled slot it fills.
     const int uw = __builtin_amdgcn_readfirstlane(wave);
     constexpr int K_RPL = 1024 / KROW;          // key rows per wave-load
-    const bf16* k_src[K_LOADS];
-    int k_row[K_LOADS];
+    const bf16* t_src[LPW];                     // wave-load j = jj * NW + wave: K loads first, then V^T
+    int t_row[LPW];                             // key row of a K load (clamped per tile), -1 for V^T
 #pragma unroll
-    for (int j = 0; j < K_LOADS; ++j) {
-        const int key = (j * 4 + uw) * K_RPL + lane / KCH;
-        const int c = (lane % KCH) ^ kswz(key);
-        k_row[j] = key;
-        k_src[j] = a.K + (size_t)h * a.nk * HD + c * 8;
-    }
-    const bf16* v_src[V_LOADS];
-#pragma unroll
-    for (int j = 0; j < V_LOADS; ++j) {
-        const int row = (j * 4 + uw) * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ vswz(row);
-        v_src[j] = a.Vt + ((size_t)h * HD + row) * a.nk_pad + c * 8;
+    for (int jj = 0; jj < LPW; ++jj) {
+        const int j = jj * NW + uw;
+        if (j < KL) {
+            const int key = j * K_RPL + lane / KCH;
+            t_row[jj] = key;
+            t_src[jj] = a.K + (size_t)h * a.nk * HD + ((lane % KCH) ^ kswz(key)) * 8;
+        } else {
+            const int row = min(j - KL, VL - 1) * 8 + (lane >> 3);
+            t_row[jj] = -1;
+            t_src[jj] = a.Vt + ((size_t)h * HD + row) * a.nk_pad + ((lane & 7) ^ vswz(row)) * 8;
+        }
     }
     auto issue_tile = [&](int t, int buf) {
         const int k0 = t * BKV;
-        char* dK = sK + buf * K_TILE + uw * 1024;
-        char* dV = sV + buf * V_TILE + uw * 1024;
 #pragma unroll
-        for (int j = 0; j < K_LOADS; ++j)
-            lds_load16(k_src[j] + (size_t)min(k0 + k_row[j], a.nk - 1) * HD, dK + j * 4096);
-#pragma unroll
-        for (int j = 0; j < V_LOADS; ++j) lds_load16(v_src[j] + k0, dV + j * 4096);
+        for (int jj = 0; jj < LPW; ++jj) {
+            const int j = jj * NW + uw;         // wave-uniform
+            if (j < KL)
+                lds_load16(t_src[jj] + (size_t)min(k0 + t_row[jj], a.nk - 1) * HD, sK + buf * K_TILE + j * 1024);
+            else if (j < KL + VL)
+                lds_load16(t_src[jj] + k0, sV + buf * V_TILE + (j - KL) * 1024);
+        }
     };
 
     floatx16 o[DT];
@@ -251,19 +253,30 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(AttnArgs a) {
     }
 }
 
-template <int HD>
+template <int HD, int NW>
 hipError_t launch(const AttnArgs& a, hipStream_t s) {
     const size_t smem = 2 * (BKV * HD * 2 + HD * 128);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_kernel<HD>,
+        hipError_t e = hipFuncSetAttribute((const void*)attn_fwd_kernel<HD, NW>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int nqt = (a.nq + BQ - 1) / BQ;
-    hipLaunchKernelGGL((attn_fwd_kernel<HD>), dim3(nqt * a.H), dim3(256), smem, s, a);
+    const int nqt = (a.nq + 32 * NW - 1) / (32 * NW);
+    hipLaunchKernelGGL((attn_fwd_kernel<HD, NW>), dim3(nqt * a.H), dim3(64 * NW), smem, s, a);
     return hipGetLastError();
+}
+
+template <int HD>
+hipError_t launch_nw(int nw, const AttnArgs& a, hipStream_t s) {
+    switch (nw) {
+        case 5: return launch<HD, 5>(a, s);
+        case 6: return launch<HD, 6>(a, s);
+        case 7: return launch<HD, 7>(a, s);
+        case 8: return launch<HD, 8>(a, s);
+        default: return launch<HD, 4>(a, s);
+    }
 }
 
 }  // namespace
@@ -275,10 +288,31 @@ const char* attn_check(const AttnArgs& a) {
     if (!a.Q || !a.K || !a.Vt || !a.O) return "attention: null operand";
     if (((uintptr_t)a.Q | (uintptr_t)a.K | (uintptr_t)a.Vt) % 16) return "attention: operands must be 16-byte aligned";
     if (((uintptr_t)a.O % 8) || (a.o_hs % 4) || (a.o_qs % 4)) return "attention: output must be 8-byte aligned";
-    if ((long)((a.nq + BQ - 1) / BQ) * a.H > 0x7fffffffL) return "attention: grid too large";
+    if ((long)((a.nq + 127) / 128) * a.H > 0x7fffffffL) return "attention: grid too large";
     return nullptr;
 }
 
+// Waves per workgroup: a CU holds 8 waves of this kernel (two 4-wave workgroups or one of 5..8), so
+// a round of workgroups costs (waves resident per CU) / 8 of a full round; pick the height with the
+// cheapest total, preferring fewer, taller workgroups (fewer K/V tile copies) on ties.
+int attn_waves(const AttnArgs& a) {
+#ifdef CF_DBG_NW
+    return CF_DBG_NW;
+#endif
+    // a grid that cannot even give every CU one 4-wave workgroup is spread as widely as possible
+    if ((long)((a.nq + 127) / 128) * a.H <= 256) return 4;
+    int best = 4;
+    double best_cost = 1e300;
+    for (int nw = 8; nw >= 4; --nw) {
+        const long items = (long)((a.nq + 32 * nw - 1) / (32 * nw)) * a.H;
+        const long slots = nw == 4 ? 512 : 256;
+        const double cost = (double)((items + slots - 1) / slots) * (nw == 4 ? 1.0 : nw / 8.0);
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = nw; }
+    }
+    return best;
+}
+
 hipError_t attn_launch(const AttnArgs& a, hipStream_t s) {
-    return a.hd == 128 ? launch<128>(a, s) : launch<64>(a, s);
+    const int nw = attn_waves(a);
+    return a.hd == 128 ? launch_nw<128>(nw, a, s) : launch_nw<64>(nw, a, s);
 }
