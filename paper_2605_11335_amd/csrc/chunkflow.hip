@@ -312,7 +312,7 @@ hipEvent_t prof_event(cf_ctx* c) {
     return e;
 }
 
-// kid + K_COUNT * variant; variant 1 = the 128x128-tile instantiation of a GEMM
+// kid + K_COUNT * variant; variant = the GEMM's tile shape (gemm_tile)
 struct ProfScope {
     cf_ctx* c; hipStream_t s; ProfEntry pe; bool on;
     ProfScope(cf_ctx* c_, hipStream_t s_, int kid, double flops, double bytes, int variant = 0)
@@ -332,12 +332,12 @@ int prof_resolve(cf_ctx* c) {
     if (c->prof_pending.empty()) return CF_OK;
     CF_HIP(c, hipDeviceSynchronize());
     if (c->ktimes.empty()) {
-        c->ktimes.resize(2 * K_COUNT);
-        for (int i = 0; i < 2 * K_COUNT; ++i) {
+        c->ktimes.resize(3 * K_COUNT);
+        for (int i = 0; i < 3 * K_COUNT; ++i) {
             memset(&c->ktimes[i], 0, sizeof(cf_kernel_time));
             const bool gemm = strncmp(kKidName[i % K_COUNT], "gemm_", 5) == 0;
             snprintf(c->ktimes[i].name, sizeof c->ktimes[i].name, "%s%s", kKidName[i % K_COUNT],
-                     gemm ? (i < K_COUNT ? "/256x256" : "/128x128") : "");
+                     gemm ? (i < K_COUNT ? "/256x256" : (i < 2 * K_COUNT ? "/128x128" : "/256x128")) : "");
         }
     }
     for (auto& pe : c->prof_pending) {
@@ -444,7 +444,7 @@ int run_linear(Fwd& F, int kid, const std::string& wname, const std::string& bna
         p.n0 = r0;
         p.n1 = r1;
         if (const char* msg = gemm_check(p)) return fail(F.c, CF_ERR_ARG, "%s (%s)", msg, wname.c_str());
-        ProfScope ps(F.c, F.s, kid, 2.0 * p.M * (r1 - r0) * p.K, 0, gemm_tile(p) == 256 ? 0 : 1);
+        ProfScope ps(F.c, F.s, kid, 2.0 * p.M * (r1 - r0) * p.K, 0, gemm_tile(p));
         CF_HIP(F.c, gemm_launch(p, F.s));
         return CF_OK;
     });

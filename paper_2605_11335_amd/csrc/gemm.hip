@@ -341,15 +341,28 @@ const char* gemm_check(const GemmArgs& g) {
     return nullptr;
 }
 
+// Tile shape for a launch: 0 = 256x256, 1 = 128x128, 2 = 256 tokens x 128 features.  The big tile
+// has the best arithmetic intensity but needs enough tiles to cover the 256 CUs; estimated cost =
+// rounds x tile area / relative efficiency of the shape (128x128 runs two workgroups per CU).
 int gemm_tile(const GemmArgs& g) {
-    // Small problems take 128x128 tiles so that the grid still covers the chip.
-    const long tiles256 = (long)((g.M + 255) / 256) * ((g.n1 - g.n0 + 255) / 256);
-    return tiles256 >= 128 ? 256 : 128;
+#ifdef CF_DBG_TILE
+    return CF_DBG_TILE;
+#endif
+    const long m256 = (g.M + 255) / 256, m128 = (g.M + 127) / 128;
+    const long n = g.n1 - g.n0, n256 = (n + 255) / 256, n128 = (n + 127) / 128;
+    auto rounds = [](long tiles, long slots) { return (double)((tiles + slots - 1) / slots); };
+    const double c256 = rounds(m256 * n256, 256) * 1.0;
+    const double c128 = rounds(m128 * n128, 512) * 2.0 * 0.25 / 0.65;
+    const double c2x1 = rounds(m256 * n128, 256) * 0.5 / 0.80;
+    if (c256 <= c128 && c256 <= c2x1) return 0;
+    return c2x1 <= c128 ? 2 : 1;
 }
 
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
-    const bool big = gemm_tile(g) == 256;
+    const int t = gemm_tile(g);
     if (g.epi == EPI_SPLIT_GELU)
-        return big ? launch<256, 256, EPI_SPLIT_GELU>(g, s) : launch<128, 128, EPI_SPLIT_GELU>(g, s);
-    return big ? launch<256, 256, EPI_GATE_RESID>(g, s) : launch<128, 128, EPI_GATE_RESID>(g, s);
+        return t == 0 ? launch<256, 256, EPI_SPLIT_GELU>(g, s)
+                      : (t == 2 ? launch<256, 128, EPI_SPLIT_GELU>(g, s) : launch<128, 128, EPI_SPLIT_GELU>(g, s));
+    return t == 0 ? launch<256, 256, EPI_GATE_RESID>(g, s)
+                  : (t == 2 ? launch<256, 128, EPI_GATE_RESID>(g, s) : launch<128, 128, EPI_GATE_RESID>(g, s));
 }

@@ -23,7 +23,7 @@ struct GemmArgs {
     const float* resid; const float* gate; float* y; int ldy;
 };
 const char* gemm_check(const GemmArgs& g);
-int gemm_tile(const GemmArgs& g);      // 256 or 128: the square tile gemm_launch will use
+int gemm_tile(const GemmArgs& g);      // tile gemm_launch will use: 0 = 256x256, 1 = 128x128, 2 = 256x128
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s);
 
 // Positions of this rank's tokens in the joint sequence: up to two contiguous segments

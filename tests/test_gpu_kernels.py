@@ -196,3 +196,23 @@ def test_attention_every_workgroup_height(H, n, hd):
     rng = np.random.default_rng(H + n + hd)
     got, ref = run_attention(rng.normal(size=(H, n, hd)), rng.normal(size=(H, n, hd)), rng.normal(size=(H, n, hd)), hd)
     assert rel_l2(got, ref) < 6e-3 and max_abs(got, ref) < 2e-2 * max(1.0, np.abs(ref).max())
+
+
+def test_linear_rectangular_tile_shapes():
+    """Shapes that make the launcher pick the 256x128 tile (both epilogues), with ragged edges."""
+    rng = np.random.default_rng(21)
+    M, N, K = 2304, 3080, 256
+    a, ab = bf16_round(rng.normal(size=(M, K)))
+    buf, w, b, w_off, b_off = make_blob(rng, N, K)
+    blob = torch.from_numpy(buf).to(DEV)
+    out = torch.zeros((M, N), dtype=torch.int16, device=DEV)
+    B.cf_op_linear(dev_bits(ab), blob, w_off, b_off, M, N, K, out)
+    resid = rng.normal(size=(M, N)).astype(np.float32)
+    g = rng.normal(size=N).astype(np.float32)
+    y = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    B.cf_op_linear_residual(dev_bits(ab), blob, w_off, b_off, M, N, K, torch.from_numpy(resid).to(DEV),
+                            torch.from_numpy(g).to(DEV), y)
+    torch.cuda.synchronize()
+    z = a.astype(np.float64) @ w.T + b
+    assert_bf16_close(host_bits(out), z, extra_abs=1e-4)
+    assert max_abs(y.cpu().numpy(), resid + g.astype(np.float64) * z) < 1e-3
