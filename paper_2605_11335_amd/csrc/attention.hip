@@ -138,9 +138,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
                 } else {
                     s[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i & 3], qf[i >> 1], s[i & 1], 0, 0, 0);
                 }
-#ifndef CF_DBG_NOKFRAG
                 if (i + 4 < 2 * KS) kf[i & 3] = kfrag(i + 4);
-#endif
             }
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
@@ -197,13 +195,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-#if defined(CF_DBG_NOEXP)
-                const float p = fmaf(s[mt][v], c2, -mc);
-#elif defined(CF_DBG_NOSOFTMAX)
-                const float p = s[mt][v];
-#else
                 const float p = __builtin_amdgcn_exp2f(fmaf(s[mt][v], c2, -mc));
-#endif
                 s[mt][v] = p;
                 psum += p;
             }
@@ -220,9 +212,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
 #pragma unroll
             for (int i = 0; i < 4 * DT; ++i) {
                 o[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i & 3], pf[i / DT], o[i % DT], 0, 0, 0);
-#ifndef CF_DBG_NOVFRAG
                 if (i + 4 < 4 * DT) vf[i & 3] = vfrag(i + 4);
-#endif
             }
 #pragma unroll
             for (int i = 0; i < 4 * DT - 4; ++i) {
@@ -296,9 +286,6 @@ const char* attn_check(const AttnArgs& a) {
 // a round of workgroups costs (waves resident per CU) / 8 of a full round; pick the height with the
 // cheapest total, preferring fewer, taller workgroups (fewer K/V tile copies) on ties.
 int attn_waves(const AttnArgs& a) {
-#ifdef CF_DBG_NW
-    return CF_DBG_NW;
-#endif
     // a grid that cannot even give every CU one 4-wave workgroup is spread as widely as possible
     if ((long)((a.nq + 127) / 128) * a.H <= 256) return 4;
     int best = 4;

@@ -42,11 +42,7 @@ __device__ __forceinline__ void lds_load16(const void* gptr, void* lds) {
 // (the last fragments of the current slab) have returned; after the barrier that holds for the
 // whole workgroup, so the next slab may be read and the current one overwritten.
 __device__ __forceinline__ void slab_handover() {
-#ifndef CF_DBG_NOBARRIER
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#else
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-#endif
 }
 
 template <int BM, int BN, int EPI>
@@ -345,9 +341,6 @@ const char* gemm_check(const GemmArgs& g) {
 // has the best arithmetic intensity but needs enough tiles to cover the 256 CUs; estimated cost =
 // rounds x tile area / relative efficiency of the shape (128x128 runs two workgroups per CU).
 int gemm_tile(const GemmArgs& g) {
-#ifdef CF_DBG_TILE
-    return CF_DBG_TILE;
-#endif
     const long m256 = (g.M + 255) / 256, m128 = (g.M + 127) / 128;
     const long n = g.n1 - g.n0, n256 = (n + 255) / 256, n128 = (n + 127) / 128;
     auto rounds = [](long tiles, long slots) { return (double)((tiles + slots - 1) / slots); };
