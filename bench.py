@@ -205,11 +205,22 @@ def main():
 
     if args.sweep:
         grid = []
+        link = None                       # H2D rate of the fully offloaded, uncontended point
         for mode in ("off", "on", "pause"):
             set_contention(mode)
-            for r in (0.0, 0.25, 0.5, 0.75, 1.0):
+            base_ms = None                # r = 1 step time of this contention mode
+            pts = []
+            for r in (1.0, 0.75, 0.5, 0.25, 0.0):
                 ms, act, s2 = arm(r, max(3, args.steps // 2), 1)
-                grid.append({"contention": mode, "r": r, "actual_r": act, "step_ms": ms,
+                pts.append((r, ms, act, s2))
+                if r == 1.0:
+                    base_ms = ms
+            if mode == "off":
+                link = L * run.blob_bytes / (pts[-1][1] * 1e-3)
+            for r, ms, act, s2 in reversed(pts):
+                # first-order prediction (Eq. 1-3 applied per block): max(compute window, prefetch time)
+                pred = L * max(base_ms / L, (1.0 - act) * run.blob_bytes / link * 1e3)
+                grid.append({"contention": mode, "r": r, "actual_r": act, "step_ms": ms, "model_step_ms": pred,
                              "weight_memory_bytes": s2["weight_memory_bytes"],
                              "h2d_gbs": L * (run.blob_bytes - s2["resident_bytes"]) / (ms * 1e-3) / 1e9,
                              "pauses": s2["pauses"]})
