@@ -125,6 +125,13 @@ int cf_n_chunks(const cf_ctx* ctx, int32_t* out);
 /* tensors in blob order; *n is capacity on entry, count on return (call with out=NULL to query) */
 int cf_blob_layout(const cf_ctx* ctx, cf_tensor_slot* out, int32_t* n);
 int cf_workspace_bytes(const cf_ctx* ctx, uint64_t* out);
+/* Host-only view of how dit_block_fwd cuts weight matrix `tensor` into panels of output features
+ * when the first n_resident_chunks chunks are resident (Sec. 3.2/3.3): panel i covers rows
+ * [row0[i], row1[i]) and may run once chunk wait_chunk[i] has landed (-1: no streamed chunk
+ * needed).  Boundaries are multiples of `granule` rows except the last.  *n: capacity / count;
+ * pass NULL arrays to query the count. */
+int cf_plan_panels(const cf_ctx* ctx, const char* tensor, int32_t granule, int32_t n_resident_chunks,
+                   int32_t* row0, int32_t* row1, int32_t* wait_chunk, int32_t* n);
 
 /* ---- weights (Sec. 2.2: all layers are placed in pinned host memory at initialisation).
  * host_blob must be pinned (hipHostMalloc), hold exactly cf_blob_bytes and outlive the context. */

@@ -51,7 +51,7 @@ class cf_kernel_time(C.Structure):
 
 #: every symbol include/chunkflow.h declares
 EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_chunks", "cf_blob_layout",
-           "cf_workspace_bytes", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
+           "cf_workspace_bytes", "cf_plan_panels", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
            "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
            "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling",
            "cf_kernel_times", "cf_kernel_times_reset", "cf_sync", "cf_op_linear", "cf_op_linear_residual",
@@ -84,6 +84,8 @@ def lib() -> C.CDLL:
                 fn.restype = C.c_int
         _lib.set_resident_fraction.argtypes = [C.c_void_p, C.c_double, C.POINTER(C.c_double)]
         _lib.cf_set_contention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64, C.c_int32]
+        _lib.cf_plan_panels.argtypes = [C.c_void_p, C.c_char_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.POINTER(C.c_int32)]
         _lib.cf_register_block.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64]
         _lib.chunked_prefetch_begin.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.chunked_prefetch_wait.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
@@ -168,6 +170,13 @@ class Context:
         v = C.c_uint64()
         _check(lib().cf_workspace_bytes(self._h, C.byref(v)), self._h)
         return v.value
+
+    def cf_plan_panels(self, tensor: str, granule: int, n_resident_chunks: int) -> List[tuple]:
+        n = C.c_int32(0)
+        _check(lib().cf_plan_panels(self._h, tensor.encode(), granule, n_resident_chunks, None, None, None, C.byref(n)), self._h)
+        r0, r1, w = (C.c_int32 * n.value)(), (C.c_int32 * n.value)(), (C.c_int32 * n.value)()
+        _check(lib().cf_plan_panels(self._h, tensor.encode(), granule, n_resident_chunks, r0, r1, w, C.byref(n)), self._h)
+        return [(r0[i], r1[i], w[i]) for i in range(n.value)]
 
     def cf_blob_layout(self) -> List[dict]:
         n = C.c_int32(0)

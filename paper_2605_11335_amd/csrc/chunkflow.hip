@@ -385,28 +385,45 @@ int need(Fwd& F, const TensorDesc& t) {
     return CF_OK;
 }
 
-// Launch `fn(row0, row1)` over the rows of weight matrix t as they become available: before
-// blocking on a chunk that is still streaming, everything whose bytes lie in earlier chunks is
-// launched (rounded down to `granule` rows so that launches stay tile-aligned).
-template <class Fn>
-int panels(Fwd& F, const TensorDesc& t, int granule, Fn&& fn) {
-    cf_ctx* c = F.c;
+// Panel plan of a weight matrix (pure host arithmetic): rows become usable chunk by chunk, so the
+// matrix is cut into panels [row0, row1), each tagged with the last chunk that must have landed
+// before it may run (-1: needs no streamed chunk beyond `already`).  Before blocking on a chunk
+// that is still streaming, everything whose bytes lie in earlier chunks forms a panel (rounded
+// down to `granule` rows so that launches stay tile-aligned).  `already` = highest chunk known
+// to be present (resident prefix or waited for earlier).
+struct Panel { int row0, row1, wait; };
+
+std::vector<Panel> plan_panels(const cf_ctx* c, const TensorDesc& t, int granule, int already) {
+    std::vector<Panel> out;
     const uint64_t row_bytes = 2ull * t.cols;
     const int first = (int)(t.off / c->chunk_bytes), last = (int)((t.off + t.bytes() - 1) / c->chunk_bytes);
-    int row0 = 0;
+    int row0 = 0, pending_wait = -1;
     for (int k = first; k <= last; ++k) {
-        if (k < c->n_res_chunks || k <= c->waited_upto) continue;
+        if (k <= already) continue;
         const uint64_t lim = chunk_begin(c, k);
         int avail = lim <= t.off ? 0 : (int)std::min<uint64_t>(t.rows, (lim - t.off) / row_bytes);
         avail = avail / granule * granule;
         if (avail > row0) {
-            CF_TRY(fn(row0, avail));
+            out.push_back(Panel{row0, avail, pending_wait});
             row0 = avail;
         }
-        CF_TRY(wait_chunk(c, F.block, k, F.s));
-        c->waited_upto = k;
+        pending_wait = k;               // rows beyond `avail` need chunk k
     }
-    if ((int)t.rows > row0) CF_TRY(fn(row0, (int)t.rows));
+    if ((int)t.rows > row0) out.push_back(Panel{row0, (int)t.rows, pending_wait});
+    return out;
+}
+
+// Launch `fn(row0, row1)` over the panels of weight matrix t, each behind its chunk wait.
+template <class Fn>
+int panels(Fwd& F, const TensorDesc& t, int granule, Fn&& fn) {
+    cf_ctx* c = F.c;
+    for (const Panel& p : plan_panels(c, t, granule, std::max(c->waited_upto, c->n_res_chunks - 1))) {
+        if (p.wait > c->waited_upto && p.wait >= c->n_res_chunks) {
+            CF_TRY(wait_chunk(c, F.block, p.wait, F.s));
+            c->waited_upto = p.wait;
+        }
+        CF_TRY(fn(p.row0, p.row1));
+    }
     return CF_OK;
 }
 
@@ -673,6 +690,21 @@ int cf_blob_layout(const cf_ctx* c, cf_tensor_slot* out, int32_t* n) {
         }
     }
     *n = cnt;
+    return CF_OK;
+}
+
+int cf_plan_panels(const cf_ctx* c, const char* tensor, int32_t granule, int32_t n_resident_chunks, int32_t* row0,
+                   int32_t* row1, int32_t* wait_chunk_out, int32_t* n) {
+    if (!c || !tensor || !n || granule <= 0) return CF_ERR_ARG;
+    const TensorDesc* t = cf_find(c, tensor);
+    if (!t) return fail(c, CF_ERR_ARG, "no tensor named %s in the blob", tensor);
+    if (n_resident_chunks < 0 || n_resident_chunks > c->n_chunks) return fail(c, CF_ERR_ARG, "resident chunk count out of range");
+    const std::vector<Panel> plan = plan_panels(c, *t, granule, n_resident_chunks - 1);
+    if (row0 && row1 && wait_chunk_out) {
+        if (*n < (int)plan.size()) return fail(c, CF_ERR_ARG, "need room for %d panels", (int)plan.size());
+        for (size_t i = 0; i < plan.size(); ++i) { row0[i] = plan[i].row0; row1[i] = plan[i].row1; wait_chunk_out[i] = plan[i].wait; }
+    }
+    *n = (int)plan.size();
     return CF_OK;
 }
 

@@ -99,3 +99,33 @@ def test_block_range_is_checked_without_a_gpu():
     with pytest.raises(B.ChunkflowError) as e:
         c.chunked_prefetch_begin(5, None)
     assert e.value.code == B.CF_ERR_ARG
+
+
+@pytest.mark.parametrize("name,chunk_mib", [("flux", 16), ("flux", 35.4), ("wan", 64), ("toy", 0.5), ("hunyuan", 256)])
+def test_panel_plans_cover_every_row_once_behind_the_right_chunk(name, chunk_mib):
+    """Host logic of the per-chunk consumer waits: for every weight matrix and every resident
+    prefix, panels tile the rows exactly, are tile-aligned, and every byte of a panel lies in a
+    chunk that is resident or not later than the chunk the panel waits for."""
+    cfg = wl.CONFIGS[name]
+    cb = int(chunk_mib * (1 << 20)) // 256 * 256
+    c = ctx_for(cfg, cb)
+    n_chunks = c.cf_n_chunks()
+    bounds = och.chunk_bounds(c.cf_blob_bytes(), cb)
+    for t in c.cf_blob_layout():
+        if t["rows"] == 1:
+            continue
+        row_bytes = 2 * t["cols"]
+        for n_res in sorted({0, 1, n_chunks // 3, n_chunks // 2, n_chunks - 1, n_chunks}):
+            plan = c.cf_plan_panels(t["name"], 256, n_res)
+            assert plan[0][0] == 0 and plan[-1][1] == t["rows"]
+            for (a0, a1, w), nxt in zip(plan, plan[1:] + [None]):
+                assert a0 < a1
+                if nxt is not None:
+                    assert a1 == nxt[0] and a1 % 256 == 0 and w < nxt[2]
+                last_byte = t["offset"] + a1 * row_bytes - 1
+                need = next(k for k, (s, e) in enumerate(bounds) if s <= last_byte < e)
+                assert need < n_res or need <= w, (t["name"], n_res, a0, a1, w, need)
+                if w >= 0:
+                    assert w >= n_res        # never waits for a resident chunk
+            if n_res == n_chunks:
+                assert plan == [(0, t["rows"], -1)]     # fully resident: one launch, no wait
