@@ -298,10 +298,10 @@ int wait_chunk(cf_ctx* c, int block, int k, hipStream_t s) {
 // profiling: hipEvent pair around each kernel launch, resolved lazily
 // ------------------------------------------------------------------------------------------
 enum Kid {
-    K_MODVEC, K_LN, K_LIN1, K_QKV, K_RELAYOUT, K_PEER, K_ATTN, K_GATHER, K_LIN2, K_OUT, K_UP, K_DOWN,
+    K_MODVEC, K_LN, K_LIN1, K_QKV, K_RELAYOUT, K_ATTN, K_GATHER, K_LIN2, K_OUT, K_UP, K_DOWN,
     K_CROSS_Q, K_CROSS_KV, K_CROSS_ATTN, K_CROSS_OUT, K_COUNT
 };
-const char* kKidName[K_COUNT] = {"modvec", "ln_modulate", "gemm_lin1", "gemm_qkv", "qk_relayout", "peer_scatter",
+const char* kKidName[K_COUNT] = {"modvec", "ln_modulate", "gemm_lin1", "gemm_qkv", "pre_attention",
                                  "attention", "attn_gather", "gemm_lin2", "gemm_out", "gemm_up", "gemm_down",
                                  "gemm_cross_q", "gemm_cross_kv", "cross_attention", "gemm_cross_out"};
 
@@ -332,12 +332,12 @@ int prof_resolve(cf_ctx* c) {
     if (c->prof_pending.empty()) return CF_OK;
     CF_HIP(c, hipDeviceSynchronize());
     if (c->ktimes.empty()) {
-        c->ktimes.resize(3 * K_COUNT);
-        for (int i = 0; i < 3 * K_COUNT; ++i) {
+        c->ktimes.resize(2 * K_COUNT);
+        for (int i = 0; i < 2 * K_COUNT; ++i) {
             memset(&c->ktimes[i], 0, sizeof(cf_kernel_time));
             const bool gemm = strncmp(kKidName[i % K_COUNT], "gemm_", 5) == 0;
             snprintf(c->ktimes[i].name, sizeof c->ktimes[i].name, "%s%s", kKidName[i % K_COUNT],
-                     gemm ? (i < K_COUNT ? "/256x256" : (i < 2 * K_COUNT ? "/128x128" : "/256x128")) : "");
+                     gemm ? (i < K_COUNT ? "/256x256" : "/128x128") : "");
         }
     }
     for (auto& pe : c->prof_pending) {
@@ -509,16 +509,15 @@ int run_joint_attention(Fwd& F, const RelayoutArgs* parts, int n_parts, bf16* ds
     const TokenMap map = token_map(m);
     const int npad = n_pad_of(m.n_total);
     const cf_block_io* io = F.io;
-    for (int i = 0; i < n_parts; ++i) {
-        ProfScope ps(c, F.s, K_RELAYOUT, 0, 2.0 * 2 * parts[i].rows * 3.0 * m.d);
-        CF_HIP(c, relayout_launch(parts[i], F.s));
-    }
-    if (P > 1) {
-        if (!io->peer_q || !io->peer_k || !io->peer_v || !io->peer_attn)
-            return fail(c, CF_ERR_ARG, "sp_degree > 1 needs peer_q, peer_k, peer_v and peer_attn");
-        ProfScope ps(c, F.s, K_PEER, 0, 2.0 * 2 * 3 * hl * (double)(map.n_total - map.n_local) * hd);
-        CF_HIP(c, peer_scatter_launch((const bf16*)io->peer_q, (const bf16*)io->peer_k, (const bf16*)io->peer_v,
-                                      F.ws.Q, F.ws.K, F.ws.Vt, hl, hd, npad, map, F.s));
+    if (P > 1 && (!io->peer_q || !io->peer_k || !io->peer_v || !io->peer_attn))
+        return fail(c, CF_ERR_ARG, "sp_degree > 1 needs peer_q, peer_k, peer_v and peer_attn");
+    {
+        double bytes = 0;
+        for (int i = 0; i < n_parts; ++i) bytes += 2.0 * 2 * parts[i].rows * 3.0 * m.d;
+        if (P > 1) bytes += 2.0 * 2 * 3 * hl * (double)(map.n_total - map.n_local) * hd;
+        ProfScope ps(c, F.s, K_RELAYOUT, 0, bytes);
+        CF_HIP(c, pre_attention_launch(parts, n_parts, P > 1 ? (const bf16*)io->peer_q : nullptr,
+                                       P > 1 ? (const bf16*)io->peer_k : nullptr, P > 1 ? (const bf16*)io->peer_v : nullptr, F.s));
     }
     CF_TRY(emulate_collectives(F, 3));
     AttnArgs a;

@@ -32,23 +32,38 @@ __device__ __forceinline__ int remote_pos(const TokenMap& m, int i) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// m[n] = W[n,:] . t + b[n]; one wave per output row
+// m[n] = W[n,:] . t + b[n]; a wave owns MV_ROWS consecutive rows so that each slice of t is read
+// once per MV_ROWS weight vectors and that many 16-byte loads are in flight per lane.  A row's sum
+// is accumulated in the same lane order whatever rows share its wave.
+constexpr int MV_ROWS = 4;
 __global__ __launch_bounds__(256) void modvec_kernel(WView W, uint64_t w_off, uint64_t b_off, const float* __restrict__ t,
                                                      float* __restrict__ m, int n0, int n1, int K) {
     const int lane = threadIdx.x & 63;
-    const int n = n0 + blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int n = n0 + (blockIdx.x * 4 + (threadIdx.x >> 6)) * MV_ROWS;
     if (n >= n1) return;
-    const uint64_t row = w_off + (uint64_t)n * K * 2;
-    float acc = 0.f;
+    float acc[MV_ROWS];
+#pragma unroll
+    for (int r = 0; r < MV_ROWS; ++r) acc[r] = 0.f;
     for (int c = lane; c < K / 8; c += 64) {
-        const uint4 u = *(const uint4*)wv_ptr(W, row + (uint64_t)c * 16);
-        float w[8];
-        unpack8(u, w);
+        uint4 u[MV_ROWS];
+#pragma unroll
+        for (int r = 0; r < MV_ROWS; ++r) {
+            const int nr = min(n + r, n1 - 1);
+            u[r] = *(const uint4*)wv_ptr(W, w_off + ((uint64_t)nr * K + (uint64_t)c * 8) * 2);
+        }
         const float4 t0 = *(const float4*)(t + c * 8), t1 = *(const float4*)(t + c * 8 + 4);
-        acc += w[0] * t0.x + w[1] * t0.y + w[2] * t0.z + w[3] * t0.w + w[4] * t1.x + w[5] * t1.y + w[6] * t1.z + w[7] * t1.w;
+#pragma unroll
+        for (int r = 0; r < MV_ROWS; ++r) {
+            float w[8];
+            unpack8(u[r], w);
+            acc[r] += w[0] * t0.x + w[1] * t0.y + w[2] * t0.z + w[3] * t0.w + w[4] * t1.x + w[5] * t1.y + w[6] * t1.z + w[7] * t1.w;
+        }
     }
-    acc = wave_sum(acc);
-    if (lane == 0) m[n] = acc + wv_bf16(W, b_off, n);
+#pragma unroll
+    for (int r = 0; r < MV_ROWS; ++r) {
+        const float v = wave_sum(acc[r]);
+        if (lane == 0 && n + r < n1) m[n + r] = v + wv_bf16(W, b_off, n + r);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -118,12 +133,12 @@ hipError_t ln_dispatch(const float* x, const float* shift, const float* scale, c
 // ---------------------------------------------------------------------------------------------
 // q,k: optional per-head RMSNorm, then head-major placement (own heads) or send buffers (others).
 // v of other heads: send buffer.  A group of hd/8 lanes owns one (row, tensor, head) vector.
-__global__ __launch_bounds__(256) void qk_relayout_kernel(RelayoutArgs r) {
+__device__ __forceinline__ void qk_relayout_part(const RelayoutArgs& r, int bid, int nblk) {
     const int lph = r.hd / 8;                       // lanes per head vector
     const int vec_per_blk = 256 / lph;
     const long n_vec = (long)r.rows * 3 * r.n_heads;
     const int sub = threadIdx.x % lph;
-    for (long vi = (long)blockIdx.x * vec_per_blk + threadIdx.x / lph; vi < n_vec; vi += (long)gridDim.x * vec_per_blk) {
+    for (long vi = (long)bid * vec_per_blk + threadIdx.x / lph; vi < n_vec; vi += (long)nblk * vec_per_blk) {
         const int hh = vi % r.n_heads;
         const int tns = (vi / r.n_heads) % 3;       // 0 q, 1 k, 2 v
         const int row = vi / (3 * r.n_heads);
@@ -167,12 +182,10 @@ __global__ __launch_bounds__(256) void qk_relayout_kernel(RelayoutArgs r) {
 // [token, hd] rows of one head -> Vt[head, d, position] (keys contiguous).  64 tokens per block.
 // src element (h, i, d) at src + h*src_hs + i*src_rs + d; i counts local rows (remote=0) or
 // remote rows (remote=1) and maps to its position in the joint sequence.
-__global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict__ src, long src_hs, long src_rs, int n_rows,
-                                                          int row0, bf16* __restrict__ Vt, int hd, int n_pad, TokenMap map,
-                                                          int remote) {
-    __shared__ uint16_t tile[64 * (128 + 2)];
-    const int h = blockIdx.y;
-    const int i0 = blockIdx.x * 64;
+__device__ __forceinline__ void v_transpose_part(uint16_t* tile, int bx, int h, const bf16* __restrict__ src, long src_hs,
+                                                 long src_rs, int n_rows, int row0, bf16* __restrict__ Vt, int hd, int n_pad,
+                                                 const TokenMap& map, int remote) {
+    const int i0 = bx * 64;
     const int stride = hd + 2;
     const int cpr = hd / 8;
     for (int q = threadIdx.x; q < 64 * cpr; q += 256) {
@@ -209,7 +222,7 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict
         }
     }
     // zero the pad columns once per (head, d) row
-    if (blockIdx.x == 0 && !remote) {
+    if (bx == 0 && !remote) {
         for (int q = threadIdx.x; q < hd * (n_pad - map.n_total); q += 256) {
             const int dd = q / (n_pad - map.n_total), p = map.n_total + q % (n_pad - map.n_total);
             ((uint16_t*)Vt)[((size_t)h * hd + dd) * n_pad + p] = 0;
@@ -218,12 +231,12 @@ __global__ __launch_bounds__(256) void v_transpose_kernel(const bf16* __restrict
 }
 
 // peer q/k rows -> head-major operands at the remote positions (16-byte chunk copies)
-__global__ __launch_bounds__(256) void peer_qk_kernel(const bf16* __restrict__ pq, const bf16* __restrict__ pk,
-                                                      bf16* __restrict__ Q, bf16* __restrict__ K, int h_local, int hd, TokenMap map) {
+__device__ __forceinline__ void peer_qk_part(int bid, int nblk, const bf16* __restrict__ pq, const bf16* __restrict__ pk,
+                                             bf16* __restrict__ Q, bf16* __restrict__ K, int h_local, int hd, const TokenMap& map) {
     const int cpr = hd / 8;
     const int n_rem = map.n_total - map.n_local;
     const long total = 2L * h_local * n_rem * cpr;
-    for (long q = (long)blockIdx.x * 256 + threadIdx.x; q < total; q += (long)gridDim.x * 256) {
+    for (long q = (long)bid * 256 + threadIdx.x; q < total; q += (long)nblk * 256) {
         const int c = q % cpr;
         long rest = q / cpr;
         const int i = rest % n_rem; rest /= n_rem;
@@ -232,6 +245,45 @@ __global__ __launch_bounds__(256) void peer_qk_kernel(const bf16* __restrict__ p
         const bf16* s = (tns ? pk : pq) + ((size_t)h * n_rem + i) * hd + c * 8;
         bf16* d = (tns ? K : Q) + ((size_t)h * map.n_total + remote_pos(map, i)) * hd + c * 8;
         *(uint4*)d = *(const uint4*)s;
+    }
+}
+
+// Everything between the QKV projection and attention in ONE launch: per part (one per stream)
+// the q/k RMSNorm + head-major relayout and the transposition of the own heads' v, then the peer
+// rows (q, k copied, v transposed).  Workgroups are dealt to the sub-tasks by index range.
+struct PreAttnArgs {
+    RelayoutArgs part[2];
+    int n_parts;
+    const bf16 *peer_q, *peer_k, *peer_v;      // may be NULL (sp_degree 1, or projection-only use)
+    int seg[7];                                // end of each segment: qk0, vt0, qk1, vt1, peer_qk, peer_vt (, total)
+};
+
+__global__ __launch_bounds__(256) void pre_attention_kernel(PreAttnArgs a) {
+    __shared__ uint16_t tile[64 * (128 + 2)];
+    const int b = blockIdx.x;
+    int lo = 0;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        if (p >= a.n_parts) break;
+        const RelayoutArgs& r = a.part[p];
+        if (b < a.seg[2 * p]) { qk_relayout_part(r, b - lo, a.seg[2 * p] - lo); return; }
+        lo = a.seg[2 * p];
+        if (b < a.seg[2 * p + 1]) {
+            const int nbx = (r.rows + 63) / 64, i = b - lo;
+            v_transpose_part(tile, i % nbx, i / nbx, r.src + r.col_v + (size_t)r.h0 * r.hd, (long)r.hd, (long)r.ld, r.rows,
+                             r.row0, r.Vt, r.hd, r.n_pad, r.map, 0);
+            return;
+        }
+        lo = a.seg[2 * p + 1];
+    }
+    const RelayoutArgs& r0 = a.part[0];
+    const int n_rem = r0.map.n_total - r0.map.n_local;
+    if (b < a.seg[4]) { peer_qk_part(b - lo, a.seg[4] - lo, a.peer_q, a.peer_k, r0.Q, r0.K, r0.h_local, r0.hd, r0.map); return; }
+    lo = a.seg[4];
+    if (b < a.seg[5]) {
+        const int nbx = (n_rem + 63) / 64, i = b - lo;
+        v_transpose_part(tile, i % nbx, i / nbx, a.peer_v, (long)n_rem * r0.hd, (long)r0.hd, n_rem, 0, r0.Vt, r0.hd, r0.n_pad,
+                         r0.map, 1);
     }
 }
 
@@ -311,7 +363,7 @@ hipError_t modvec_launch(const WView& W, uint64_t w_off, uint64_t b_off, const f
                          int K, hipStream_t s) {
     if (n1 <= n0) return hipSuccess;
     if (K % 8) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(modvec_kernel, dim3((n1 - n0 + 3) / 4), dim3(256), 0, s, W, w_off, b_off, t, m, n0, n1, K);
+    hipLaunchKernelGGL(modvec_kernel, dim3((n1 - n0 + 4 * MV_ROWS - 1) / (4 * MV_ROWS)), dim3(256), 0, s, W, w_off, b_off, t, m, n0, n1, K);
     return hipGetLastError();
 }
 
@@ -326,35 +378,43 @@ hipError_t ln_affine_launch(const float* x, const WView& W, uint64_t w_off, uint
     return ln_dispatch<true>(x, nullptr, nullptr, W, w_off, b_off, xn, rows, d, d, s);
 }
 
-hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s) {
-    if (r.rows <= 0) return hipSuccess;
-    if (r.hd != 64 && r.hd != 128) return hipErrorInvalidValue;
-    const long n_vec = (long)r.rows * 3 * r.n_heads;
-    hipLaunchKernelGGL(qk_relayout_kernel, dim3(grid_for(n_vec, 256 / (r.hd / 8))), dim3(256), 0, s, r);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    if (r.col_v >= 0 && r.Vt) {
-        // own heads of v, transposed
-        hipLaunchKernelGGL(v_transpose_kernel, dim3((r.rows + 63) / 64, r.h_local), dim3(256), 0, s,
-                           r.src + r.col_v + (size_t)r.h0 * r.hd, (long)r.hd, (long)r.ld, r.rows, r.row0, r.Vt, r.hd,
-                           r.n_pad, r.map, 0);
-        e = hipGetLastError();
+hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf16* peer_q, const bf16* peer_k,
+                                const bf16* peer_v, hipStream_t s) {
+    if (n_parts < 1 || n_parts > 2) return hipErrorInvalidValue;
+    PreAttnArgs a{};
+    a.n_parts = n_parts;
+    a.peer_q = peer_q; a.peer_k = peer_k; a.peer_v = peer_v;
+    int end = 0;
+    for (int p = 0; p < 2; ++p) {
+        if (p < n_parts) {
+            const RelayoutArgs& r = parts[p];
+            if (r.hd != 64 && r.hd != 128) return hipErrorInvalidValue;
+            a.part[p] = r;
+            if (r.rows > 0) end += grid_for((long)r.rows * 3 * r.n_heads, 256 / (r.hd / 8));
+            a.seg[2 * p] = end;
+            if (r.rows > 0 && r.col_v >= 0 && r.Vt) end += ((r.rows + 63) / 64) * r.h_local;
+            a.seg[2 * p + 1] = end;
+        } else {
+            a.seg[2 * p] = a.seg[2 * p + 1] = end;
+        }
     }
-    return e;
-}
-
-hipError_t peer_scatter_launch(const bf16* peer_q, const bf16* peer_k, const bf16* peer_v, bf16* Q, bf16* K, bf16* Vt,
-                               int h_local, int hd, int n_pad, TokenMap map, hipStream_t s) {
-    const int n_rem = map.n_total - map.n_local;
-    if (n_rem <= 0) return hipSuccess;
-    const long total = 2L * h_local * n_rem * (hd / 8);
-    hipLaunchKernelGGL(peer_qk_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, peer_q, peer_k, Q, K, h_local, hd, map);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(v_transpose_kernel, dim3((n_rem + 63) / 64, h_local), dim3(256), 0, s, peer_v,
-                       (long)n_rem * hd, (long)hd, n_rem, 0, Vt, hd, n_pad, map, 1);
+    const RelayoutArgs& r0 = parts[0];
+    const int n_rem = r0.map.n_total - r0.map.n_local;
+    if (peer_q && peer_k && peer_v && n_rem > 0) {
+        end += grid_for(2L * r0.h_local * n_rem * (r0.hd / 8), 256);
+        a.seg[4] = end;
+        end += ((n_rem + 63) / 64) * r0.h_local;
+        a.seg[5] = end;
+    } else {
+        a.seg[4] = a.seg[5] = end;
+    }
+    a.seg[6] = end;
+    if (end == 0) return hipSuccess;
+    hipLaunchKernelGGL(pre_attention_kernel, dim3(end), dim3(256), 0, s, a);
     return hipGetLastError();
 }
+
+hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s) { return pre_attention_launch(&r, 1, nullptr, nullptr, nullptr, s); }
 
 hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, int ld, bf16* send_attn,
                               int n_heads, int h0, int h_local, int hd, TokenMap map, hipStream_t s) {

@@ -337,25 +337,22 @@ const char* gemm_check(const GemmArgs& g) {
     return nullptr;
 }
 
-// Tile shape for a launch: 0 = 256x256, 1 = 128x128, 2 = 256 tokens x 128 features.  The big tile
-// has the best arithmetic intensity but needs enough tiles to cover the 256 CUs; estimated cost =
-// rounds x tile area / relative efficiency of the shape (128x128 runs two workgroups per CU).
+// Tile shape for a launch: 0 = 256x256, 1 = 128x128.  The big tile has the best arithmetic
+// intensity but needs enough tiles to cover the 256 CUs; estimated cost = rounds x tile area /
+// relative efficiency of the shape (128x128 runs two workgroups per CU).  A 256-token x 128-feature
+// tile looked better than 128x128 with operands hot in the last-level cache but was the slowest of
+// the three inside a block, where every weight byte is read once, cold; it is not built.
 int gemm_tile(const GemmArgs& g) {
     const long m256 = (g.M + 255) / 256, m128 = (g.M + 127) / 128;
     const long n = g.n1 - g.n0, n256 = (n + 255) / 256, n128 = (n + 127) / 128;
     auto rounds = [](long tiles, long slots) { return (double)((tiles + slots - 1) / slots); };
     const double c256 = rounds(m256 * n256, 256) * 1.0;
     const double c128 = rounds(m128 * n128, 512) * 2.0 * 0.25 / 0.65;
-    const double c2x1 = rounds(m256 * n128, 256) * 0.5 / 0.80;
-    if (c256 <= c128 && c256 <= c2x1) return 0;
-    return c2x1 <= c128 ? 2 : 1;
+    return c256 <= c128 ? 0 : 1;
 }
 
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     const int t = gemm_tile(g);
-    if (g.epi == EPI_SPLIT_GELU)
-        return t == 0 ? launch<256, 256, EPI_SPLIT_GELU>(g, s)
-                      : (t == 2 ? launch<256, 128, EPI_SPLIT_GELU>(g, s) : launch<128, 128, EPI_SPLIT_GELU>(g, s));
-    return t == 0 ? launch<256, 256, EPI_GATE_RESID>(g, s)
-                  : (t == 2 ? launch<256, 128, EPI_GATE_RESID>(g, s) : launch<128, 128, EPI_GATE_RESID>(g, s));
+    if (g.epi == EPI_SPLIT_GELU) return t == 0 ? launch<256, 256, EPI_SPLIT_GELU>(g, s) : launch<128, 128, EPI_SPLIT_GELU>(g, s);
+    return t == 0 ? launch<256, 256, EPI_GATE_RESID>(g, s) : launch<128, 128, EPI_GATE_RESID>(g, s);
 }

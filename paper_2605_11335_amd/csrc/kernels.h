@@ -23,7 +23,7 @@ struct GemmArgs {
     const float* resid; const float* gate; float* y; int ldy;
 };
 const char* gemm_check(const GemmArgs& g);
-int gemm_tile(const GemmArgs& g);      // tile gemm_launch will use: 0 = 256x256, 1 = 128x128, 2 = 256x128
+int gemm_tile(const GemmArgs& g);      // tile gemm_launch will use: 0 = 256x256, 1 = 128x128
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s);
 
 // Positions of this rank's tokens in the joint sequence: up to two contiguous segments
@@ -72,10 +72,11 @@ struct RelayoutArgs {
 };
 hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s);
 
-// Peer rows (what the exchange delivers) into the head-major operands at the remote positions.
-hipError_t peer_scatter_launch(const bf16* peer_q, const bf16* peer_k, const bf16* peer_v,
-                               bf16* Q, bf16* K, bf16* Vt, int h_local, int hd, int n_pad,
-                               TokenMap map, hipStream_t s);
+// One launch for everything between the QKV projection and attention: the relayout of up to two
+// parts (one per stream) and, when given, the peer rows (what the exchange delivers) placed at the
+// remote positions of parts[0]'s operands (q, k copied; v transposed).
+hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf16* peer_q, const bf16* peer_k,
+                                const bf16* peer_v, hipStream_t s);
 
 // After attention on the full sequence: local rows of the local heads and peer_attn (other heads)
 // into the [n_local, ld] operand of the output projection; remote rows into send_attn.

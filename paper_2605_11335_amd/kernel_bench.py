@@ -7,7 +7,9 @@ device-to-device copy of known size, used to calibrate hardware byte counters.
     python -m paper_2605_11335_amd.kernel_bench copy 536870912 [iters]      # bytes
 
 Timing uses events on the current stream; inputs are seeded N(0,1) activations and N(0,0.02)
-weights in bf16.
+weights in bf16.  The GEMM benchmarks rotate over enough operand sets that consecutive launches
+never find their operands in the 256 MB last-level cache: inside a block every weight byte is read
+once per step, cold, and tile shapes rank differently hot and cold.
 """
 from __future__ import annotations
 
@@ -39,17 +41,24 @@ def main(argv):
     torch.manual_seed(0)
     if which in ("linear", "linear_residual"):
         M, N, K = (int(v) for v in shape.split("x"))
-        A = torch.randn(M, K, device=DEV).to(torch.bfloat16)
-        W = (torch.randn(N, K, device=DEV) * 0.02).to(torch.bfloat16)
+        sets = max(2, -(-(1 << 30) // (2 * K * (M + N))))        # operands of all sets together > 1 GiB
+        A = [torch.randn(M, K, device=DEV).to(torch.bfloat16) for _ in range(sets)]
+        W = [(torch.randn(N, K, device=DEV) * 0.02).to(torch.bfloat16) for _ in range(sets)]
+        turn = [0]
+
+        def nxt():
+            turn[0] = (turn[0] + 1) % sets
+            return turn[0]
+
         if which == "linear":
             out = torch.empty(M, N, dtype=torch.bfloat16, device=DEV)
-            ms = timeit(lambda: B.cf_op_linear(A, W, 0, -1, M, N, K, out), iters)
+            ms = timeit(lambda: B.cf_op_linear(A[nxt()], W[turn[0]], 0, -1, M, N, K, out), iters)
         else:
             resid = torch.randn(M, N, device=DEV)
             gate = torch.randn(N, device=DEV)
             y = torch.empty(M, N, device=DEV)
-            ms = timeit(lambda: B.cf_op_linear_residual(A, W, 0, -1, M, N, K, resid, gate, y), iters)
-        print(f"{which} {M}x{N}x{K}: {ms:.4f} ms  {2 * M * N * K / ms / 1e9:.1f} TFLOP/s")
+            ms = timeit(lambda: B.cf_op_linear_residual(A[nxt()], W[turn[0]], 0, -1, M, N, K, resid, gate, y), iters)
+        print(f"{which} {M}x{N}x{K} ({sets} operand sets in turn): {ms:.4f} ms  {2 * M * N * K / ms / 1e9:.1f} TFLOP/s")
     elif which == "attention":
         H, N, hd = (int(v) for v in shape.split("x"))
         npad = (N + 63) // 64 * 64

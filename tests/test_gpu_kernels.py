@@ -198,8 +198,8 @@ def test_attention_every_workgroup_height(H, n, hd):
     assert rel_l2(got, ref) < 6e-3 and max_abs(got, ref) < 2e-2 * max(1.0, np.abs(ref).max())
 
 
-def test_linear_rectangular_tile_shapes():
-    """Shapes that make the launcher pick the 256x128 tile (both epilogues), with ragged edges."""
+def test_linear_under_one_round_of_tiles():
+    """A grid that covers the chip less than once (both epilogues), with a ragged feature edge."""
     rng = np.random.default_rng(21)
     M, N, K = 2304, 3080, 256
     a, ab = bf16_round(rng.normal(size=(M, K)))
