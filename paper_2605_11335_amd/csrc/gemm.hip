@@ -38,6 +38,16 @@ __device__ __forceinline__ void lds_load16(const void* gptr, void* lds) {
                                      (void __attribute__((address_space(3)))*)lds, 16, 0, 0);
 }
 
+// The same through a buffer resource: the address is base + voff (per lane) + soff (uniform), and
+// lanes whose offset lies past the resource's size fetch zeros, which takes care of ragged tile
+// edges.  The memory pipeline takes these a little faster than loads with a 64-bit address per lane.
+__device__ __forceinline__ void lds_bload16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t soff, void* lds) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void __attribute__((address_space(3)))*)lds, 16, voff, soff, 0, 0);
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint64_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)(bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes), 0x00020000);
+}
+
 // Slab hand-over: this wave's global->LDS loads (the next slab) have landed and its LDS reads
 // (the last fragments of the current slab) have returned; after the barrier that holds for the
 // whole workgroup, so the next slab may be read and the current one overwritten.
@@ -80,25 +90,27 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // wave's 64 x 16 bytes to consecutive LDS addresses, i.e. RPL rows; which 16-byte chunk of
     // its row a lane fetches is chosen so that the chunk lands in its swizzled slot.
     const int uw = __builtin_amdgcn_readfirstlane(wave);
-    const char* a_ptr[A_LOADS];
-    const char* w_ptr[W_LOADS];      // fast path: the row's bytes all live in one buffer
-    uint64_t w_src[W_LOADS];         // blob offsets, for the tile that holds the resident/streamed split
+    uint32_t a_voff[A_LOADS], w_voff[W_LOADS];   // byte offsets from the tile's first row
+    uint64_t w_src[W_LOADS];                     // blob offsets, for the tile that holds the resident/streamed split
 #pragma unroll
     for (int j = 0; j < A_LOADS; ++j) {
         const int row = (j * 4 + uw) * RPL + lane / CHUNKS;
         const int c = (lane % CHUNKS) ^ swz(row);
-        a_ptr[j] = (const char*)(g.A + (size_t)min(m0 + row, g.M - 1) * g.lda + c * 8);
+        a_voff[j] = (uint32_t)row * (uint32_t)g.lda * 2u + c * 16;
     }
 #pragma unroll
     for (int j = 0; j < W_LOADS; ++j) {
         const int row = (j * 4 + uw) * RPL + lane / CHUNKS;
         const int c = (lane % CHUNKS) ^ swz(row);
+        w_voff[j] = (uint32_t)row * (uint32_t)g.K * 2u + c * 16;
         w_src[j] = g.w_off + ((uint64_t)min(n0 + row, g.N - 1) * g.K + c * 8) * 2;
-        w_ptr[j] = wv_ptr(g.W, w_src[j]);
     }
     // does the byte where the blob switches buffers fall inside this tile's weight rows?
     const uint64_t t_begin = g.w_off + (uint64_t)n0 * g.K * 2, t_end = g.w_off + (uint64_t)min(n0 + BN, g.N) * g.K * 2;
     const bool straddle = g.W.split > t_begin && g.W.split < t_end;
+    // resources that end with the tile's last valid row: the rows of a ragged tile beyond it read zeros
+    const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(g.A + (size_t)m0 * g.lda, ((uint64_t)(g.M - 1 - m0) * g.lda + g.K) * 2);
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wv_ptr(g.W, t_begin), t_end - t_begin);
 
     floatx16 acc[NT][MT];
 #pragma unroll
@@ -124,19 +136,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
         char* dA = sA + st * A_STAGE + uw * 1024;
         char* dW = sW + st * W_STAGE + uw * 1024;
 #pragma unroll
-        for (int j = 0; j < A_LOADS; ++j) lds_load16(a_ptr[j] + k0, dA + j * 4096);
+        for (int j = 0; j < A_LOADS; ++j) lds_bload16(a_rsrc, a_voff[j], k0, dA + j * 4096);
 #pragma unroll
-        for (int j = 0; j < W_LOADS; ++j)
-            lds_load16(decltype(slow)::value ? wv_ptr(g.W, w_src[j] + k0) : w_ptr[j] + k0, dW + j * 4096);
+        for (int j = 0; j < W_LOADS; ++j) {
+            if (decltype(slow)::value) lds_load16(wv_ptr(g.W, w_src[j] + k0), dW + j * 4096);
+            else lds_bload16(w_rsrc, w_voff[j], k0, dW + j * 4096);
+        }
     };
     auto issue_one = [&](auto slow, int kt_, int q) {        // q-th load of slab kt_ (A loads first)
         const int k0 = kt_ * BK * 2, st = kt_ & 1;
         if (q < A_LOADS) {
-            lds_load16(a_ptr[q] + k0, sA + st * A_STAGE + uw * 1024 + q * 4096);
+            lds_bload16(a_rsrc, a_voff[q], k0, sA + st * A_STAGE + uw * 1024 + q * 4096);
         } else if (q < A_LOADS + W_LOADS) {
             const int j = q - A_LOADS;
-            lds_load16(decltype(slow)::value ? wv_ptr(g.W, w_src[j] + k0) : w_ptr[j] + k0,
-                       sW + st * W_STAGE + uw * 1024 + j * 4096);
+            if (decltype(slow)::value) lds_load16(wv_ptr(g.W, w_src[j] + k0), sW + st * W_STAGE + uw * 1024 + j * 4096);
+            else lds_bload16(w_rsrc, w_voff[j], k0, sW + st * W_STAGE + uw * 1024 + j * 4096);
         }
     };
     auto load_frags = [&](int buf, const char* cA, const char* cW, int kk) {
@@ -321,6 +335,7 @@ const char* gemm_check(const GemmArgs& g) {
     if (g.N % 8) return "gemm: N must be a multiple of 8";
     if (g.n0 < 0 || g.n1 > g.N || g.n0 >= g.n1 || (g.n0 % 8) || (g.n1 % 8)) return "gemm: bad feature panel";
     if (g.lda < g.K || (g.lda % 8)) return "gemm: lda must be >= K and a multiple of 8";
+    if ((uint64_t)g.lda * 512 >= (1ull << 32)) return "gemm: lda too large for 32-bit offsets inside a tile";
     if ((g.w_off % 16) || (g.has_bias && (g.bias_off % 16))) return "gemm: weight/bias offsets must be 16-byte aligned";
     if (((uintptr_t)g.A) % 16) return "gemm: A must be 16-byte aligned";
     if (g.epi == EPI_SPLIT_GELU) {
