@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="flux", choices=["toy", "flux", "wan", "hunyuan"])
+    ap.add_argument("--config", default="flux", choices=["toy", "flux", "wan", "hunyuan", "flux_mm", "toy_mm"])
     ap.add_argument("--blocks", type=int, default=0, help="override the number of blocks (0 = the config's)")
     ap.add_argument("--resident", type=float, default=0.0, help="resident fraction of the offloaded arm")
     ap.add_argument("--chunk-mib", type=float, default=0.0, help="chunk size in MiB (0 = the config's chunk count)")
@@ -75,24 +75,35 @@ def main():
     from paper_2605_11335_amd.runner import BlockRunner, chunk_bytes_for
 
     cfg = wl.CONFIGS[args.config]
+    if cfg.n_double and cfg.n_blocks > 12 and not args.blocks:
+        args.blocks = 6          # the full MMDiT stack holds 24 GB of distinct seeded weights; keep its 1:2 mix
     if args.blocks:
-        cfg = cfg.with_(n_blocks=args.blocks)
+        # a mixed stack keeps its proportion of double-stream blocks
+        cfg = cfg.with_(n_blocks=args.blocks,
+                        n_double=(max(1, round(args.blocks * cfg.n_double / cfg.n_blocks)) if cfg.n_double else 0))
     L = cfg.n_blocks
     chunk_bytes = int(args.chunk_mib * (1 << 20)) if args.chunk_mib else chunk_bytes_for(cfg)
 
     t_setup = time.perf_counter()
     run = BlockRunner(cfg, chunk_bytes=chunk_bytes)
     for b in range(L):
-        run.register_params(b, wl.gen_block_params(cfg, b))
-    # chained residual stream: block l writes the buffer block l+1 reads
-    tens = [run.make_io(wl.gen_block_inputs(cfg, b)) for b in range(L)]
-    for b in range(1, L):
-        tens[b]["x"] = tens[b - 1]["y"]
-        if "x_txt" in tens[b]:
-            tens[b]["x_txt"] = tens[b - 1]["y_txt"]
+        run.register_params(b, wl.gen_block_params(cfg.block_cfg(b), b))
+    # chained residual stream: block l writes the buffer block l+1 reads; the rows are this rank's
+    # text rows followed by its image rows, which a double-stream block sees as two tensors
+    tens = [run.make_io(wl.gen_block_inputs(cfg.block_cfg(b), b)) for b in range(L)]
+    tl = cfg.n_txt_local
+    bufs = [torch.randn((cfg.n_local, cfg.d), device=run.device).to(torch.bfloat16).float() for _ in range(L + 1)]
+    for b in range(L):
+        if cfg.kind_of(b) == wl.KIND_DOUBLE:
+            tens[b]["x_txt"], tens[b]["x"] = bufs[b][:tl], bufs[b][tl:]
+            tens[b]["y_txt"], tens[b]["y"] = bufs[b + 1][:tl], bufs[b + 1][tl:]
+        else:
+            tens[b]["x"], tens[b]["y"] = bufs[b], bufs[b + 1]
     ios = [run.io_struct(t) for t in tens]
-    print(f"[bench] {cfg.name}: {L} blocks, blob {run.blob_bytes/1e6:.1f} MB, {run.n_chunks} chunks of "
-          f"{chunk_bytes/1e6:.2f} MB, setup {time.perf_counter()-t_setup:.1f}s", file=sys.stderr)
+    blob_total = run.total_blob_bytes                      # weight bytes of the whole stack
+    print(f"[bench] {cfg.name}: {L} blocks, blobs {blob_total/1e6:.1f} MB in all, chunks of "
+          f"{chunk_bytes/1e6:.2f} MB ({[run.ctx.cf_n_chunks(b) for b in range(L)]} per block), "
+          f"setup {time.perf_counter()-t_setup:.1f}s", file=sys.stderr)
 
     comm_host = None
     def set_contention(mode):
@@ -151,8 +162,11 @@ def main():
         off_prof_ms, _, _ = arm(args.resident, args.steps, args.warmup)
         kt_off = run.ctx.cf_kernel_times()
         run.ctx.cf_set_profiling(False)
-        h2d_per_step = L * (run.blob_bytes - st["resident_bytes"])
-        assert st["h2d_bytes"] == (total_steps * L + 1) * (run.blob_bytes - st["resident_bytes"]), "I/O volume changed"
+        h2d_per_step = st["model_blob_bytes"] - st["model_resident_bytes"]
+        # the drain block's streamed bytes: all but its leading round(r * n_chunks) chunks
+        n_res0 = int(np.floor(args.resident * run.ctx.cf_n_chunks(0) + 0.5))
+        first = run.blob_bytes_of[0] - min(run.blob_bytes_of[0], n_res0 * chunk_bytes)
+        assert st["h2d_bytes"] == total_steps * h2d_per_step + first, "I/O volume changed"
         h2d_gbs = h2d_per_step / (off_ms * 1e-3) / 1e9
     else:
         h2d_per_step, h2d_gbs = 0, 0.0
@@ -172,11 +186,12 @@ def main():
         "value": value, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": value, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {L} blocks, d={cfg.d}, H={cfg.n_heads}x{cfg.head_dim}, f={cfg.f}, "
+        "config": {"workload": f"{cfg.name}: {L} blocks" + (f" ({cfg.n_double} double-stream + {L - cfg.n_double} single-stream)" if cfg.n_double else "") + f", d={cfg.d}, H={cfg.n_heads}x{cfg.head_dim}, f={cfg.f}, "
                                f"N={cfg.n_total}, Ulysses P={cfg.sp_degree} share (GEMMs on {cfg.n_local} tokens, "
                                f"attention {cfg.h_local} heads over {cfg.n_total})",
                    "arm": "chunked offload" if do_off else "resident",
                    "chunk_bytes": chunk_bytes, "chunks_per_block": run.n_chunks, "blob_bytes": run.blob_bytes,
+                   "blob_bytes_all_blocks": blob_total,
                    "resident_fraction": actual_r if do_off else 1.0, "contention": args.contention},
         "offload_ms": off_ms, "resident_ms": res_ms,
         "offload_over_resident": (off_ms / res_ms) if (do_res and do_off) else None,
@@ -185,7 +200,7 @@ def main():
         "h2d_gbs": h2d_gbs, "h2d_frac_link_peak": h2d_gbs / PEAK_LINK_GBS,
         "h2d_bytes_per_step": h2d_per_step,
         "exposed_prefetch_ms": (off_ms - res_ms) if (do_res and do_off) else None,
-        "weight_memory_bytes": st["weight_memory_bytes"] if st else L * run.blob_bytes,
+        "weight_memory_bytes": st["weight_memory_bytes"] if st else blob_total,
         "roofline": {"bound": "mfma", "kernel": dom["name"], "arm": arm_name,
                      "achieved": dom_flops / dom_ms / 1e9,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom_flops / dom_ms / 1e9 / PEAK_BF16_TFLOPS,
@@ -195,7 +210,7 @@ def main():
     }
 
     # ---- overlap-model view of this machine (Eq. 1-4 with the measured eta's)
-    blob = run.blob_bytes
+    blob = blob_total / L                 # per block, averaged over the stack (App. B, block-averaged)
     t_comp_blk = (res_ms if do_res else off_ms) / L
     t_pref_blk = (blob / (h2d_gbs * 1e9) * 1e3) if h2d_gbs > 0 else None
     result["model"] = {"t_comp_block_ms": t_comp_blk, "t_pref_block_ms": t_pref_blk,
@@ -216,13 +231,13 @@ def main():
                 if r == 1.0:
                     base_ms = ms
             if mode == "off":
-                link = L * run.blob_bytes / (pts[-1][1] * 1e-3)
+                link = blob_total / (pts[-1][1] * 1e-3)
             for r, ms, act, s2 in reversed(pts):
                 # first-order prediction (Eq. 1-3 applied per block): max(compute window, prefetch time)
-                pred = L * max(base_ms / L, (1.0 - act) * run.blob_bytes / link * 1e3)
+                pred = L * max(base_ms / L, (1.0 - act) * blob_total / L / link * 1e3)
                 grid.append({"contention": mode, "r": r, "actual_r": act, "step_ms": ms, "model_step_ms": pred,
                              "weight_memory_bytes": s2["weight_memory_bytes"],
-                             "h2d_gbs": L * (run.blob_bytes - s2["resident_bytes"]) / (ms * 1e-3) / 1e9,
+                             "h2d_gbs": (s2["model_blob_bytes"] - s2["model_resident_bytes"]) / (ms * 1e-3) / 1e9,
                              "pauses": s2["pauses"]})
                 print("[sweep] " + json.dumps(grid[-1]), file=sys.stderr)
         set_contention("off")
@@ -232,20 +247,23 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import block as ob
         import threadpoolctl
-        params, inputs = wl.gen_block_params(cfg, 0), wl.gen_block_inputs(cfg, 0)
         rows = None
-        sample = "1 full block"
+        sample = "1 full block of each kind"
         if cfg.n_total > 8192:                    # exact row sample: attention would take hours
             rng = np.random.default_rng(1)
             rows = np.sort(rng.choice(cfg.n_local, 256, replace=False))
             sample = "256 of %d local rows of 1 block (all keys), scaled by rows" % cfg.n_local
-        t0 = time.perf_counter()
-        ob.block_forward(cfg, params, inputs, rows=rows, send_rows=(None if rows is None else np.arange(0)))
-        dt = time.perf_counter() - t0
         scale = 1.0 if rows is None else cfg.n_local / 256.0
+        total = 0.0
+        for b in sorted({cfg.kinds.index(k) for k in set(cfg.kinds)}):      # first block of each kind
+            cb = cfg.block_cfg(b)
+            params, inputs = wl.gen_block_params(cb, b), wl.gen_block_inputs(cb, b)
+            t0 = time.perf_counter()
+            ob.block_forward(cb, params, inputs, rows=rows, send_rows=(None if rows is None else np.arange(0)))
+            total += (time.perf_counter() - t0) * cfg.kinds.count(cb.kind)
         threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
-        result["cpu_baseline"] = {"value": dt * 1e3 * L * scale, "unit": "ms", "cores": threads, "kind": "oracle",
-                                  "sample": f"{sample}, float64 NumPy, x{L} blocks per step"
+        result["cpu_baseline"] = {"value": total * 1e3 * scale, "unit": "ms", "cores": threads, "kind": "oracle",
+                                  "sample": f"{sample}, float64 NumPy, times the number of blocks of that kind per step"
                                             + ("" if rows is None else " (linear extrapolation)")}
     run.close()
     print(json.dumps(result))

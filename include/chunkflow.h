@@ -59,7 +59,7 @@ typedef struct {
     int32_t n_total;         /* N */
     int32_t sp_degree;       /* P; divides n_heads, n_total (and n_txt_total) */
     int32_t sp_rank;
-    int32_t n_txt_total;     /* CF_DOUBLE_STREAM: text tokens in the joint sequence, else 0 */
+    int32_t n_txt_total;     /* text tokens leading the joint sequence (double-stream and mixed models), else 0 */
     int32_t l_ctx;           /* CF_DIT_CROSS: context length, else 0 */
     int32_t qk_rmsnorm;      /* per-head RMSNorm on q and k (learned weight, eps 1e-6) */
     uint64_t chunk_bytes;    /* C of Sec. 3.2; multiple of 256 */
@@ -98,12 +98,14 @@ typedef struct {
 typedef struct {
     uint64_t h2d_bytes;          /* bytes copied by chunked_prefetch_begin since the last reset   */
     uint64_t h2d_chunks;
-    uint64_t resident_bytes;     /* per block */
+    uint64_t resident_bytes;     /* per block (mixed-kind model: mean over its blocks, rounded down) */
     uint64_t blob_bytes;
     uint64_t weight_memory_bytes;/* device bytes held for weights: resident buffers + 2 slots     */
     uint64_t comm_bytes_h2d;     /* emulated collective traffic                                   */
     uint64_t comm_bytes_d2h;
     uint64_t pauses;             /* chunk launches that were made to wait for a collective        */
+    uint64_t model_resident_bytes;/* resident bytes summed over all blocks                          */
+    uint64_t model_blob_bytes;   /* blob bytes summed over all blocks                              */
 } cf_stats_t;
 
 /* Per-kernel timing collected while profiling is on (cf_set_profiling). */
@@ -120,11 +122,24 @@ typedef struct {
 int cf_create(const cf_model_desc* desc, cf_ctx** out);
 int cf_destroy(cf_ctx* ctx);                                   /* syncs, frees everything it owns */
 const char* cf_last_error(const cf_ctx* ctx);                  /* ctx may be NULL: last create error */
-int cf_blob_bytes(const cf_ctx* ctx, uint64_t* out);
+int cf_blob_bytes(const cf_ctx* ctx, uint64_t* out);            /* of block 0; every block's in a one-kind model */
 int cf_n_chunks(const cf_ctx* ctx, int32_t* out);
 /* tensors in blob order; *n is capacity on entry, count on return (call with out=NULL to query) */
 int cf_blob_layout(const cf_ctx* ctx, cf_tensor_slot* out, int32_t* n);
-int cf_workspace_bytes(const cf_ctx* ctx, uint64_t* out);
+int cf_workspace_bytes(const cf_ctx* ctx, uint64_t* out);      /* enough for every kind in the model */
+/* A model that mixes block kinds (App. B: MMDiT = double-stream blocks followed by single-stream
+ * blocks over the concatenated text+image sequence): kinds[b] is the cf_block_kind of block b,
+ * n must equal n_blocks.  Call right after cf_create, before any block is registered.  Each kind
+ * has its own blob layout and chunk count (same chunk_bytes); the two staging slots are sized for
+ * the kind with the most streamed bytes; set_resident_fraction keeps the leading
+ * round(r * n_chunks(kind)) chunks of every block.  With n_txt_total > 0 a single-stream block's
+ * rows are this rank's text rows followed by its image rows, at the joint positions the
+ * double-stream blocks use, so x_txt/x of one kind and x of the other can alias one buffer. */
+int cf_set_block_kinds(cf_ctx* ctx, const int32_t* kinds, int32_t n);
+int cf_block_kind_of(const cf_ctx* ctx, int32_t block, int32_t* out);
+int cf_blob_bytes_of(const cf_ctx* ctx, int32_t block, uint64_t* out);
+int cf_n_chunks_of(const cf_ctx* ctx, int32_t block, int32_t* out);
+int cf_blob_layout_of(const cf_ctx* ctx, int32_t block, cf_tensor_slot* out, int32_t* n);
 /* Host-only view of how dit_block_fwd cuts weight matrix `tensor` into panels of output features
  * when the first n_resident_chunks chunks are resident (Sec. 3.2/3.3): panel i covers rows
  * [row0[i], row1[i]) and may run once chunk wait_chunk[i] has landed (-1: no streamed chunk

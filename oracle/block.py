@@ -134,9 +134,11 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, mc: Optional[MacCount
 
 def local_positions(cfg) -> np.ndarray:
     """Positions in the joint sequence of this rank's tokens: contiguous split per stream,
-    text rows before image rows in the joint order of a double-stream block."""
+    text rows before image rows in the joint order.  That order is the double-stream block's and,
+    in an MMDiT stack (App. B), also that of the single-stream blocks that follow it on the
+    concatenated sequence."""
     r, p = cfg.sp_rank, cfg.sp_degree
-    if cfg.kind == KIND_DOUBLE:
+    if cfg.n_txt > 0:
         tl = cfg.n_txt // p
         il = cfg.n_total // p - tl
         return np.concatenate([np.arange(r * tl, (r + 1) * tl),

@@ -41,7 +41,8 @@ class cf_block_io(C.Structure):
 class cf_stats_t(C.Structure):
     _fields_ = [("h2d_bytes", C.c_uint64), ("h2d_chunks", C.c_uint64), ("resident_bytes", C.c_uint64),
                 ("blob_bytes", C.c_uint64), ("weight_memory_bytes", C.c_uint64),
-                ("comm_bytes_h2d", C.c_uint64), ("comm_bytes_d2h", C.c_uint64), ("pauses", C.c_uint64)]
+                ("comm_bytes_h2d", C.c_uint64), ("comm_bytes_d2h", C.c_uint64), ("pauses", C.c_uint64),
+                ("model_resident_bytes", C.c_uint64), ("model_blob_bytes", C.c_uint64)]
 
 
 class cf_kernel_time(C.Structure):
@@ -51,6 +52,7 @@ class cf_kernel_time(C.Structure):
 
 #: every symbol include/chunkflow.h declares
 EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_chunks", "cf_blob_layout",
+           "cf_set_block_kinds", "cf_block_kind_of", "cf_blob_bytes_of", "cf_n_chunks_of", "cf_blob_layout_of",
            "cf_workspace_bytes", "cf_plan_panels", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
            "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
            "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling",
@@ -87,6 +89,11 @@ def lib() -> C.CDLL:
         _lib.cf_plan_panels.argtypes = [C.c_void_p, C.c_char_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(C.c_int32)]
         _lib.cf_register_block.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64]
+        _lib.cf_set_block_kinds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
+        _lib.cf_block_kind_of.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        _lib.cf_blob_bytes_of.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        _lib.cf_n_chunks_of.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        _lib.cf_blob_layout_of.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         _lib.chunked_prefetch_begin.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.chunked_prefetch_wait.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib.dit_block_fwd.argtypes = [C.c_void_p, C.c_int32, C.POINTER(cf_block_io), C.c_void_p]
@@ -156,14 +163,23 @@ class Context:
             pass
 
     # ---- layout
-    def cf_blob_bytes(self) -> int:
-        v = C.c_uint64()
-        _check(lib().cf_blob_bytes(self._h, C.byref(v)), self._h)
+    def cf_set_block_kinds(self, kinds) -> None:
+        arr = (C.c_int32 * len(kinds))(*[int(k) for k in kinds])
+        _check(lib().cf_set_block_kinds(self._h, arr, len(kinds)), self._h)
+
+    def cf_block_kind_of(self, block: int) -> int:
+        v = C.c_int32()
+        _check(lib().cf_block_kind_of(self._h, block, C.byref(v)), self._h)
         return v.value
 
-    def cf_n_chunks(self) -> int:
+    def cf_blob_bytes(self, block: int = 0) -> int:
+        v = C.c_uint64()
+        _check(lib().cf_blob_bytes_of(self._h, block, C.byref(v)), self._h)
+        return v.value
+
+    def cf_n_chunks(self, block: int = 0) -> int:
         v = C.c_int32()
-        _check(lib().cf_n_chunks(self._h, C.byref(v)), self._h)
+        _check(lib().cf_n_chunks_of(self._h, block, C.byref(v)), self._h)
         return v.value
 
     def cf_workspace_bytes(self) -> int:
@@ -178,18 +194,18 @@ class Context:
         _check(lib().cf_plan_panels(self._h, tensor.encode(), granule, n_resident_chunks, r0, r1, w, C.byref(n)), self._h)
         return [(r0[i], r1[i], w[i]) for i in range(n.value)]
 
-    def cf_blob_layout(self) -> List[dict]:
+    def cf_blob_layout(self, block: int = 0) -> List[dict]:
         n = C.c_int32(0)
-        _check(lib().cf_blob_layout(self._h, None, C.byref(n)), self._h)
+        _check(lib().cf_blob_layout_of(self._h, block, None, C.byref(n)), self._h)
         arr = (cf_tensor_slot * n.value)()
-        _check(lib().cf_blob_layout(self._h, arr, C.byref(n)), self._h)
+        _check(lib().cf_blob_layout_of(self._h, block, arr, C.byref(n)), self._h)
         return [dict(name=a.name.decode(), offset=a.offset, rows=a.rows, cols=a.cols) for a in arr]
 
-    def pack_blob(self, params: Dict[str, np.ndarray], out: np.ndarray) -> None:
+    def pack_blob(self, params: Dict[str, np.ndarray], out: np.ndarray, block: int = 0) -> None:
         """Place named bf16 tensors (uint16 bit patterns) at the library's offsets; pad is zero."""
-        assert out.dtype == np.uint8 and out.size == self.cf_blob_bytes()
+        assert out.dtype == np.uint8 and out.size == self.cf_blob_bytes(block)
         out[:] = 0
-        for t in self.cf_blob_layout():
+        for t in self.cf_blob_layout(block):
             a = np.ascontiguousarray(params[t["name"]], dtype=np.uint16).reshape(-1)
             assert a.size == t["rows"] * t["cols"], t["name"]
             out[t["offset"]:t["offset"] + 2 * a.size] = a.view(np.uint8)
@@ -228,12 +244,12 @@ class Context:
         _check(lib().cf_comm_end(self._h, _stream_handle(comm_stream), _stream_handle(compute_stream)), self._h)
 
     def cf_checksum_block(self, block: int, stream=None) -> List[int]:
-        out = (C.c_uint64 * self.cf_n_chunks())()
+        out = (C.c_uint64 * self.cf_n_chunks(block))()
         _check(lib().cf_checksum_block(self._h, block, out, _stream_handle(stream)), self._h)
         return list(out)
 
     def cf_read_block(self, block: int, stream=None) -> np.ndarray:
-        out = np.empty(self.cf_blob_bytes(), dtype=np.uint8)
+        out = np.empty(self.cf_blob_bytes(block), dtype=np.uint8)
         _check(lib().cf_read_block(self._h, block, out.ctypes.data, _stream_handle(stream)), self._h)
         return out
 

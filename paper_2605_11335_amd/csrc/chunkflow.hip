@@ -40,18 +40,17 @@ inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 // blob layout: tensors in the order the block consumes them (small vectors ahead of the matrix
 // that needs them), each 256-byte aligned, so a prefix of chunks is a prefix of the computation
 // ------------------------------------------------------------------------------------------
-void add_tensor(cf_ctx* c, const std::string& name, uint32_t rows, uint32_t cols) {
+void add_tensor(Plan* c, const std::string& name, uint32_t rows, uint32_t cols) {
     TensorDesc t{name, align_up(c->blob_bytes, 256), rows, cols};
     c->blob_bytes = t.off + t.bytes();
     c->tensors.push_back(t);
 }
 
-void plan_layout(cf_ctx* c) {
-    const cf_model_desc& m = c->d;
+void plan_layout(Plan* c, const cf_model_desc& m, int kind, uint64_t chunk_bytes) {
     const uint32_t d = m.d, f = m.f, hd = m.head_dim;
-    c->tensors.clear();
-    c->blob_bytes = 0;
-    if (m.kind == CF_SINGLE_STREAM) {
+    *c = Plan{};
+    c->kind = kind;
+    if (kind == CF_SINGLE_STREAM) {
         add_tensor(c, "b_mod", 1, 3 * d);
         add_tensor(c, "w_mod", 3 * d, d);
         add_tensor(c, "b1", 1, 3 * d + f);
@@ -59,7 +58,7 @@ void plan_layout(cf_ctx* c) {
         add_tensor(c, "w1", 3 * d + f, d);
         add_tensor(c, "b2", 1, d);
         add_tensor(c, "w2", d, d + f);
-    } else if (m.kind == CF_DIT_CROSS) {
+    } else if (kind == CF_DIT_CROSS) {
         add_tensor(c, "b_mod", 1, 6 * d);
         add_tensor(c, "w_mod", 6 * d, d);
         add_tensor(c, "b_qkv", 1, 3 * d);
@@ -98,7 +97,7 @@ void plan_layout(cf_ctx* c) {
         }
     }
     c->blob_bytes = align_up(c->blob_bytes, 256);
-    c->n_chunks = (int)((c->blob_bytes + c->chunk_bytes - 1) / c->chunk_bytes);
+    c->n_chunks = (int)((c->blob_bytes + chunk_bytes - 1) / chunk_bytes);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -118,27 +117,26 @@ struct Ws {
 
 inline int n_pad_of(int n) { return (n + 63) / 64 * 64; }
 
-Ws carve(const cf_ctx* c, char* base) {
-    const cf_model_desc& m = c->d;
+Ws carve(const cf_model_desc& m, int kind, char* base) {
     Ws w;
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { char* p = base + off; off = align_up(off + bytes, 256); return p; };
     const uint64_t nl = m.n_total / m.sp_degree, d = m.d, f = m.f, N = m.n_total, hd = m.head_dim;
     const uint64_t hl = m.n_heads / m.sp_degree;
-    const int nmod = m.kind == CF_SINGLE_STREAM ? 3 : (m.kind == CF_DIT_CROSS ? 6 : 12);
+    const int nmod = kind == CF_SINGLE_STREAM ? 3 : (kind == CF_DIT_CROSS ? 6 : 12);
     w.mod = (float*)take(4ull * nmod * d);
     w.xn = (bf16*)take(2 * nl * d);
     w.qkv = (bf16*)take(2 * nl * 3 * d);
-    w.c = (bf16*)take(2 * nl * (m.kind == CF_SINGLE_STREAM ? d + f : d));
+    w.c = (bf16*)take(2 * nl * (kind == CF_SINGLE_STREAM ? d + f : d));
     w.Q = (bf16*)take(2 * hl * N * hd);
     w.K = (bf16*)take(2 * hl * N * hd);
     w.Vt = (bf16*)take(2 * hl * hd * n_pad_of(N));
     if (m.sp_degree > 1) w.O = (bf16*)take(2 * hl * N * hd);
-    if (m.kind != CF_SINGLE_STREAM) {
+    if (kind != CF_SINGLE_STREAM) {
         w.x1 = (float*)take(4 * nl * d);
         w.up = (bf16*)take(2 * nl * f);
     }
-    if (m.kind == CF_DIT_CROSS) {
+    if (kind == CF_DIT_CROSS) {
         w.x2 = (float*)take(4 * nl * d);
         w.ckv = (bf16*)take(2ull * m.l_ctx * 2 * d);
         w.cQ = (bf16*)take(2 * nl * d);
@@ -156,7 +154,7 @@ int ensure_device(cf_ctx* c) {
     if (c->device_ready) return CF_OK;
     CF_HIP(c, hipGetDevice(&c->device));
     for (int s = 0; s < 2; ++s) {
-        c->chunk_ev[s].resize(c->n_chunks);
+        c->chunk_ev[s].resize(c->max_chunks);
         for (auto& e : c->chunk_ev[s]) CF_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
         CF_HIP(c, hipEventCreateWithFlags(&c->done_ev[s], hipEventDisableTiming));
     }
@@ -181,27 +179,28 @@ void free_weights(cf_ctx* c) {
 }
 
 int upload_resident(cf_ctx* c, int block) {
-    if (!c->res_bytes || !c->host[block]) return CF_OK;
+    const uint64_t res_bytes = c->P(block).res_bytes;
+    if (!res_bytes || !c->host[block]) return CF_OK;
     if (!c->res_buf[block]) {
-        if (hipMalloc((void**)&c->res_buf[block], c->res_bytes) != hipSuccess) {
+        if (hipMalloc((void**)&c->res_buf[block], res_bytes) != hipSuccess) {
             (void)hipGetLastError();
             return fail(c, CF_ERR_NOMEM, "hipMalloc of %llu resident bytes for block %d failed",
-                        (unsigned long long)c->res_bytes, block);
+                        (unsigned long long)res_bytes, block);
         }
     }
-    CF_HIP(c, hipMemcpy(c->res_buf[block], c->host[block], c->res_bytes, hipMemcpyHostToDevice));
+    CF_HIP(c, hipMemcpy(c->res_buf[block], c->host[block], res_bytes, hipMemcpyHostToDevice));
     return CF_OK;
 }
 
 inline uint64_t chunk_begin(const cf_ctx* c, int k) { return (uint64_t)k * c->chunk_bytes; }
-inline uint64_t chunk_end(const cf_ctx* c, int k) { return std::min(c->blob_bytes, (uint64_t)(k + 1) * c->chunk_bytes); }
+inline uint64_t chunk_end(const cf_ctx* c, const Plan& p, int k) { return std::min(p.blob_bytes, (uint64_t)(k + 1) * c->chunk_bytes); }
 
 WView view_of(const cf_ctx* c, int block) {
     WView v;
     v.lo = (const char*)c->res_buf[block];
     const int sl = c->block_slot[block];
-    v.hi = (sl >= 0 && c->slot[sl]) ? (const char*)c->slot[sl] - c->res_bytes : nullptr;
-    v.split = c->res_bytes;
+    v.hi = (sl >= 0 && c->slot[sl]) ? (const char*)c->slot[sl] - c->P(block).res_bytes : nullptr;
+    v.split = c->P(block).res_bytes;
     return v;
 }
 
@@ -210,10 +209,11 @@ WView view_of(const cf_ctx* c, int block) {
 // collective has been issued, parks the copy stream on that collective's completion event
 // ------------------------------------------------------------------------------------------
 int enqueue_block_copies(cf_ctx* c, int block, int s, hipStream_t copy, bool bounded) {
+    const Plan& p = c->P(block);
     if (c->done_valid[s]) CF_HIP(c, hipStreamWaitEvent(copy, c->done_ev[s], 0));   // slot's last reader
-    for (int k = c->n_res_chunks; k < c->n_chunks; ++k) {
+    for (int k = p.n_res_chunks; k < p.n_chunks; ++k) {
         if (bounded) {
-            if (k - 2 >= c->n_res_chunks) CF_HIP(c, hipEventSynchronize(c->chunk_ev[s][k - 2]));
+            if (k - 2 >= p.n_res_chunks) CF_HIP(c, hipEventSynchronize(c->chunk_ev[s][k - 2]));
             std::lock_guard<std::mutex> lk(c->mu);
             if (c->pause_flag) {
                 CF_HIP(c, hipStreamWaitEvent(copy, c->comm_done_ev, 0));
@@ -221,8 +221,8 @@ int enqueue_block_copies(cf_ctx* c, int block, int s, hipStream_t copy, bool bou
                 c->stats.pauses++;
             }
         }
-        const uint64_t b = chunk_begin(c, k), e = chunk_end(c, k);
-        CF_HIP(c, hipMemcpyAsync(c->slot[s] + (b - c->res_bytes), c->host[block] + b, e - b, hipMemcpyHostToDevice, copy));
+        const uint64_t b = chunk_begin(c, k), e = chunk_end(c, p, k);
+        CF_HIP(c, hipMemcpyAsync(c->slot[s] + (b - p.res_bytes), c->host[block] + b, e - b, hipMemcpyHostToDevice, copy));
         CF_HIP(c, hipEventRecord(c->chunk_ev[s][k], copy));
         {
             std::lock_guard<std::mutex> lk(c->mu);
@@ -253,7 +253,7 @@ void worker_main(cf_ctx* c) {
             std::lock_guard<std::mutex> lk(c->mu);
             if (rc != CF_OK) {
                 c->worker_err = c->err;
-                c->enq_count[job.slot] = c->n_chunks;   // never leave the consumer waiting
+                c->enq_count[job.slot] = c->max_chunks;   // never leave the consumer waiting
             }
             c->err = saved;
             c->worker_busy = false;
@@ -281,7 +281,7 @@ void worker_stop(cf_ctx* c) {
 
 // device-side wait for chunk k of `block` on stream s
 int wait_chunk(cf_ctx* c, int block, int k, hipStream_t s) {
-    if (k < c->n_res_chunks) return CF_OK;
+    if (k < c->P(block).n_res_chunks) return CF_OK;
     const int sl = c->block_slot[block];
     if (sl < 0 || c->slot_tenant[sl] != block || c->slot_state[sl] == SLOT_EMPTY)
         return fail(c, CF_ERR_STATE, "block %d: chunk %d awaited but its prefetch was not begun", block, k);
@@ -367,8 +367,8 @@ struct Fwd {
     Ws ws;
 };
 
-const TensorDesc& T(const cf_ctx* c, const std::string& name) {
-    for (auto& t : c->tensors)
+const TensorDesc& T(const Fwd& F, const std::string& name) {
+    for (auto& t : F.c->P(F.block).tensors)
         if (t.name == name) return t;
     static TensorDesc none{"", 0, 0, 0};
     return none;
@@ -378,7 +378,7 @@ const TensorDesc& T(const cf_ctx* c, const std::string& name) {
 int need(Fwd& F, const TensorDesc& t) {
     // the copy stream is in order: the last chunk's event covers the earlier ones
     const int last = (int)((t.off + t.bytes() - 1) / F.c->chunk_bytes);
-    if (last >= F.c->n_res_chunks && last > F.c->waited_upto) {
+    if (last >= F.c->P(F.block).n_res_chunks && last > F.c->waited_upto) {
         CF_TRY(wait_chunk(F.c, F.block, last, F.s));
         F.c->waited_upto = last;
     }
@@ -417,8 +417,9 @@ std::vector<Panel> plan_panels(const cf_ctx* c, const TensorDesc& t, int granule
 template <class Fn>
 int panels(Fwd& F, const TensorDesc& t, int granule, Fn&& fn) {
     cf_ctx* c = F.c;
-    for (const Panel& p : plan_panels(c, t, granule, std::max(c->waited_upto, c->n_res_chunks - 1))) {
-        if (p.wait > c->waited_upto && p.wait >= c->n_res_chunks) {
+    const int n_res = c->P(F.block).n_res_chunks;
+    for (const Panel& p : plan_panels(c, t, granule, std::max(c->waited_upto, n_res - 1))) {
+        if (p.wait > c->waited_upto && p.wait >= n_res) {
             CF_TRY(wait_chunk(c, F.block, p.wait, F.s));
             c->waited_upto = p.wait;
         }
@@ -428,7 +429,7 @@ int panels(Fwd& F, const TensorDesc& t, int granule, Fn&& fn) {
 }
 
 int run_modvec(Fwd& F, const std::string& wname, const std::string& bname, const float* t, float* out) {
-    const TensorDesc &w = T(F.c, wname), &b = T(F.c, bname);
+    const TensorDesc &w = T(F, wname), &b = T(F, bname);
     CF_TRY(need(F, b));
     return panels(F, w, 8, [&](int r0, int r1) -> int {
         ProfScope ps(F.c, F.s, K_MODVEC, 2.0 * (r1 - r0) * w.cols, 2.0 * (r1 - r0) * w.cols);
@@ -447,7 +448,7 @@ int run_ln_mod(Fwd& F, const float* x, const float* shift, const float* scale, b
 // out-feature panels of one linear layer; `g` carries everything but the panel and the weights
 int run_linear(Fwd& F, int kid, const std::string& wname, const std::string& bname, GemmArgs g) {
     if (g.M <= 0) return CF_OK;
-    const TensorDesc &w = T(F.c, wname), &b = T(F.c, bname);
+    const TensorDesc &w = T(F, wname), &b = T(F, bname);
     CF_TRY(need(F, b));
     g.W = F.W;
     g.w_off = w.off;
@@ -471,7 +472,7 @@ TokenMap token_map(const cf_model_desc& m) {
     TokenMap t;
     t.n_total = m.n_total;
     t.n_local = m.n_total / m.sp_degree;
-    if (m.kind == CF_DOUBLE_STREAM) {
+    if (m.n_txt_total > 0) {            // text rows, then image rows, each split contiguously over the ranks
         const int tl = m.n_txt_total / m.sp_degree, il = t.n_local - tl;
         t.pos0 = m.sp_rank * tl; t.len0 = tl;
         t.pos1 = m.n_txt_total + m.sp_rank * il; t.len1 = il;
@@ -550,7 +551,7 @@ RelayoutArgs relayout_for(Fwd& F, const bf16* src, int rows, int row0, const std
     r.hd = m.head_dim;
     r.W = F.W;
     r.has_norm = m.qk_rmsnorm;
-    if (m.qk_rmsnorm) { r.qn_off = T(F.c, qn).off; r.kn_off = T(F.c, kn).off; }
+    if (m.qk_rmsnorm) { r.qn_off = T(F, qn).off; r.kn_off = T(F, kn).off; }
     r.map = token_map(m);
     r.row0 = row0;
     r.Q = F.ws.Q; r.K = F.ws.K; r.Vt = F.ws.Vt;
@@ -568,7 +569,7 @@ int fwd_single(Fwd& F) {
     CF_TRY(run_modvec(F, "w_mod", "b_mod", io->temb, F.ws.mod));
     const float *shift = F.ws.mod, *scale = F.ws.mod + d, *gate = F.ws.mod + 2 * d;
     CF_TRY(run_ln_mod(F, io->x, shift, scale, F.ws.xn, nl));
-    if (m.qk_rmsnorm) { CF_TRY(need(F, T(c, "q_norm"))); CF_TRY(need(F, T(c, "k_norm"))); }
+    if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, "q_norm"))); CF_TRY(need(F, T(F, "k_norm"))); }
     GemmArgs g{};
     g.A = F.ws.xn; g.lda = d; g.M = nl; g.epi = EPI_SPLIT_GELU;
     g.out0 = F.ws.qkv; g.ld0 = 3 * d; g.n_split = 3 * d;
@@ -599,15 +600,30 @@ int check_desc(const cf_model_desc* m) {
     if (m->sp_degree <= 0 || m->sp_rank < 0 || m->sp_rank >= m->sp_degree) return fail(nullptr, CF_ERR_ARG, "bad sp_degree/sp_rank");
     if (m->n_heads % m->sp_degree) return fail(nullptr, CF_ERR_ARG, "sp_degree must divide n_heads");
     if (m->n_total <= 0 || m->n_total % m->sp_degree) return fail(nullptr, CF_ERR_ARG, "sp_degree must divide n_total");
-    if (m->kind == CF_DOUBLE_STREAM) {
-        if (m->n_txt_total <= 0 || m->n_txt_total >= m->n_total || m->n_txt_total % m->sp_degree)
-            return fail(nullptr, CF_ERR_ARG, "double-stream needs 0 < n_txt_total < n_total, divisible by sp_degree");
-    } else if (m->n_txt_total) {
-        return fail(nullptr, CF_ERR_ARG, "n_txt_total is only meaningful for double-stream blocks");
+    if (m->kind == CF_DOUBLE_STREAM && m->n_txt_total <= 0) return fail(nullptr, CF_ERR_ARG, "double-stream needs n_txt_total > 0");
+    if (m->n_txt_total) {
+        if (m->kind == CF_DIT_CROSS) return fail(nullptr, CF_ERR_ARG, "n_txt_total has no meaning for DiT blocks");
+        if (m->n_txt_total < 0 || m->n_txt_total >= m->n_total || m->n_txt_total % m->sp_degree)
+            return fail(nullptr, CF_ERR_ARG, "need 0 < n_txt_total < n_total, divisible by sp_degree");
     }
     if (m->kind == CF_DIT_CROSS && m->l_ctx <= 0) return fail(nullptr, CF_ERR_ARG, "DiT block needs l_ctx > 0");
     if (m->chunk_bytes == 0 || m->chunk_bytes % 256) return fail(nullptr, CF_ERR_ARG, "chunk_bytes must be a positive multiple of 256");
     return CF_OK;
+}
+
+// (re)build the plans of the kinds the model uses
+void plan_model(cf_ctx* c) {
+    for (int k = 0; k < 3; ++k) c->plan[k] = Plan{};
+    c->ws_bytes = 0;
+    c->max_chunks = 0;
+    for (int k : c->block_kind) {
+        Plan& p = c->plan[k];
+        if (p.kind >= 0) continue;
+        plan_layout(&p, c->d, k, c->chunk_bytes);
+        p.ws_bytes = carve(c->d, k, nullptr).total;
+        c->ws_bytes = std::max(c->ws_bytes, p.ws_bytes);
+        c->max_chunks = std::max(c->max_chunks, p.n_chunks);
+    }
 }
 
 int check_block(const cf_ctx* c, int block) {
@@ -631,8 +647,8 @@ int cf_create(const cf_model_desc* desc, cf_ctx** out) {
     if (!c) return fail(nullptr, CF_ERR_NOMEM, "out of host memory");
     c->d = *desc;
     c->chunk_bytes = desc->chunk_bytes;
-    plan_layout(c);
-    c->ws_bytes = carve(c, nullptr).total;
+    c->block_kind.assign(desc->n_blocks, desc->kind);
+    plan_model(c);
     c->host.assign(desc->n_blocks, nullptr);
     c->res_buf.assign(desc->n_blocks, nullptr);
     c->block_slot.assign(desc->n_blocks, -1);
@@ -663,41 +679,70 @@ int cf_destroy(cf_ctx* c) {
 
 const char* cf_last_error(const cf_ctx* c) { return c ? c->err.c_str() : g_create_err.c_str(); }
 
-int cf_blob_bytes(const cf_ctx* c, uint64_t* out) {
-    if (!c || !out) return CF_ERR_ARG;
-    *out = c->blob_bytes;
+int cf_set_block_kinds(cf_ctx* c, const int32_t* kinds, int32_t n) {
+    if (!c || !kinds) return CF_ERR_ARG;
+    if (n != c->d.n_blocks) return fail(c, CF_ERR_ARG, "%d kinds given for %d blocks", n, c->d.n_blocks);
+    if (c->device_ready) return fail(c, CF_ERR_STATE, "block kinds must be set before any block is registered");
+    for (int b = 0; b < n; ++b) {
+        if (kinds[b] < 0 || kinds[b] > 2) return fail(c, CF_ERR_ARG, "block %d: unknown kind %d", b, kinds[b]);
+        if (kinds[b] == CF_DOUBLE_STREAM && c->d.n_txt_total <= 0) return fail(c, CF_ERR_ARG, "block %d: double-stream needs n_txt_total > 0", b);
+        if (kinds[b] == CF_DIT_CROSS && (c->d.l_ctx <= 0 || c->d.n_txt_total)) return fail(c, CF_ERR_ARG, "block %d: DiT block needs l_ctx > 0 and no text rows", b);
+    }
+    c->block_kind.assign(kinds, kinds + n);
+    plan_model(c);
     return CF_OK;
 }
 
-int cf_n_chunks(const cf_ctx* c, int32_t* out) {
-    if (!c || !out) return CF_ERR_ARG;
-    *out = c->n_chunks;
+int cf_block_kind_of(const cf_ctx* c, int32_t block, int32_t* out) {
+    CF_TRY(check_block(c, block));
+    if (!out) return CF_ERR_ARG;
+    *out = c->block_kind[block];
     return CF_OK;
 }
 
-int cf_blob_layout(const cf_ctx* c, cf_tensor_slot* out, int32_t* n) {
-    if (!c || !n) return CF_ERR_ARG;
-    const int cnt = (int)c->tensors.size();
+int cf_blob_bytes_of(const cf_ctx* c, int32_t block, uint64_t* out) {
+    CF_TRY(check_block(c, block));
+    if (!out) return CF_ERR_ARG;
+    *out = c->P(block).blob_bytes;
+    return CF_OK;
+}
+
+int cf_n_chunks_of(const cf_ctx* c, int32_t block, int32_t* out) {
+    CF_TRY(check_block(c, block));
+    if (!out) return CF_ERR_ARG;
+    *out = c->P(block).n_chunks;
+    return CF_OK;
+}
+
+int cf_blob_layout_of(const cf_ctx* c, int32_t block, cf_tensor_slot* out, int32_t* n) {
+    CF_TRY(check_block(c, block));
+    if (!n) return CF_ERR_ARG;
+    const std::vector<TensorDesc>& ts = c->P(block).tensors;
+    const int cnt = (int)ts.size();
     if (out) {
         if (*n < cnt) return fail(c, CF_ERR_ARG, "layout needs room for %d tensors", cnt);
         for (int i = 0; i < cnt; ++i) {
             memset(&out[i], 0, sizeof out[i]);
-            snprintf(out[i].name, sizeof out[i].name, "%s", c->tensors[i].name.c_str());
-            out[i].offset = c->tensors[i].off;
-            out[i].rows = c->tensors[i].rows;
-            out[i].cols = c->tensors[i].cols;
+            snprintf(out[i].name, sizeof out[i].name, "%s", ts[i].name.c_str());
+            out[i].offset = ts[i].off;
+            out[i].rows = ts[i].rows;
+            out[i].cols = ts[i].cols;
         }
     }
     *n = cnt;
     return CF_OK;
 }
 
+int cf_blob_bytes(const cf_ctx* c, uint64_t* out) { return cf_blob_bytes_of(c, 0, out); }
+int cf_n_chunks(const cf_ctx* c, int32_t* out) { return cf_n_chunks_of(c, 0, out); }
+int cf_blob_layout(const cf_ctx* c, cf_tensor_slot* out, int32_t* n) { return cf_blob_layout_of(c, 0, out, n); }
+
 int cf_plan_panels(const cf_ctx* c, const char* tensor, int32_t granule, int32_t n_resident_chunks, int32_t* row0,
                    int32_t* row1, int32_t* wait_chunk_out, int32_t* n) {
     if (!c || !tensor || !n || granule <= 0) return CF_ERR_ARG;
-    const TensorDesc* t = cf_find(c, tensor);
+    const TensorDesc* t = cf_find(c->P(0), tensor);
     if (!t) return fail(c, CF_ERR_ARG, "no tensor named %s in the blob", tensor);
-    if (n_resident_chunks < 0 || n_resident_chunks > c->n_chunks) return fail(c, CF_ERR_ARG, "resident chunk count out of range");
+    if (n_resident_chunks < 0 || n_resident_chunks > c->P(0).n_chunks) return fail(c, CF_ERR_ARG, "resident chunk count out of range");
     const std::vector<Panel> plan = plan_panels(c, *t, granule, n_resident_chunks - 1);
     if (row0 && row1 && wait_chunk_out) {
         if (*n < (int)plan.size()) return fail(c, CF_ERR_ARG, "need room for %d panels", (int)plan.size());
@@ -716,8 +761,8 @@ int cf_workspace_bytes(const cf_ctx* c, uint64_t* out) {
 int cf_register_block(cf_ctx* c, int32_t block, const void* host_blob, uint64_t bytes) {
     CF_TRY(check_block(c, block));
     if (!host_blob) return fail(c, CF_ERR_ARG, "null host blob");
-    if (bytes != c->blob_bytes)
-        return fail(c, CF_ERR_ARG, "blob is %llu bytes, layout needs %llu", (unsigned long long)bytes, (unsigned long long)c->blob_bytes);
+    if (bytes != c->P(block).blob_bytes)
+        return fail(c, CF_ERR_ARG, "blob is %llu bytes, layout needs %llu", (unsigned long long)bytes, (unsigned long long)c->P(block).blob_bytes);
     hipPointerAttribute_t attr;
     hipError_t e = hipPointerGetAttributes(&attr, host_blob);
     if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
@@ -733,16 +778,26 @@ int cf_register_block(cf_ctx* c, int32_t block, const void* host_blob, uint64_t 
 int set_resident_fraction(cf_ctx* c, double r, double* actual) {
     if (!c) return CF_ERR_ARG;
     if (!(r >= 0.0 && r <= 1.0)) return fail(c, CF_ERR_ARG, "resident fraction %g outside [0,1]", r);
-    const int n_res = (int)std::floor(r * c->n_chunks + 0.5);
-    const uint64_t res_bytes = n_res ? chunk_end(c, n_res - 1) : 0;
-    if (actual) *actual = (double)res_bytes / (double)c->blob_bytes;
+    // per kind: the leading round(r * n_chunks) chunks; the fraction reported is over the whole model
+    int n_res[3] = {0, 0, 0};
+    uint64_t res_bytes[3] = {0, 0, 0}, slot_bytes = 0;
+    for (int k = 0; k < 3; ++k) {
+        const Plan& p = c->plan[k];
+        if (p.kind < 0) continue;
+        n_res[k] = (int)std::floor(r * p.n_chunks + 0.5);
+        res_bytes[k] = n_res[k] ? chunk_end(c, p, n_res[k] - 1) : 0;
+        slot_bytes = std::max(slot_bytes, p.blob_bytes - res_bytes[k]);
+    }
+    if (actual) {
+        double res = 0, all = 0;
+        for (int k : c->block_kind) { res += (double)res_bytes[k]; all += (double)c->plan[k].blob_bytes; }
+        *actual = res / all;
+    }
     CF_TRY(ensure_device(c));
     worker_drain(c);
     CF_HIP(c, hipDeviceSynchronize());
     free_weights(c);
-    c->n_res_chunks = n_res;
-    c->res_bytes = res_bytes;
-    const uint64_t slot_bytes = c->blob_bytes - res_bytes;
+    for (int k = 0; k < 3; ++k) { c->plan[k].n_res_chunks = n_res[k]; c->plan[k].res_bytes = res_bytes[k]; }
     if (slot_bytes) {
         for (int s = 0; s < 2; ++s)
             if (hipMalloc((void**)&c->slot[s], slot_bytes) != hipSuccess) {
@@ -758,7 +813,7 @@ int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
     CF_TRY(check_block(c, block));
     if (!c->host[block]) return fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
     CF_TRY(ensure_device(c));
-    if (c->n_res_chunks == c->n_chunks) return CF_OK;              // 100 % resident: nothing to move
+    if (c->P(block).n_res_chunks == c->P(block).n_chunks) return CF_OK;   // 100 % resident: nothing to move
     if (!c->slot[0]) CF_TRY(set_resident_fraction(c, 0.0, nullptr));
     if (c->block_slot[block] >= 0 && c->slot_state[c->block_slot[block]] == SLOT_FILLED)
         return fail(c, CF_ERR_STATE, "block %d is already prefetched and waiting for its forward", block);
@@ -779,7 +834,7 @@ int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
         if (!c->worker.joinable()) c->worker = std::thread(worker_main, c);
         {
             std::lock_guard<std::mutex> lk(c->mu);
-            c->enq_count[s] = c->n_res_chunks;
+            c->enq_count[s] = c->P(block).n_res_chunks;
             c->jobs.push_back(PrefetchJob{block, s, (hipStream_t)copy_stream});
         }
         c->cv.notify_all();
@@ -790,9 +845,10 @@ int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
 
 int chunked_prefetch_wait(cf_ctx* c, int32_t block, int32_t chunk, void* compute_stream) {
     CF_TRY(check_block(c, block));
-    if (chunk < -1 || chunk >= c->n_chunks) return fail(c, CF_ERR_ARG, "chunk %d out of range", chunk);
-    const int last = chunk < 0 ? c->n_chunks - 1 : chunk;
-    if (last < c->n_res_chunks) return CF_OK;
+    const Plan& p = c->P(block);
+    if (chunk < -1 || chunk >= p.n_chunks) return fail(c, CF_ERR_ARG, "chunk %d out of range", chunk);
+    const int last = chunk < 0 ? p.n_chunks - 1 : chunk;
+    if (last < p.n_res_chunks) return CF_OK;
     // the copy stream is in order: waiting for `last` covers every earlier chunk
     return wait_chunk(c, block, last, (hipStream_t)compute_stream);
 }
@@ -804,19 +860,20 @@ int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute
     if (!io->workspace || io->workspace_bytes < c->ws_bytes || ((uintptr_t)io->workspace % 256))
         return fail(c, CF_ERR_ARG, "workspace must be 256-byte aligned and at least %llu bytes", (unsigned long long)c->ws_bytes);
     if (((uintptr_t)io->x | (uintptr_t)io->y | (uintptr_t)io->temb) % 16) return fail(c, CF_ERR_ARG, "x, y, temb must be 16-byte aligned");
-    if (c->d.kind == CF_DOUBLE_STREAM && (!io->x_txt || !io->y_txt)) return fail(c, CF_ERR_ARG, "double-stream needs x_txt and y_txt");
-    if (c->d.kind == CF_DIT_CROSS && !io->ctx) return fail(c, CF_ERR_ARG, "DiT block needs ctx");
+    const Plan& p = c->P(block);
+    if (p.kind == CF_DOUBLE_STREAM && (!io->x_txt || !io->y_txt)) return fail(c, CF_ERR_ARG, "double-stream needs x_txt and y_txt");
+    if (p.kind == CF_DIT_CROSS && !io->ctx) return fail(c, CF_ERR_ARG, "DiT block needs ctx");
     if (!c->host[block]) return fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
     CF_TRY(ensure_device(c));
     const int s = c->block_slot[block];
-    const bool streamed = c->n_res_chunks < c->n_chunks;
+    const bool streamed = p.n_res_chunks < p.n_chunks;
     if (streamed && (s < 0 || c->slot_tenant[s] != block || c->slot_state[s] != SLOT_FILLED))
         return fail(c, CF_ERR_STATE, "block %d: chunked_prefetch_begin must precede dit_block_fwd", block);
 
-    Fwd F{c, block, (hipStream_t)compute_stream, view_of(c, block), io, carve(c, (char*)io->workspace)};
-    c->waited_upto = c->n_res_chunks - 1;
+    Fwd F{c, block, (hipStream_t)compute_stream, view_of(c, block), io, carve(c->d, p.kind, (char*)io->workspace)};
+    c->waited_upto = p.n_res_chunks - 1;
     int rc;
-    switch (c->d.kind) {
+    switch (p.kind) {
         case CF_SINGLE_STREAM: rc = fwd_single(F); break;
         case CF_DIT_CROSS: rc = fwd_dit(F); break;
         default: rc = fwd_double(F); break;
@@ -884,18 +941,19 @@ int cf_checksum_block(cf_ctx* c, int32_t block, uint64_t* host_out, void* stream
     if (!host_out) return fail(c, CF_ERR_ARG, "null output");
     CF_TRY(ensure_device(c));
     hipStream_t s = (hipStream_t)stream;
-    if (c->n_res_chunks < c->n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
+    const Plan& p = c->P(block);
+    if (p.n_res_chunks < p.n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
     uint64_t* dev = nullptr;
-    if (hipMalloc((void**)&dev, 8ull * c->n_chunks) != hipSuccess) { (void)hipGetLastError(); return fail(c, CF_ERR_NOMEM, "hipMalloc failed"); }
+    if (hipMalloc((void**)&dev, 8ull * p.n_chunks) != hipSuccess) { (void)hipGetLastError(); return fail(c, CF_ERR_NOMEM, "hipMalloc failed"); }
     const WView v = view_of(c, block);
     int rc = CF_OK;
-    for (int k = 0; k < c->n_chunks && rc == CF_OK; ++k) {
-        const uint64_t b = chunk_begin(c, k), e = chunk_end(c, k);
-        const char* p = (b < v.split ? v.lo : v.hi) + b;
-        hipError_t he = checksum_launch(p, e - b, b / 8, dev + k, s);
+    for (int k = 0; k < p.n_chunks && rc == CF_OK; ++k) {
+        const uint64_t b = chunk_begin(c, k), e = chunk_end(c, p, k);
+        const char* src = (b < v.split ? v.lo : v.hi) + b;
+        hipError_t he = checksum_launch(src, e - b, b / 8, dev + k, s);
         if (he != hipSuccess) rc = fail(c, CF_ERR_HIP, "checksum launch failed: %s", hipGetErrorString(he));
     }
-    if (rc == CF_OK && hipMemcpyAsync(host_out, dev, 8ull * c->n_chunks, hipMemcpyDeviceToHost, s) != hipSuccess) rc = fail(c, CF_ERR_HIP, "checksum copy failed");
+    if (rc == CF_OK && hipMemcpyAsync(host_out, dev, 8ull * p.n_chunks, hipMemcpyDeviceToHost, s) != hipSuccess) rc = fail(c, CF_ERR_HIP, "checksum copy failed");
     if (hipStreamSynchronize(s) != hipSuccess && rc == CF_OK) rc = fail(c, CF_ERR_HIP, "checksum sync failed");
     (void)hipFree(dev);
     return rc;
@@ -906,13 +964,14 @@ int cf_read_block(cf_ctx* c, int32_t block, void* host_out, void* stream) {
     if (!host_out) return fail(c, CF_ERR_ARG, "null output");
     CF_TRY(ensure_device(c));
     hipStream_t s = (hipStream_t)stream;
-    if (c->n_res_chunks < c->n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
-    if (c->res_bytes) {
+    const Plan& p = c->P(block);
+    if (p.n_res_chunks < p.n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
+    if (p.res_bytes) {
         if (!c->res_buf[block]) return fail(c, CF_ERR_STATE, "block %d not registered", block);
-        CF_HIP(c, hipMemcpyAsync(host_out, c->res_buf[block], c->res_bytes, hipMemcpyDeviceToHost, s));
+        CF_HIP(c, hipMemcpyAsync(host_out, c->res_buf[block], p.res_bytes, hipMemcpyDeviceToHost, s));
     }
-    if (c->res_bytes < c->blob_bytes)
-        CF_HIP(c, hipMemcpyAsync((char*)host_out + c->res_bytes, c->slot[c->block_slot[block]], c->blob_bytes - c->res_bytes, hipMemcpyDeviceToHost, s));
+    if (p.res_bytes < p.blob_bytes)
+        CF_HIP(c, hipMemcpyAsync((char*)host_out + p.res_bytes, c->slot[c->block_slot[block]], p.blob_bytes - p.res_bytes, hipMemcpyDeviceToHost, s));
     CF_HIP(c, hipStreamSynchronize(s));
     return CF_OK;
 }
@@ -921,9 +980,17 @@ int cf_stats(cf_ctx* c, cf_stats_t* out) {
     if (!c || !out) return CF_ERR_ARG;
     std::lock_guard<std::mutex> lk(c->mu);
     *out = c->stats;
-    out->resident_bytes = c->res_bytes;
-    out->blob_bytes = c->blob_bytes;
-    out->weight_memory_bytes = c->res_bytes * (uint64_t)c->d.n_blocks + 2 * (c->blob_bytes - c->res_bytes);
+    // resident and blob bytes per block, averaged over the model's blocks; weight memory (Sec. 3.3)
+    // = every block's resident part + two staging slots sized for the largest streamed part
+    uint64_t res = 0, all = 0, slot = 0;
+    for (int k : c->block_kind) { res += c->plan[k].res_bytes; all += c->plan[k].blob_bytes; }
+    for (int k = 0; k < 3; ++k)
+        if (c->plan[k].kind >= 0) slot = std::max(slot, c->plan[k].blob_bytes - c->plan[k].res_bytes);
+    out->resident_bytes = res / c->d.n_blocks;
+    out->blob_bytes = all / c->d.n_blocks;
+    out->weight_memory_bytes = res + 2 * slot;
+    out->model_resident_bytes = res;
+    out->model_blob_bytes = all;
     return CF_OK;
 }
 
@@ -1098,26 +1165,26 @@ int fwd_dit(Fwd& F) {
                 *g2 = w.mod + 5 * d;
     // self-attention
     CF_TRY(run_ln_mod(F, io->x, sh1, sc1, w.xn, nl));
-    if (m.qk_rmsnorm) { CF_TRY(need(F, T(c, "q_norm"))); CF_TRY(need(F, T(c, "k_norm"))); }
+    if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, "q_norm"))); CF_TRY(need(F, T(F, "k_norm"))); }
     CF_TRY(run_linear(F, K_QKV, "w_qkv", "b_qkv", plain_linear(w.xn, d, nl, w.qkv, 3 * d)));
     RelayoutArgs r = relayout_for(F, w.qkv, nl, 0, "q_norm", "k_norm");
     CF_TRY(run_joint_attention(F, &r, 1, w.c, d));
     CF_TRY(run_linear(F, K_OUT, "w_o", "b_o", resid_linear(w.c, d, nl, io->x, g1, w.x1, d)));
     // cross-attention: queries from the local tokens (all heads), keys/values from the context
-    CF_TRY(need(F, T(c, "ln_c_w")));
-    CF_TRY(need(F, T(c, "ln_c_b")));
+    CF_TRY(need(F, T(F, "ln_c_w")));
+    CF_TRY(need(F, T(F, "ln_c_b")));
     {
         ProfScope ps(c, F.s, K_LN, 0, 6.0 * nl * d);
-        CF_HIP(c, ln_affine_launch(w.x1, F.W, T(c, "ln_c_w").off, T(c, "ln_c_b").off, w.xn, nl, d, F.s));
+        CF_HIP(c, ln_affine_launch(w.x1, F.W, T(F, "ln_c_w").off, T(F, "ln_c_b").off, w.xn, nl, d, F.s));
     }
-    if (m.qk_rmsnorm) { CF_TRY(need(F, T(c, "cq_norm"))); CF_TRY(need(F, T(c, "ck_norm"))); }
+    if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, "cq_norm"))); CF_TRY(need(F, T(F, "ck_norm"))); }
     CF_TRY(run_linear(F, K_CROSS_Q, "w_cq", "b_cq", plain_linear(w.xn, d, nl, w.qkv, d)));
     CF_TRY(run_linear(F, K_CROSS_KV, "w_ckv", "b_ckv", plain_linear((const bf16*)io->ctx, d, lc, w.ckv, 2 * d)));
     {
         RelayoutArgs rq{};
         rq.src = w.qkv; rq.ld = d; rq.rows = nl; rq.col_q = 0; rq.col_k = -1; rq.col_v = -1;
         rq.n_heads = H; rq.h0 = 0; rq.h_local = H; rq.hd = hd; rq.W = F.W; rq.has_norm = m.qk_rmsnorm;
-        if (m.qk_rmsnorm) { rq.qn_off = T(c, "cq_norm").off; rq.kn_off = T(c, "ck_norm").off; }
+        if (m.qk_rmsnorm) { rq.qn_off = T(F, "cq_norm").off; rq.kn_off = T(F, "ck_norm").off; }
         rq.map = identity_map(nl); rq.row0 = 0; rq.Q = w.cQ; rq.K = nullptr; rq.Vt = nullptr; rq.n_pad = 0;
         RelayoutArgs rk = rq;
         rk.src = w.ckv; rk.ld = 2 * d; rk.rows = lc; rk.col_q = -1; rk.col_k = 0; rk.col_v = d;
@@ -1159,7 +1226,7 @@ int fwd_double(Fwd& F) {
     for (int s = 0; s < 2; ++s) CF_TRY(run_ln_mod(F, xin[s], mod(s, 0), mod(s, 1), w.xn + (size_t)row0[s] * d, rows[s]));
     RelayoutArgs parts[2];
     for (int s = 0; s < 2; ++s) {
-        if (m.qk_rmsnorm) { CF_TRY(need(F, T(c, nm(st[s], "q_norm")))); CF_TRY(need(F, T(c, nm(st[s], "k_norm")))); }
+        if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, nm(st[s], "q_norm")))); CF_TRY(need(F, T(F, nm(st[s], "k_norm")))); }
         CF_TRY(run_linear(F, K_QKV, nm(st[s], "w_qkv"), nm(st[s], "b_qkv"),
                           plain_linear(w.xn + (size_t)row0[s] * d, d, rows[s], w.qkv + (size_t)row0[s] * 3 * d, 3 * d)));
         parts[s] = relayout_for(F, w.qkv + (size_t)row0[s] * 3 * d, rows[s], row0[s], nm(st[s], "q_norm"), nm(st[s], "k_norm"));
@@ -1180,8 +1247,8 @@ int fwd_double(Fwd& F) {
 
 }  // namespace
 
-const TensorDesc* cf_find(const cf_ctx* c, const char* name) {
-    for (auto& t : c->tensors)
+const TensorDesc* cf_find(const Plan& c, const char* name) {
+    for (auto& t : c.tensors)
         if (t.name == name) return &t;
     return nullptr;
 }

@@ -35,20 +35,33 @@ struct PrefetchJob {
     hipStream_t copy;
 };
 
-struct cf_ctx {
-    cf_model_desc d{};
+// Blob layout, chunk plan and residency of one block kind (a model may mix kinds, App. B:
+// double-stream blocks followed by single-stream ones)
+struct Plan {
+    int kind = -1;
     std::vector<TensorDesc> tensors;
-    uint64_t blob_bytes = 0, chunk_bytes = 0;
+    uint64_t blob_bytes = 0;
     int n_chunks = 0;
-    uint64_t ws_bytes = 0;
-
-    // residency (Sec. 3.3): leading n_res_chunks chunks of every block stay in HBM
+    // residency (Sec. 3.3): the leading n_res_chunks chunks of every block of this kind stay in HBM
     int n_res_chunks = 0;
     uint64_t res_bytes = 0;
+    uint64_t ws_bytes = 0;
+};
+
+struct cf_ctx {
+    cf_model_desc d{};
+    uint64_t chunk_bytes = 0;
+    Plan plan[3];                       // indexed by cf_block_kind; kind < 0 = not used by this model
+    std::vector<int> block_kind;
+    uint64_t ws_bytes = 0;              // largest over the kinds in use
+    int max_chunks = 0;
+    const Plan& P(int block) const { return plan[block_kind[block]]; }
+
     std::vector<const uint8_t*> host;
     std::vector<uint8_t*> res_buf;
 
-    // staging (Sec. 2.2: two layers live) -- slot s holds blob bytes [res_bytes, blob) of its tenant
+    // staging (Sec. 2.2: two layers live) -- slot s holds blob bytes [res_bytes, blob) of its tenant;
+    // slots are sized for the kind with the most streamed bytes
     bool device_ready = false;
     int device = 0;
     uint8_t* slot[2] = {nullptr, nullptr};
@@ -88,4 +101,4 @@ struct cf_ctx {
     mutable std::string err;
 };
 
-const TensorDesc* cf_find(const cf_ctx* c, const char* name);
+const TensorDesc* cf_find(const Plan& p, const char* name);

@@ -15,15 +15,25 @@ import torch
 from . import binding as B
 
 
+def make_context(cfg, chunk_bytes: int) -> B.Context:
+    """Context for a stack of blocks; a mixed stack (cfg.n_double leading double-stream blocks)
+    gets its per-block kinds."""
+    ctx = B.Context(B.desc_from_config(cfg, chunk_bytes))
+    if cfg.n_double:
+        ctx.cf_set_block_kinds(cfg.kinds)
+    return ctx
+
+
 def blob_bytes_for(cfg) -> int:
-    ctx = B.Context(B.desc_from_config(cfg, 1 << 20))
-    n = ctx.cf_blob_bytes()
+    """Blob size of a block (the smallest over the kinds of a mixed stack)."""
+    ctx = make_context(cfg, 1 << 20)
+    n = min(ctx.cf_blob_bytes(b) for b in range(cfg.n_blocks))
     ctx.close()
     return n
 
 
 def chunk_bytes_for(cfg, n_chunks: Optional[int] = None) -> int:
-    """Chunk size that cuts the blob into the configuration's number of chunks."""
+    """Chunk size that cuts the (smallest) blob into the configuration's number of chunks."""
     n_chunks = n_chunks or cfg.n_chunks
     blob = blob_bytes_for(cfg)
     return (blob + n_chunks - 1) // n_chunks // 256 * 256 + (256 if ((blob + n_chunks - 1) // n_chunks) % 256 else 0)
@@ -39,8 +49,10 @@ class BlockRunner:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.chunk_bytes = chunk_bytes or chunk_bytes_for(self.cfg)
-        self.ctx = B.Context(B.desc_from_config(self.cfg, self.chunk_bytes))
-        self.blob_bytes = self.ctx.cf_blob_bytes()
+        self.ctx = make_context(self.cfg, self.chunk_bytes)
+        self.blob_bytes_of = [self.ctx.cf_blob_bytes(b) for b in range(self.cfg.n_blocks)]
+        self.total_blob_bytes = sum(self.blob_bytes_of)
+        self.blob_bytes = self.blob_bytes_of[0]
         self.n_chunks = self.ctx.cf_n_chunks()
         self.compute = torch.cuda.Stream(device=self.device)
         self.copy = torch.cuda.Stream(device=self.device)
@@ -52,8 +64,8 @@ class BlockRunner:
 
     # ---- weights
     def register_params(self, block: int, params: Dict[str, np.ndarray]) -> torch.Tensor:
-        blob = torch.empty(self.blob_bytes, dtype=torch.uint8, pin_memory=True)
-        self.ctx.pack_blob(params, blob.numpy())
+        blob = torch.empty(self.blob_bytes_of[block], dtype=torch.uint8, pin_memory=True)
+        self.ctx.pack_blob(params, blob.numpy(), block)
         self.ctx.cf_register_block(block, blob)
         while len(self.blobs) <= block:
             self.blobs.append(None)

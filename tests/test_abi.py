@@ -4,6 +4,8 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 import workload as wl
@@ -129,3 +131,36 @@ def test_panel_plans_cover_every_row_once_behind_the_right_chunk(name, chunk_mib
                     assert w >= n_res        # never waits for a resident chunk
             if n_res == n_chunks:
                 assert plan == [(0, t["rows"], -1)]     # fully resident: one launch, no wait
+
+
+def test_mixed_block_kinds_are_planned_per_block():
+    """App. B composition: double-stream blocks then single-stream ones; each kind has its own
+    layout and chunk count, the workspace covers both."""
+    cfg = wl.CONFIGS["toy_mm"]
+    chunk = 1 << 20
+    ctx = B.Context(B.desc_from_config(cfg, chunk))
+    try:
+        single_bytes, single_ws = ctx.cf_blob_bytes(), ctx.cf_workspace_bytes()
+        ctx.cf_set_block_kinds(cfg.kinds)
+        assert [ctx.cf_block_kind_of(b) for b in range(cfg.n_blocks)] == [wl.KIND_DOUBLE, wl.KIND_SINGLE, wl.KIND_SINGLE]
+        assert ctx.cf_blob_bytes(1) == ctx.cf_blob_bytes(2) == single_bytes
+        assert ctx.cf_workspace_bytes() >= single_ws
+        for b in range(cfg.n_blocks):
+            specs = wl.param_specs(cfg.block_cfg(b))
+            lay = ctx.cf_blob_layout(b)
+            assert sorted(t["name"] for t in lay) == sorted(s[0] for s in specs)
+            want = sum(-(-2 * int(np.prod(s[1])) // 256) * 256 for s in specs)
+            assert ctx.cf_blob_bytes(b) == want
+            assert ctx.cf_n_chunks(b) == -(-want // chunk)
+        with pytest.raises(B.ChunkflowError):
+            ctx.cf_set_block_kinds([0, 0])                      # one kind per block
+        with pytest.raises(B.ChunkflowError):
+            ctx.cf_set_block_kinds([wl.KIND_DIT, 0, 0])         # no cross-attention context in this model
+    finally:
+        ctx.close()
+    no_txt = B.Context(B.desc_from_config(wl.CONFIGS["toy"], chunk))
+    try:
+        with pytest.raises(B.ChunkflowError):
+            no_txt.cf_set_block_kinds([wl.KIND_DOUBLE, 0])      # double-stream needs text rows
+    finally:
+        no_txt.close()

@@ -46,6 +46,7 @@ class BlockConfig:
     qk_rmsnorm: bool = True
     n_chunks: int = 8   # chunks per block the config asks for (chunk_bytes derived)
     temb_std: float = 1.0
+    n_double: int = 0   # mixed model: the first n_double blocks are double-stream, the rest `kind`
 
     @property
     def n_local(self) -> int:
@@ -61,6 +62,17 @@ class BlockConfig:
 
     def with_(self, **kw) -> "BlockConfig":
         return dataclasses.replace(self, **kw)
+
+    def kind_of(self, block: int) -> int:
+        return KIND_DOUBLE if block < self.n_double else self.kind
+
+    @property
+    def kinds(self) -> List[int]:
+        return [self.kind_of(b) for b in range(self.n_blocks)]
+
+    def block_cfg(self, block: int) -> "BlockConfig":
+        """The configuration of one block of a (possibly mixed) stack, as a one-kind config."""
+        return dataclasses.replace(self, kind=self.kind_of(block), n_double=0)
 
 
 def _temb_std(d: int) -> float:
@@ -87,6 +99,15 @@ CONFIGS: Dict[str, BlockConfig] = {
     "hunyuan": BlockConfig("hunyuan", KIND_DOUBLE, n_blocks=20, d=3072, n_heads=24, head_dim=128,
                            f=12288, n_total=118800 + 256, sp_degree=2, n_txt=256, qk_rmsnorm=True,
                            n_chunks=8, temb_std=_temb_std(3072)),
+    # The MMDiT composition of a Flux-like denoiser (App. B): 19 double-stream blocks, then 38
+    # single-stream blocks over the concatenated 512 text + 4096 image tokens, P=2.
+    "flux_mm": BlockConfig("flux_mm", KIND_SINGLE, n_blocks=57, d=3072, n_heads=24, head_dim=128, f=12288,
+                           n_total=4608, sp_degree=2, n_txt=512, qk_rmsnorm=True, n_chunks=8,
+                           temb_std=_temb_std(3072), n_double=19),
+    # The same composition small enough for the CPU oracle in seconds.
+    "toy_mm": BlockConfig("toy_mm", KIND_SINGLE, n_blocks=3, d=512, n_heads=8, head_dim=64, f=2048,
+                          n_total=640, sp_degree=2, n_txt=128, qk_rmsnorm=True, n_chunks=4, temb_std=1.0,
+                          n_double=1),
 }
 
 
@@ -213,9 +234,10 @@ def gen_block_inputs(cfg: BlockConfig, block: int) -> Dict[str, np.ndarray]:
 
 def local_positions(cfg: BlockConfig) -> np.ndarray:
     """Positions, in the joint N-token sequence, of this rank's local tokens (ascending).
-    Tokens split contiguously per stream: text rows first (double-stream), then image rows."""
+    Tokens split contiguously per stream: text rows first (when the joint sequence has any), then
+    image rows."""
     r, p = cfg.sp_rank, cfg.sp_degree
-    if cfg.kind == KIND_DOUBLE:
+    if cfg.n_txt > 0:
         tl = cfg.n_txt_local
         il = cfg.n_local - tl
         txt = np.arange(r * tl, (r + 1) * tl)
