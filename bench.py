@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--contention", choices=["off", "on", "pause"], default="off",
                     help="emulated all-to-all traffic on a third stream; 'pause' adds pause/resume")
     ap.add_argument("--sweep", action="store_true", help="memory-latency grid (r x chunk x contention) to stderr")
+    ap.add_argument("--tune-budget-frac", type=float, default=0.5,
+                    help="with --sweep: weight-memory budget, as a fraction of the stack's weights, handed to the tuner")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["both", "resident", "offload"], default="both")
     return ap.parse_args()
@@ -62,6 +64,27 @@ def time_steps(run, ios, steps, warmup, torch):
     run.ctx.cf_sync()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def block_times(run, ios, torch, reps=5):
+    """Per-block compute time with everything resident: events on the compute stream around each
+    block forward, median over `reps` passes."""
+    import numpy as np
+    L = len(ios)
+    run.ctx.set_resident_fraction(1.0)
+    ms = np.zeros((reps, L))
+    for rep in range(reps + 1):                       # first pass warms up
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(L + 1)]
+        evs[0].record(run.compute)
+        for l in range(L):
+            run.begin(l)
+            run.fwd(l, ios[l])
+            evs[l + 1].record(run.compute)
+        run.ctx.cf_sync()
+        torch.cuda.synchronize()
+        if rep:
+            ms[rep - 1] = [evs[l].elapsed_time(evs[l + 1]) for l in range(L)]
+    return np.median(ms, axis=0)
 
 
 def main():
@@ -221,6 +244,9 @@ def main():
     if args.sweep:
         grid = []
         link = None                       # H2D rate of the fully offloaded, uncontended point
+        # per-kind block compute time for the chunk-level model
+        bt = block_times(run, ios, torch)
+        t_comp = {k: float(np.mean([bt[b] for b in range(L) if cfg.kind_of(b) == k])) for k in set(cfg.kinds)}
         for mode in ("off", "on", "pause"):
             set_contention(mode)
             base_ms = None                # r = 1 step time of this contention mode
@@ -233,15 +259,28 @@ def main():
             if mode == "off":
                 link = blob_total / (pts[-1][1] * 1e-3)
             for r, ms, act, s2 in reversed(pts):
-                # first-order prediction (Eq. 1-3 applied per block): max(compute window, prefetch time)
+                # first-order prediction (Eq. 1-3 applied per block): max(compute window, prefetch time);
+                # chunk-level prediction: the library's walk of the two streams (uncontended link)
                 pred = L * max(base_ms / L, (1.0 - act) * blob_total / L / link * 1e3)
+                sim = run.ctx.cf_simulate(r, t_comp, link / 1e9)
                 grid.append({"contention": mode, "r": r, "actual_r": act, "step_ms": ms, "model_step_ms": pred,
+                             "sim_step_ms": sim["step_ms"] if mode == "off" else None,
                              "weight_memory_bytes": s2["weight_memory_bytes"],
                              "h2d_gbs": (s2["model_blob_bytes"] - s2["model_resident_bytes"]) / (ms * 1e-3) / 1e9,
                              "pauses": s2["pauses"]})
                 print("[sweep] " + json.dumps(grid[-1]), file=sys.stderr)
         set_contention("off")
         result["sweep"] = grid
+        # the dial (Sec. 3.3): fastest resident fraction under a weight-memory budget, then measured
+        budget = int(args.tune_budget_frac * blob_total)
+        choice = run.ctx.cf_tune(t_comp, link / 1e9, [chunk_bytes], 16, memory_budget_bytes=budget)
+        ms, act, s2 = arm(choice["r"], max(3, args.steps // 2), 1)
+        result["tune"] = {"budget_bytes": budget, "t_comp_ms_per_block": t_comp, "link_gbs": link / 1e9,
+                          "chosen_r": choice["r"], "feasible": choice["feasible"],
+                          "predicted_step_ms": choice["step_ms"], "measured_step_ms": ms,
+                          "predicted_weight_memory_bytes": choice["weight_memory_bytes"],
+                          "measured_weight_memory_bytes": s2["weight_memory_bytes"]}
+        print("[tune] " + json.dumps(result["tune"]), file=sys.stderr)
 
     # ---- CPU oracle on this host, bounded sample: one full-size block
     if not args.no_cpu_baseline:

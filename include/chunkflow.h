@@ -117,6 +117,30 @@ typedef struct {
     double bytes;                /* algorithmic HBM bytes summed over those launches (0 if n/a) */
 } cf_kernel_time;
 
+/* What the overlap model needs to know about the machine (Sec. 3.1: eta_c * P_peak and
+ * eta_p * BW enter only through these measured figures). */
+typedef struct {
+    double t_comp_ms[3];         /* compute time of one block of each cf_block_kind, everything resident */
+    double link_gbs;             /* achieved host-to-device rate of chunk copies, 1e9 bytes/s            */
+    double chunk_overhead_us;    /* fixed cost per chunk copy (launch + event), 0 if unknown             */
+} cf_machine_t;
+
+typedef struct {
+    double step_ms;              /* predicted steady-state step time                                      */
+    double compute_ms;           /* sum of the blocks' compute times                                      */
+    double exposed_ms;           /* step_ms - compute_ms: prefetch time the compute could not hide        */
+    uint64_t weight_memory_bytes;/* resident parts of all blocks + two staging slots (Sec. 3.3)           */
+    uint64_t h2d_bytes_per_step;
+    double resident_fraction;    /* byte fraction actually resident for the requested r                   */
+} cf_sim_result;
+
+typedef struct {
+    uint64_t chunk_bytes;
+    double r;
+    int32_t feasible;            /* 1 if the choice meets the constraint, 0 if nothing did (closest given) */
+    cf_sim_result sim;
+} cf_tune_choice;
+
 /* ---- context and layout (Sec. 3.2: a layer's parameters are partitioned into fixed-size chunks).
  * cf_create validates the description and plans blob layout and chunking; it touches no GPU. */
 int cf_create(const cf_model_desc* desc, cf_ctx** out);
@@ -147,6 +171,21 @@ int cf_blob_layout_of(const cf_ctx* ctx, int32_t block, cf_tensor_slot* out, int
  * pass NULL arrays to query the count. */
 int cf_plan_panels(const cf_ctx* ctx, const char* tensor, int32_t granule, int32_t n_resident_chunks,
                    int32_t* row0, int32_t* row1, int32_t* wait_chunk, int32_t* n);
+
+/* ---- overlap model at chunk granularity and the memory-latency dial (Sec. 3.1-3.3; host only).
+ * cf_simulate walks the copy stream and the compute stream of the scheduler chunk by chunk for the
+ * context's model, chunk size and block kinds: chunks of block i+1 are copied back to back while
+ * block i computes (after block i-1 released the slot), and the part of a block's compute that a
+ * chunk's bytes enable starts when the chunk has landed; the first round(r * n_chunks) chunks of
+ * every block are resident.  With one chunk per block and r = 0 the result is the sum over blocks
+ * of max(T_comp, T_pref) (Eq. 1-3).  Emulated collectives are not modelled.
+ * cf_tune evaluates chunk_candidates x {0, 1/r_steps, ..., 1} and returns, under a memory budget
+ * (step_target_ms = 0), the fastest point that fits, or, under a step-time target
+ * (memory_budget_bytes = 0), the point with the least weight memory that meets it.  Exactly one of
+ * the two constraints must be given. */
+int cf_simulate(const cf_ctx* ctx, double r, const cf_machine_t* machine, cf_sim_result* out);
+int cf_tune(const cf_ctx* ctx, const cf_machine_t* machine, const uint64_t* chunk_candidates, int32_t n_candidates,
+            int32_t r_steps, uint64_t memory_budget_bytes, double step_target_ms, cf_tune_choice* out);
 
 /* ---- weights (Sec. 2.2: all layers are placed in pinned host memory at initialisation).
  * host_blob must be pinned (hipHostMalloc), hold exactly cf_blob_bytes and outlive the context. */

@@ -68,3 +68,42 @@ def chunk_checksums(blob: np.ndarray, chunk_bytes: int):
     """Per-chunk checksums of a host blob (uint8 array)."""
     b = np.ascontiguousarray(blob).view(np.uint8).reshape(-1)
     return [checksum_words(b[s:e], s // 8) for s, e in chunk_bounds(len(b), chunk_bytes)]
+
+
+# ---------------------------------------------------------------- blob layout (this build's own)
+
+def blob_layout(cfg):
+    """[(name, offset, rows, cols)] of one block's bf16 tensors inside its blob.
+
+    The paper fixes no layout.  This build packs a block's parameters in the order the block
+    consumes them, small vectors ahead of the matrix they go with, every tensor on a 256-byte
+    boundary and the blob padded to one, so that a prefix of chunks is a prefix of the
+    computation (Sec. 3.2).  Matrices are [out_features, in_features].  A double-stream block
+    lists the text stream before the image stream inside every stage."""
+    d, f, hd = cfg.d, cfg.f, cfg.head_dim
+    norms = lambda pre: ([(pre + "q_norm", 1, hd), (pre + "k_norm", 1, hd)] if cfg.qk_rmsnorm else [])
+    if cfg.kind == 0:      # single-stream
+        ts = [("b_mod", 1, 3 * d), ("w_mod", 3 * d, d), ("b1", 1, 3 * d + f)] + norms("") + \
+             [("w1", 3 * d + f, d), ("b2", 1, d), ("w2", d, d + f)]
+    elif cfg.kind == 1:    # DiT with cross-attention
+        ts = [("b_mod", 1, 6 * d), ("w_mod", 6 * d, d), ("b_qkv", 1, 3 * d)] + norms("") + \
+             [("w_qkv", 3 * d, d), ("b_o", 1, d), ("w_o", d, d), ("ln_c_w", 1, d), ("ln_c_b", 1, d), ("b_cq", 1, d)] + \
+             norms("c") + \
+             [("w_cq", d, d), ("b_ckv", 1, 2 * d), ("w_ckv", 2 * d, d), ("b_co", 1, d), ("w_co", d, d),
+              ("b_up", 1, f), ("w_up", f, d), ("b_down", 1, d), ("w_down", d, f)]
+    else:                  # double-stream
+        ts = []
+        for s in ("txt_", "img_"):
+            ts += [(s + "b_mod", 1, 6 * d), (s + "w_mod", 6 * d, d)]
+        for s in ("txt_", "img_"):
+            ts += [(s + "b_qkv", 1, 3 * d)] + norms(s) + [(s + "w_qkv", 3 * d, d)]
+        for s in ("txt_", "img_"):
+            ts += [(s + "b_o", 1, d), (s + "w_o", d, d)]
+        for s in ("txt_", "img_"):
+            ts += [(s + "b_up", 1, f), (s + "w_up", f, d), (s + "b_down", 1, d), (s + "w_down", d, f)]
+    out, off = [], 0
+    for name, rows, cols in ts:
+        off = -(-off // 256) * 256
+        out.append((name, off, rows, cols))
+        off += 2 * rows * cols
+    return out, -(-off // 256) * 256

@@ -145,3 +145,98 @@ def exposed_time(t_comp_block, b_pref, n_blocks, plat: Platform, resident_fracti
 def weight_memory(blob_bytes, n_blocks, resident_fraction):
     """Resident share of every block plus two staging slots for the streamed share."""
     return resident_fraction * n_blocks * blob_bytes + 2 * (1.0 - resident_fraction) * blob_bytes
+
+
+# ---------------------------------------------------------------- chunk-level walk (parity unpinned)
+
+def segment_shares(cfg, layout, blob_bytes, chunk_bytes):
+    """Share of one block's compute that each chunk completes (sums to 1).
+
+    A weight matrix contributes its App. B term, 2 * rows_of_activations * out * in FLOPs.  The
+    scheduler runs a linear layer in panels of whole row groups, a group being as many output
+    features as it takes, in 256-wide tiles, to give 256 tiles together with the 256-row token
+    tiles (a launch that covers the chip less than once is no faster than one that covers it
+    once); a group is booked on the chunk that holds its last byte.  The modulation matrix
+    multiplies a single vector and goes 8 rows at a time.  The joint attention term
+    (4 * H_local * N^2 * hd for this rank's heads) is booked on the chunk that completes the QKV
+    projection, the DiT block's cross-attention term (4 * H * n_local * L_ctx * hd) on the chunk
+    that completes the context K/V projection."""
+    n_chunks = -(-blob_bytes // chunk_bytes)
+    seg = [0.0] * n_chunks
+    nl = cfg.n_total / cfg.sp_degree
+    tl = cfg.n_txt / cfg.sp_degree
+    for name, off, rows, cols in layout:
+        if rows == 1:
+            continue
+        if name.endswith("w_mod"):
+            act, group = 1.0, 8
+        else:
+            if cfg.kind == 1:
+                act = cfg.l_ctx if name == "w_ckv" else nl
+            elif cfg.kind == 2:
+                act = tl if name.startswith("txt_") else nl - tl
+            else:
+                act = nl
+            token_tiles = max(1, -(-int(act) // 256))
+            group = 256 * -(-256 // token_tiles)
+        for r0 in range(0, rows, group):
+            r1 = min(rows, r0 + group)
+            seg[(off + r1 * 2 * cols - 1) // chunk_bytes] += 2.0 * act * (r1 - r0) * cols
+        end = off + 2 * rows * cols
+        if name in ("w1", "w_qkv", "img_w_qkv"):
+            seg[(end - 1) // chunk_bytes] += 4.0 * (cfg.n_heads / cfg.sp_degree) * cfg.n_total * cfg.n_total * cfg.head_dim
+        if name == "w_ckv":
+            seg[(end - 1) // chunk_bytes] += 4.0 * cfg.n_heads * nl * cfg.l_ctx * cfg.head_dim
+    total = sum(seg)
+    return [v / total for v in seg]
+
+
+def simulate_step(blocks, chunk_bytes, r, link_gbs, chunk_overhead_us=0.0, n_steps=4):
+    """Steady-state step time of the two-stream schedule, chunk by chunk.
+
+    blocks: one dict per block of the stack with 'blob_bytes', 't_comp_ms' and 'shares' (per-chunk
+    compute shares).  Copy stream: the streamed chunks of block i+1 are copied in order once the
+    prefetch has been issued (start of block i, Sec. 2.2), the chunks of block i are out and block
+    i-1, the last tenant of the slot, has finished.  Compute stream: segment k of a block starts
+    when segment k-1 has ended and, unless chunk k is resident (the first round(r*n_chunks) chunks,
+    Sec. 3.3), when chunk k has landed.  Returns (step_ms, exposed_ms, weight_memory_bytes)."""
+    L = len(blocks)
+    ms_per_byte = 1e3 / (link_gbs * 1e9)
+    info = []
+    for b in blocks:
+        n = -(-b["blob_bytes"] // chunk_bytes)
+        n_res = int((r * n + 0.5) // 1)
+        res_bytes = min(b["blob_bytes"], n_res * chunk_bytes)
+        sizes = [min(chunk_bytes, b["blob_bytes"] - k * chunk_bytes) for k in range(n)]
+        info.append((n, n_res, res_bytes, sizes))
+    finish = {}            # block instance -> end of its compute
+    landed = {}            # block instance -> landing time of each streamed chunk
+    link_free = 0.0
+
+    def copy(i, issued):
+        nonlocal link_free
+        n, n_res, _, sizes = info[i % L]
+        t = max(link_free, issued, finish.get(i - 2, 0.0))
+        times = {}
+        for k in range(n_res, n):
+            t += chunk_overhead_us * 1e-3 + sizes[k] * ms_per_byte
+            times[k] = t
+        landed[i] = times
+        link_free = t
+
+    copy(0, 0.0)
+    total = n_steps * L
+    for i in range(total):
+        start = finish.get(i - 1, 0.0)
+        if i + 1 < total:
+            copy(i + 1, start)
+        t = start
+        b = blocks[i % L]
+        for k, share in enumerate(b["shares"]):
+            t = max(t, landed[i].get(k, 0.0)) + share * b["t_comp_ms"]
+        finish[i] = t
+    step = finish[total - 1] - finish[total - 1 - L]
+    compute = sum(b["t_comp_ms"] for b in blocks)
+    slot = max(b["blob_bytes"] - inf[2] for b, inf in zip(blocks, info))
+    memory = sum(inf[2] for inf in info) + 2 * slot
+    return step, step - compute, memory

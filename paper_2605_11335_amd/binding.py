@@ -50,10 +50,24 @@ class cf_kernel_time(C.Structure):
                 ("flops", C.c_double), ("bytes", C.c_double)]
 
 
+class cf_machine_t(C.Structure):
+    _fields_ = [("t_comp_ms", C.c_double * 3), ("link_gbs", C.c_double), ("chunk_overhead_us", C.c_double)]
+
+
+class cf_sim_result(C.Structure):
+    _fields_ = [("step_ms", C.c_double), ("compute_ms", C.c_double), ("exposed_ms", C.c_double),
+                ("weight_memory_bytes", C.c_uint64), ("h2d_bytes_per_step", C.c_uint64),
+                ("resident_fraction", C.c_double)]
+
+
+class cf_tune_choice(C.Structure):
+    _fields_ = [("chunk_bytes", C.c_uint64), ("r", C.c_double), ("feasible", C.c_int32), ("sim", cf_sim_result)]
+
+
 #: every symbol include/chunkflow.h declares
 EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_chunks", "cf_blob_layout",
            "cf_set_block_kinds", "cf_block_kind_of", "cf_blob_bytes_of", "cf_n_chunks_of", "cf_blob_layout_of",
-           "cf_workspace_bytes", "cf_plan_panels", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
+           "cf_workspace_bytes", "cf_plan_panels", "cf_simulate", "cf_tune", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
            "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
            "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling",
            "cf_kernel_times", "cf_kernel_times_reset", "cf_sync", "cf_op_linear", "cf_op_linear_residual",
@@ -90,6 +104,9 @@ def lib() -> C.CDLL:
                                         C.POINTER(C.c_int32)]
         _lib.cf_register_block.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64]
         _lib.cf_set_block_kinds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
+        _lib.cf_simulate.argtypes = [C.c_void_p, C.c_double, C.POINTER(cf_machine_t), C.POINTER(cf_sim_result)]
+        _lib.cf_tune.argtypes = [C.c_void_p, C.POINTER(cf_machine_t), C.c_void_p, C.c_int32, C.c_int32, C.c_uint64,
+                                 C.c_double, C.POINTER(cf_tune_choice)]
         _lib.cf_block_kind_of.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.cf_blob_bytes_of.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         _lib.cf_n_chunks_of.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
@@ -193,6 +210,32 @@ class Context:
         r0, r1, w = (C.c_int32 * n.value)(), (C.c_int32 * n.value)(), (C.c_int32 * n.value)()
         _check(lib().cf_plan_panels(self._h, tensor.encode(), granule, n_resident_chunks, r0, r1, w, C.byref(n)), self._h)
         return [(r0[i], r1[i], w[i]) for i in range(n.value)]
+
+    # ---- overlap model
+    @staticmethod
+    def _machine(t_comp_ms, link_gbs: float, chunk_overhead_us: float = 0.0) -> cf_machine_t:
+        """t_comp_ms: per-block compute time, one number or {kind: ms}."""
+        t = [float(t_comp_ms)] * 3 if not isinstance(t_comp_ms, dict) else [float(t_comp_ms.get(k, 0.0)) for k in range(3)]
+        return cf_machine_t((C.c_double * 3)(*t), link_gbs, chunk_overhead_us)
+
+    @staticmethod
+    def _sim_dict(s: cf_sim_result) -> dict:
+        return {n: getattr(s, n) for n, _ in cf_sim_result._fields_}
+
+    def cf_simulate(self, r: float, t_comp_ms, link_gbs: float, chunk_overhead_us: float = 0.0) -> dict:
+        out = cf_sim_result()
+        m = self._machine(t_comp_ms, link_gbs, chunk_overhead_us)
+        _check(lib().cf_simulate(self._h, r, C.byref(m), C.byref(out)), self._h)
+        return self._sim_dict(out)
+
+    def cf_tune(self, t_comp_ms, link_gbs: float, chunk_candidates, r_steps: int, memory_budget_bytes: int = 0,
+                step_target_ms: float = 0.0, chunk_overhead_us: float = 0.0) -> dict:
+        out = cf_tune_choice()
+        m = self._machine(t_comp_ms, link_gbs, chunk_overhead_us)
+        cand = (C.c_uint64 * len(chunk_candidates))(*[int(v) for v in chunk_candidates])
+        _check(lib().cf_tune(self._h, C.byref(m), cand, len(chunk_candidates), r_steps, memory_budget_bytes,
+                             step_target_ms, C.byref(out)), self._h)
+        return dict(chunk_bytes=out.chunk_bytes, r=out.r, feasible=bool(out.feasible), **self._sim_dict(out.sim))
 
     def cf_blob_layout(self, block: int = 0) -> List[dict]:
         n = C.c_int32(0)

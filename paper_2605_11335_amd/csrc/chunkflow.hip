@@ -9,11 +9,9 @@
 
 #include "context.h"
 
-namespace {
+static std::string g_create_err;
 
-std::string g_create_err;
-
-int fail(const cf_ctx* c, int code, const char* fmt, ...) {
+int cf_fail(const cf_ctx* c, int code, const char* fmt, ...) {
     char buf[512];
     va_list ap;
     va_start(ap, fmt);
@@ -23,17 +21,13 @@ int fail(const cf_ctx* c, int code, const char* fmt, ...) {
     return code;
 }
 
+namespace {
+
 #define CF_HIP(c, call)                                                                                  \
     do {                                                                                                 \
         hipError_t e_ = (call);                                                                          \
-        if (e_ != hipSuccess) return fail((c), CF_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+        if (e_ != hipSuccess) return cf_fail((c), CF_ERR_HIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
     } while (0)
-#define CF_TRY(expr)                  \
-    do {                              \
-        int rc_ = (expr);             \
-        if (rc_ != CF_OK) return rc_; \
-    } while (0)
-
 inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 // ------------------------------------------------------------------------------------------
@@ -44,6 +38,16 @@ void add_tensor(Plan* c, const std::string& name, uint32_t rows, uint32_t cols) 
     TensorDesc t{name, align_up(c->blob_bytes, 256), rows, cols};
     c->blob_bytes = t.off + t.bytes();
     c->tensors.push_back(t);
+}
+
+}  // namespace
+
+// Rows of output features per panel of a linear layer on `m_rows` tokens.  A launch that covers
+// the chip less than once takes as long as one that covers it exactly once, so panels are made
+// of whole rounds: enough 256-wide feature tiles that, times the token tiles, there are 256.
+int cf_panel_granule(int m_rows) {
+    const int tiles_m = std::max(1, (m_rows + 255) / 256);
+    return 256 * ((256 + tiles_m - 1) / tiles_m);
 }
 
 void plan_layout(Plan* c, const cf_model_desc& m, int kind, uint64_t chunk_bytes) {
@@ -99,6 +103,8 @@ void plan_layout(Plan* c, const cf_model_desc& m, int kind, uint64_t chunk_bytes
     c->blob_bytes = align_up(c->blob_bytes, 256);
     c->n_chunks = (int)((c->blob_bytes + chunk_bytes - 1) / chunk_bytes);
 }
+
+namespace {
 
 // ------------------------------------------------------------------------------------------
 // workspace carving (same function plans the size and hands out the pointers)
@@ -184,7 +190,7 @@ int upload_resident(cf_ctx* c, int block) {
     if (!c->res_buf[block]) {
         if (hipMalloc((void**)&c->res_buf[block], res_bytes) != hipSuccess) {
             (void)hipGetLastError();
-            return fail(c, CF_ERR_NOMEM, "hipMalloc of %llu resident bytes for block %d failed",
+            return cf_fail(c, CF_ERR_NOMEM, "hipMalloc of %llu resident bytes for block %d failed",
                         (unsigned long long)res_bytes, block);
         }
     }
@@ -284,11 +290,11 @@ int wait_chunk(cf_ctx* c, int block, int k, hipStream_t s) {
     if (k < c->P(block).n_res_chunks) return CF_OK;
     const int sl = c->block_slot[block];
     if (sl < 0 || c->slot_tenant[sl] != block || c->slot_state[sl] == SLOT_EMPTY)
-        return fail(c, CF_ERR_STATE, "block %d: chunk %d awaited but its prefetch was not begun", block, k);
+        return cf_fail(c, CF_ERR_STATE, "block %d: chunk %d awaited but its prefetch was not begun", block, k);
     if (c->worker.joinable()) {
         std::unique_lock<std::mutex> lk(c->mu);
         c->cv.wait(lk, [&] { return c->enq_count[sl] > k; });
-        if (!c->worker_err.empty()) return fail(c, CF_ERR_HIP, "prefetch worker: %s", c->worker_err.c_str());
+        if (!c->worker_err.empty()) return cf_fail(c, CF_ERR_HIP, "prefetch worker: %s", c->worker_err.c_str());
     }
     CF_HIP(c, hipStreamWaitEvent(s, c->chunk_ev[sl][k], 0));
     return CF_OK;
@@ -457,11 +463,11 @@ int run_linear(Fwd& F, int kid, const std::string& wname, const std::string& bna
     g.N = (int)w.rows;
     g.K = (int)w.cols;
     if (g.epi == EPI_SPLIT_GELU && g.n_split > g.N) g.n_split = g.N;
-    return panels(F, w, 256, [&](int r0, int r1) -> int {
+    return panels(F, w, cf_panel_granule(g.M), [&](int r0, int r1) -> int {
         GemmArgs p = g;
         p.n0 = r0;
         p.n1 = r1;
-        if (const char* msg = gemm_check(p)) return fail(F.c, CF_ERR_ARG, "%s (%s)", msg, wname.c_str());
+        if (const char* msg = gemm_check(p)) return cf_fail(F.c, CF_ERR_ARG, "%s (%s)", msg, wname.c_str());
         ProfScope ps(F.c, F.s, kid, 2.0 * p.M * (r1 - r0) * p.K, 0, gemm_tile(p));
         CF_HIP(F.c, gemm_launch(p, F.s));
         return CF_OK;
@@ -511,7 +517,7 @@ int run_joint_attention(Fwd& F, const RelayoutArgs* parts, int n_parts, bf16* ds
     const int npad = n_pad_of(m.n_total);
     const cf_block_io* io = F.io;
     if (P > 1 && (!io->peer_q || !io->peer_k || !io->peer_v || !io->peer_attn))
-        return fail(c, CF_ERR_ARG, "sp_degree > 1 needs peer_q, peer_k, peer_v and peer_attn");
+        return cf_fail(c, CF_ERR_ARG, "sp_degree > 1 needs peer_q, peer_k, peer_v and peer_attn");
     {
         double bytes = 0;
         for (int i = 0; i < n_parts; ++i) bytes += 2.0 * 2 * parts[i].rows * 3.0 * m.d;
@@ -527,7 +533,7 @@ int run_joint_attention(Fwd& F, const RelayoutArgs* parts, int n_parts, bf16* ds
     a.scale = 1.0f / sqrtf((float)hd);
     if (P == 1) { a.O = dst; a.o_hs = hd; a.o_qs = ld; }
     else { a.O = F.ws.O; a.o_hs = (long)m.n_total * hd; a.o_qs = hd; }
-    if (const char* msg = attn_check(a)) return fail(c, CF_ERR_ARG, "%s", msg);
+    if (const char* msg = attn_check(a)) return cf_fail(c, CF_ERR_ARG, "%s", msg);
     {
         ProfScope ps(c, F.s, K_ATTN, 4.0 * hl * (double)m.n_total * m.n_total * hd, 0);
         CF_HIP(c, attn_launch(a, F.s));
@@ -587,27 +593,27 @@ int fwd_dit(Fwd& F);
 int fwd_double(Fwd& F);
 
 int check_desc(const cf_model_desc* m) {
-    if (!m) return fail(nullptr, CF_ERR_ARG, "null description");
-    if (m->kind < 0 || m->kind > 2) return fail(nullptr, CF_ERR_ARG, "unknown block kind %d", m->kind);
-    if (m->n_blocks <= 0) return fail(nullptr, CF_ERR_ARG, "n_blocks must be positive");
-    if (m->head_dim != 64 && m->head_dim != 128) return fail(nullptr, CF_ERR_ARG, "head_dim must be 64 or 128");
-    if (m->n_heads <= 0 || m->d != m->n_heads * m->head_dim) return fail(nullptr, CF_ERR_ARG, "d must equal n_heads * head_dim");
-    if (m->d % 256 || m->d > 4096) return fail(nullptr, CF_ERR_ARG, "d must be a multiple of 256, at most 4096");
+    if (!m) return cf_fail(nullptr, CF_ERR_ARG, "null description");
+    if (m->kind < 0 || m->kind > 2) return cf_fail(nullptr, CF_ERR_ARG, "unknown block kind %d", m->kind);
+    if (m->n_blocks <= 0) return cf_fail(nullptr, CF_ERR_ARG, "n_blocks must be positive");
+    if (m->head_dim != 64 && m->head_dim != 128) return cf_fail(nullptr, CF_ERR_ARG, "head_dim must be 64 or 128");
+    if (m->n_heads <= 0 || m->d != m->n_heads * m->head_dim) return cf_fail(nullptr, CF_ERR_ARG, "d must equal n_heads * head_dim");
+    if (m->d % 256 || m->d > 4096) return cf_fail(nullptr, CF_ERR_ARG, "d must be a multiple of 256, at most 4096");
     const int nj = m->d / 256;
     if (!(nj == 1 || nj == 2 || nj == 3 || nj == 4 || nj == 6 || nj == 8 || nj == 12 || nj == 16))
-        return fail(nullptr, CF_ERR_ARG, "d/256 must be one of 1,2,3,4,6,8,12,16");
-    if (m->f <= 0 || m->f % 64) return fail(nullptr, CF_ERR_ARG, "f must be a positive multiple of 64");
-    if (m->sp_degree <= 0 || m->sp_rank < 0 || m->sp_rank >= m->sp_degree) return fail(nullptr, CF_ERR_ARG, "bad sp_degree/sp_rank");
-    if (m->n_heads % m->sp_degree) return fail(nullptr, CF_ERR_ARG, "sp_degree must divide n_heads");
-    if (m->n_total <= 0 || m->n_total % m->sp_degree) return fail(nullptr, CF_ERR_ARG, "sp_degree must divide n_total");
-    if (m->kind == CF_DOUBLE_STREAM && m->n_txt_total <= 0) return fail(nullptr, CF_ERR_ARG, "double-stream needs n_txt_total > 0");
+        return cf_fail(nullptr, CF_ERR_ARG, "d/256 must be one of 1,2,3,4,6,8,12,16");
+    if (m->f <= 0 || m->f % 64) return cf_fail(nullptr, CF_ERR_ARG, "f must be a positive multiple of 64");
+    if (m->sp_degree <= 0 || m->sp_rank < 0 || m->sp_rank >= m->sp_degree) return cf_fail(nullptr, CF_ERR_ARG, "bad sp_degree/sp_rank");
+    if (m->n_heads % m->sp_degree) return cf_fail(nullptr, CF_ERR_ARG, "sp_degree must divide n_heads");
+    if (m->n_total <= 0 || m->n_total % m->sp_degree) return cf_fail(nullptr, CF_ERR_ARG, "sp_degree must divide n_total");
+    if (m->kind == CF_DOUBLE_STREAM && m->n_txt_total <= 0) return cf_fail(nullptr, CF_ERR_ARG, "double-stream needs n_txt_total > 0");
     if (m->n_txt_total) {
-        if (m->kind == CF_DIT_CROSS) return fail(nullptr, CF_ERR_ARG, "n_txt_total has no meaning for DiT blocks");
+        if (m->kind == CF_DIT_CROSS) return cf_fail(nullptr, CF_ERR_ARG, "n_txt_total has no meaning for DiT blocks");
         if (m->n_txt_total < 0 || m->n_txt_total >= m->n_total || m->n_txt_total % m->sp_degree)
-            return fail(nullptr, CF_ERR_ARG, "need 0 < n_txt_total < n_total, divisible by sp_degree");
+            return cf_fail(nullptr, CF_ERR_ARG, "need 0 < n_txt_total < n_total, divisible by sp_degree");
     }
-    if (m->kind == CF_DIT_CROSS && m->l_ctx <= 0) return fail(nullptr, CF_ERR_ARG, "DiT block needs l_ctx > 0");
-    if (m->chunk_bytes == 0 || m->chunk_bytes % 256) return fail(nullptr, CF_ERR_ARG, "chunk_bytes must be a positive multiple of 256");
+    if (m->kind == CF_DIT_CROSS && m->l_ctx <= 0) return cf_fail(nullptr, CF_ERR_ARG, "DiT block needs l_ctx > 0");
+    if (m->chunk_bytes == 0 || m->chunk_bytes % 256) return cf_fail(nullptr, CF_ERR_ARG, "chunk_bytes must be a positive multiple of 256");
     return CF_OK;
 }
 
@@ -628,7 +634,7 @@ void plan_model(cf_ctx* c) {
 
 int check_block(const cf_ctx* c, int block) {
     if (!c) return CF_ERR_ARG;
-    if (block < 0 || block >= c->d.n_blocks) return fail(c, CF_ERR_ARG, "block %d out of range [0,%d)", block, c->d.n_blocks);
+    if (block < 0 || block >= c->d.n_blocks) return cf_fail(c, CF_ERR_ARG, "block %d out of range [0,%d)", block, c->d.n_blocks);
     return CF_OK;
 }
 
@@ -640,11 +646,11 @@ int check_block(const cf_ctx* c, int block) {
 extern "C" {
 
 int cf_create(const cf_model_desc* desc, cf_ctx** out) {
-    if (!out) return fail(nullptr, CF_ERR_ARG, "null out pointer");
+    if (!out) return cf_fail(nullptr, CF_ERR_ARG, "null out pointer");
     *out = nullptr;
     CF_TRY(check_desc(desc));
     cf_ctx* c = new (std::nothrow) cf_ctx();
-    if (!c) return fail(nullptr, CF_ERR_NOMEM, "out of host memory");
+    if (!c) return cf_fail(nullptr, CF_ERR_NOMEM, "out of host memory");
     c->d = *desc;
     c->chunk_bytes = desc->chunk_bytes;
     c->block_kind.assign(desc->n_blocks, desc->kind);
@@ -681,12 +687,12 @@ const char* cf_last_error(const cf_ctx* c) { return c ? c->err.c_str() : g_creat
 
 int cf_set_block_kinds(cf_ctx* c, const int32_t* kinds, int32_t n) {
     if (!c || !kinds) return CF_ERR_ARG;
-    if (n != c->d.n_blocks) return fail(c, CF_ERR_ARG, "%d kinds given for %d blocks", n, c->d.n_blocks);
-    if (c->device_ready) return fail(c, CF_ERR_STATE, "block kinds must be set before any block is registered");
+    if (n != c->d.n_blocks) return cf_fail(c, CF_ERR_ARG, "%d kinds given for %d blocks", n, c->d.n_blocks);
+    if (c->device_ready) return cf_fail(c, CF_ERR_STATE, "block kinds must be set before any block is registered");
     for (int b = 0; b < n; ++b) {
-        if (kinds[b] < 0 || kinds[b] > 2) return fail(c, CF_ERR_ARG, "block %d: unknown kind %d", b, kinds[b]);
-        if (kinds[b] == CF_DOUBLE_STREAM && c->d.n_txt_total <= 0) return fail(c, CF_ERR_ARG, "block %d: double-stream needs n_txt_total > 0", b);
-        if (kinds[b] == CF_DIT_CROSS && (c->d.l_ctx <= 0 || c->d.n_txt_total)) return fail(c, CF_ERR_ARG, "block %d: DiT block needs l_ctx > 0 and no text rows", b);
+        if (kinds[b] < 0 || kinds[b] > 2) return cf_fail(c, CF_ERR_ARG, "block %d: unknown kind %d", b, kinds[b]);
+        if (kinds[b] == CF_DOUBLE_STREAM && c->d.n_txt_total <= 0) return cf_fail(c, CF_ERR_ARG, "block %d: double-stream needs n_txt_total > 0", b);
+        if (kinds[b] == CF_DIT_CROSS && (c->d.l_ctx <= 0 || c->d.n_txt_total)) return cf_fail(c, CF_ERR_ARG, "block %d: DiT block needs l_ctx > 0 and no text rows", b);
     }
     c->block_kind.assign(kinds, kinds + n);
     plan_model(c);
@@ -720,7 +726,7 @@ int cf_blob_layout_of(const cf_ctx* c, int32_t block, cf_tensor_slot* out, int32
     const std::vector<TensorDesc>& ts = c->P(block).tensors;
     const int cnt = (int)ts.size();
     if (out) {
-        if (*n < cnt) return fail(c, CF_ERR_ARG, "layout needs room for %d tensors", cnt);
+        if (*n < cnt) return cf_fail(c, CF_ERR_ARG, "layout needs room for %d tensors", cnt);
         for (int i = 0; i < cnt; ++i) {
             memset(&out[i], 0, sizeof out[i]);
             snprintf(out[i].name, sizeof out[i].name, "%s", ts[i].name.c_str());
@@ -741,11 +747,11 @@ int cf_plan_panels(const cf_ctx* c, const char* tensor, int32_t granule, int32_t
                    int32_t* row1, int32_t* wait_chunk_out, int32_t* n) {
     if (!c || !tensor || !n || granule <= 0) return CF_ERR_ARG;
     const TensorDesc* t = cf_find(c->P(0), tensor);
-    if (!t) return fail(c, CF_ERR_ARG, "no tensor named %s in the blob", tensor);
-    if (n_resident_chunks < 0 || n_resident_chunks > c->P(0).n_chunks) return fail(c, CF_ERR_ARG, "resident chunk count out of range");
+    if (!t) return cf_fail(c, CF_ERR_ARG, "no tensor named %s in the blob", tensor);
+    if (n_resident_chunks < 0 || n_resident_chunks > c->P(0).n_chunks) return cf_fail(c, CF_ERR_ARG, "resident chunk count out of range");
     const std::vector<Panel> plan = plan_panels(c, *t, granule, n_resident_chunks - 1);
     if (row0 && row1 && wait_chunk_out) {
-        if (*n < (int)plan.size()) return fail(c, CF_ERR_ARG, "need room for %d panels", (int)plan.size());
+        if (*n < (int)plan.size()) return cf_fail(c, CF_ERR_ARG, "need room for %d panels", (int)plan.size());
         for (size_t i = 0; i < plan.size(); ++i) { row0[i] = plan[i].row0; row1[i] = plan[i].row1; wait_chunk_out[i] = plan[i].wait; }
     }
     *n = (int)plan.size();
@@ -760,14 +766,14 @@ int cf_workspace_bytes(const cf_ctx* c, uint64_t* out) {
 
 int cf_register_block(cf_ctx* c, int32_t block, const void* host_blob, uint64_t bytes) {
     CF_TRY(check_block(c, block));
-    if (!host_blob) return fail(c, CF_ERR_ARG, "null host blob");
+    if (!host_blob) return cf_fail(c, CF_ERR_ARG, "null host blob");
     if (bytes != c->P(block).blob_bytes)
-        return fail(c, CF_ERR_ARG, "blob is %llu bytes, layout needs %llu", (unsigned long long)bytes, (unsigned long long)c->P(block).blob_bytes);
+        return cf_fail(c, CF_ERR_ARG, "blob is %llu bytes, layout needs %llu", (unsigned long long)bytes, (unsigned long long)c->P(block).blob_bytes);
     hipPointerAttribute_t attr;
     hipError_t e = hipPointerGetAttributes(&attr, host_blob);
     if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
         (void)hipGetLastError();
-        return fail(c, CF_ERR_ARG, "host blob must be pinned host memory (hipHostMalloc)");
+        return cf_fail(c, CF_ERR_ARG, "host blob must be pinned host memory (hipHostMalloc)");
     }
     CF_TRY(ensure_device(c));
     worker_drain(c);
@@ -777,7 +783,7 @@ int cf_register_block(cf_ctx* c, int32_t block, const void* host_blob, uint64_t 
 
 int set_resident_fraction(cf_ctx* c, double r, double* actual) {
     if (!c) return CF_ERR_ARG;
-    if (!(r >= 0.0 && r <= 1.0)) return fail(c, CF_ERR_ARG, "resident fraction %g outside [0,1]", r);
+    if (!(r >= 0.0 && r <= 1.0)) return cf_fail(c, CF_ERR_ARG, "resident fraction %g outside [0,1]", r);
     // per kind: the leading round(r * n_chunks) chunks; the fraction reported is over the whole model
     int n_res[3] = {0, 0, 0};
     uint64_t res_bytes[3] = {0, 0, 0}, slot_bytes = 0;
@@ -802,7 +808,7 @@ int set_resident_fraction(cf_ctx* c, double r, double* actual) {
         for (int s = 0; s < 2; ++s)
             if (hipMalloc((void**)&c->slot[s], slot_bytes) != hipSuccess) {
                 (void)hipGetLastError();
-                return fail(c, CF_ERR_NOMEM, "hipMalloc of a %llu-byte staging slot failed", (unsigned long long)slot_bytes);
+                return cf_fail(c, CF_ERR_NOMEM, "hipMalloc of a %llu-byte staging slot failed", (unsigned long long)slot_bytes);
             }
     }
     for (int b = 0; b < c->d.n_blocks; ++b) CF_TRY(upload_resident(c, b));
@@ -811,15 +817,15 @@ int set_resident_fraction(cf_ctx* c, double r, double* actual) {
 
 int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
     CF_TRY(check_block(c, block));
-    if (!c->host[block]) return fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
+    if (!c->host[block]) return cf_fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
     CF_TRY(ensure_device(c));
     if (c->P(block).n_res_chunks == c->P(block).n_chunks) return CF_OK;   // 100 % resident: nothing to move
     if (!c->slot[0]) CF_TRY(set_resident_fraction(c, 0.0, nullptr));
     if (c->block_slot[block] >= 0 && c->slot_state[c->block_slot[block]] == SLOT_FILLED)
-        return fail(c, CF_ERR_STATE, "block %d is already prefetched and waiting for its forward", block);
+        return cf_fail(c, CF_ERR_STATE, "block %d is already prefetched and waiting for its forward", block);
     const int s = c->next_slot;                                    // slots alternate per prefetch
     if (c->slot_state[s] == SLOT_FILLED)
-        return fail(c, CF_ERR_STATE, "slot %d still holds block %d whose forward has not been issued", s, c->slot_tenant[s]);
+        return cf_fail(c, CF_ERR_STATE, "slot %d still holds block %d whose forward has not been issued", s, c->slot_tenant[s]);
     // Bound how far the host runs ahead of the GPU: the block that last finished in the OTHER slot
     // (two forwards back) must be done before more work is queued.  The GPU still has one whole
     // block of queued work, so it never starves, and the runtime's queues never fill up -- a host
@@ -846,7 +852,7 @@ int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
 int chunked_prefetch_wait(cf_ctx* c, int32_t block, int32_t chunk, void* compute_stream) {
     CF_TRY(check_block(c, block));
     const Plan& p = c->P(block);
-    if (chunk < -1 || chunk >= p.n_chunks) return fail(c, CF_ERR_ARG, "chunk %d out of range", chunk);
+    if (chunk < -1 || chunk >= p.n_chunks) return cf_fail(c, CF_ERR_ARG, "chunk %d out of range", chunk);
     const int last = chunk < 0 ? p.n_chunks - 1 : chunk;
     if (last < p.n_res_chunks) return CF_OK;
     // the copy stream is in order: waiting for `last` covers every earlier chunk
@@ -855,20 +861,20 @@ int chunked_prefetch_wait(cf_ctx* c, int32_t block, int32_t chunk, void* compute
 
 int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute_stream) {
     CF_TRY(check_block(c, block));
-    if (!io) return fail(c, CF_ERR_ARG, "null io");
-    if (!io->x || !io->temb || !io->y) return fail(c, CF_ERR_ARG, "x, temb and y are required");
+    if (!io) return cf_fail(c, CF_ERR_ARG, "null io");
+    if (!io->x || !io->temb || !io->y) return cf_fail(c, CF_ERR_ARG, "x, temb and y are required");
     if (!io->workspace || io->workspace_bytes < c->ws_bytes || ((uintptr_t)io->workspace % 256))
-        return fail(c, CF_ERR_ARG, "workspace must be 256-byte aligned and at least %llu bytes", (unsigned long long)c->ws_bytes);
-    if (((uintptr_t)io->x | (uintptr_t)io->y | (uintptr_t)io->temb) % 16) return fail(c, CF_ERR_ARG, "x, y, temb must be 16-byte aligned");
+        return cf_fail(c, CF_ERR_ARG, "workspace must be 256-byte aligned and at least %llu bytes", (unsigned long long)c->ws_bytes);
+    if (((uintptr_t)io->x | (uintptr_t)io->y | (uintptr_t)io->temb) % 16) return cf_fail(c, CF_ERR_ARG, "x, y, temb must be 16-byte aligned");
     const Plan& p = c->P(block);
-    if (p.kind == CF_DOUBLE_STREAM && (!io->x_txt || !io->y_txt)) return fail(c, CF_ERR_ARG, "double-stream needs x_txt and y_txt");
-    if (p.kind == CF_DIT_CROSS && !io->ctx) return fail(c, CF_ERR_ARG, "DiT block needs ctx");
-    if (!c->host[block]) return fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
+    if (p.kind == CF_DOUBLE_STREAM && (!io->x_txt || !io->y_txt)) return cf_fail(c, CF_ERR_ARG, "double-stream needs x_txt and y_txt");
+    if (p.kind == CF_DIT_CROSS && !io->ctx) return cf_fail(c, CF_ERR_ARG, "DiT block needs ctx");
+    if (!c->host[block]) return cf_fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
     CF_TRY(ensure_device(c));
     const int s = c->block_slot[block];
     const bool streamed = p.n_res_chunks < p.n_chunks;
     if (streamed && (s < 0 || c->slot_tenant[s] != block || c->slot_state[s] != SLOT_FILLED))
-        return fail(c, CF_ERR_STATE, "block %d: chunked_prefetch_begin must precede dit_block_fwd", block);
+        return cf_fail(c, CF_ERR_STATE, "block %d: chunked_prefetch_begin must precede dit_block_fwd", block);
 
     Fwd F{c, block, (hipStream_t)compute_stream, view_of(c, block), io, carve(c->d, p.kind, (char*)io->workspace)};
     c->waited_upto = p.n_res_chunks - 1;
@@ -901,19 +907,19 @@ int cf_set_contention(cf_ctx* c, void* comm_stream, void* host_pinned, uint64_t 
         worker_stop(c);
         return CF_OK;
     }
-    if (bytes_per_collective % 512) return fail(c, CF_ERR_ARG, "bytes_per_collective must be a multiple of 512");
+    if (bytes_per_collective % 512) return cf_fail(c, CF_ERR_ARG, "bytes_per_collective must be a multiple of 512");
     if (bytes_per_collective) {
-        if (!host_pinned || host_bytes < bytes_per_collective) return fail(c, CF_ERR_ARG, "pinned host buffer too small");
+        if (!host_pinned || host_bytes < bytes_per_collective) return cf_fail(c, CF_ERR_ARG, "pinned host buffer too small");
         hipPointerAttribute_t attr;
         if (hipPointerGetAttributes(&attr, host_pinned) != hipSuccess || attr.type != hipMemoryTypeHost) {
             (void)hipGetLastError();
-            return fail(c, CF_ERR_ARG, "collective host buffer must be pinned host memory");
+            return cf_fail(c, CF_ERR_ARG, "collective host buffer must be pinned host memory");
         }
         if (c->comm_dev) (void)hipFree(c->comm_dev);
         c->comm_dev = nullptr;
         if (hipMalloc((void**)&c->comm_dev, bytes_per_collective) != hipSuccess) {
             (void)hipGetLastError();
-            return fail(c, CF_ERR_NOMEM, "hipMalloc of the collective buffer failed");
+            return cf_fail(c, CF_ERR_NOMEM, "hipMalloc of the collective buffer failed");
         }
     }
     c->comm_stream = (hipStream_t)comm_stream;
@@ -938,36 +944,36 @@ int cf_comm_end(cf_ctx* c, void* comm_stream, void* compute_stream) {
 
 int cf_checksum_block(cf_ctx* c, int32_t block, uint64_t* host_out, void* stream) {
     CF_TRY(check_block(c, block));
-    if (!host_out) return fail(c, CF_ERR_ARG, "null output");
+    if (!host_out) return cf_fail(c, CF_ERR_ARG, "null output");
     CF_TRY(ensure_device(c));
     hipStream_t s = (hipStream_t)stream;
     const Plan& p = c->P(block);
     if (p.n_res_chunks < p.n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
     uint64_t* dev = nullptr;
-    if (hipMalloc((void**)&dev, 8ull * p.n_chunks) != hipSuccess) { (void)hipGetLastError(); return fail(c, CF_ERR_NOMEM, "hipMalloc failed"); }
+    if (hipMalloc((void**)&dev, 8ull * p.n_chunks) != hipSuccess) { (void)hipGetLastError(); return cf_fail(c, CF_ERR_NOMEM, "hipMalloc failed"); }
     const WView v = view_of(c, block);
     int rc = CF_OK;
     for (int k = 0; k < p.n_chunks && rc == CF_OK; ++k) {
         const uint64_t b = chunk_begin(c, k), e = chunk_end(c, p, k);
         const char* src = (b < v.split ? v.lo : v.hi) + b;
         hipError_t he = checksum_launch(src, e - b, b / 8, dev + k, s);
-        if (he != hipSuccess) rc = fail(c, CF_ERR_HIP, "checksum launch failed: %s", hipGetErrorString(he));
+        if (he != hipSuccess) rc = cf_fail(c, CF_ERR_HIP, "checksum launch failed: %s", hipGetErrorString(he));
     }
-    if (rc == CF_OK && hipMemcpyAsync(host_out, dev, 8ull * p.n_chunks, hipMemcpyDeviceToHost, s) != hipSuccess) rc = fail(c, CF_ERR_HIP, "checksum copy failed");
-    if (hipStreamSynchronize(s) != hipSuccess && rc == CF_OK) rc = fail(c, CF_ERR_HIP, "checksum sync failed");
+    if (rc == CF_OK && hipMemcpyAsync(host_out, dev, 8ull * p.n_chunks, hipMemcpyDeviceToHost, s) != hipSuccess) rc = cf_fail(c, CF_ERR_HIP, "checksum copy failed");
+    if (hipStreamSynchronize(s) != hipSuccess && rc == CF_OK) rc = cf_fail(c, CF_ERR_HIP, "checksum sync failed");
     (void)hipFree(dev);
     return rc;
 }
 
 int cf_read_block(cf_ctx* c, int32_t block, void* host_out, void* stream) {
     CF_TRY(check_block(c, block));
-    if (!host_out) return fail(c, CF_ERR_ARG, "null output");
+    if (!host_out) return cf_fail(c, CF_ERR_ARG, "null output");
     CF_TRY(ensure_device(c));
     hipStream_t s = (hipStream_t)stream;
     const Plan& p = c->P(block);
     if (p.n_res_chunks < p.n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
     if (p.res_bytes) {
-        if (!c->res_buf[block]) return fail(c, CF_ERR_STATE, "block %d not registered", block);
+        if (!c->res_buf[block]) return cf_fail(c, CF_ERR_STATE, "block %d not registered", block);
         CF_HIP(c, hipMemcpyAsync(host_out, c->res_buf[block], p.res_bytes, hipMemcpyDeviceToHost, s));
     }
     if (p.res_bytes < p.blob_bytes)
@@ -1015,7 +1021,7 @@ int cf_kernel_times(cf_ctx* c, cf_kernel_time* out, int32_t* n) {
     for (auto& k : c->ktimes)
         if (k.launches) ++cnt;
     if (out) {
-        if (*n < cnt) return fail(c, CF_ERR_ARG, "need room for %d kernel records", cnt);
+        if (*n < cnt) return cf_fail(c, CF_ERR_ARG, "need room for %d kernel records", cnt);
         int i = 0;
         for (auto& k : c->ktimes)
             if (k.launches) out[i++] = k;
@@ -1035,7 +1041,7 @@ int cf_sync(cf_ctx* c) {
     if (!c) return CF_ERR_ARG;
     worker_drain(c);
     CF_HIP(c, hipDeviceSynchronize());
-    if (!c->worker_err.empty()) return fail(c, CF_ERR_HIP, "prefetch worker: %s", c->worker_err.c_str());
+    if (!c->worker_err.empty()) return cf_fail(c, CF_ERR_HIP, "prefetch worker: %s", c->worker_err.c_str());
     return CF_OK;
 }
 
@@ -1045,28 +1051,28 @@ static WView flat_view(const void* blob) { return WView{(const char*)blob, (cons
 int cf_op_linear(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off, int32_t M, int32_t N,
                  int32_t K, int32_t n0, int32_t n1, int32_t n_split, uint16_t* out0, int32_t ld0, uint16_t* out1,
                  int32_t ld1, void* stream) {
-    if (!A || !blob) return fail(nullptr, CF_ERR_ARG, "null operand");
+    if (!A || !blob) return cf_fail(nullptr, CF_ERR_ARG, "null operand");
     GemmArgs g{};
     g.A = (const bf16*)A; g.lda = lda; g.W = flat_view(blob); g.w_off = w_off;
     g.has_bias = bias_off >= 0; g.bias_off = bias_off >= 0 ? (uint64_t)bias_off : 0;
     g.M = M; g.N = N; g.K = K; g.n0 = n0; g.n1 = n1; g.epi = EPI_SPLIT_GELU;
     g.out0 = (bf16*)out0; g.ld0 = ld0; g.n_split = n_split; g.out1 = (bf16*)out1; g.ld1 = ld1; g.col1_off = 0;
-    if (const char* msg = gemm_check(g)) return fail(nullptr, CF_ERR_ARG, "%s", msg);
+    if (const char* msg = gemm_check(g)) return cf_fail(nullptr, CF_ERR_ARG, "%s", msg);
     hipError_t e = gemm_launch(g, (hipStream_t)stream);
-    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "gemm launch: %s", hipGetErrorString(e));
+    return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "gemm launch: %s", hipGetErrorString(e));
 }
 
 int cf_op_linear_residual(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off, int32_t M,
                           int32_t N, int32_t K, const float* resid, const float* gate, float* y, void* stream) {
-    if (!A || !blob) return fail(nullptr, CF_ERR_ARG, "null operand");
+    if (!A || !blob) return cf_fail(nullptr, CF_ERR_ARG, "null operand");
     GemmArgs g{};
     g.A = (const bf16*)A; g.lda = lda; g.W = flat_view(blob); g.w_off = w_off;
     g.has_bias = bias_off >= 0; g.bias_off = bias_off >= 0 ? (uint64_t)bias_off : 0;
     g.M = M; g.N = N; g.K = K; g.n0 = 0; g.n1 = N; g.epi = EPI_GATE_RESID;
     g.resid = resid; g.gate = gate; g.y = y; g.ldy = N;
-    if (const char* msg = gemm_check(g)) return fail(nullptr, CF_ERR_ARG, "%s", msg);
+    if (const char* msg = gemm_check(g)) return cf_fail(nullptr, CF_ERR_ARG, "%s", msg);
     hipError_t e = gemm_launch(g, (hipStream_t)stream);
-    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "gemm launch: %s", hipGetErrorString(e));
+    return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "gemm launch: %s", hipGetErrorString(e));
 }
 
 int cf_op_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, uint16_t* O, int32_t H, int32_t nq,
@@ -1075,34 +1081,34 @@ int cf_op_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, ui
     a.Q = (const bf16*)Q; a.K = (const bf16*)K; a.Vt = (const bf16*)Vt; a.O = (bf16*)O;
     a.o_hs = (long)nq * hd; a.o_qs = hd; a.H = H; a.nq = nq; a.nk = nk; a.nk_pad = nk_pad; a.hd = hd;
     a.scale = 1.0f / sqrtf((float)hd);
-    if (const char* msg = attn_check(a)) return fail(nullptr, CF_ERR_ARG, "%s", msg);
+    if (const char* msg = attn_check(a)) return cf_fail(nullptr, CF_ERR_ARG, "%s", msg);
     hipError_t e = attn_launch(a, (hipStream_t)stream);
-    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "attention launch: %s", hipGetErrorString(e));
+    return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "attention launch: %s", hipGetErrorString(e));
 }
 
 int cf_op_ln_modulate(const float* x, const float* shift, const float* scale, uint16_t* xn, int32_t rows, int32_t d,
                       void* stream) {
-    if (!x || !shift || !scale || !xn) return fail(nullptr, CF_ERR_ARG, "null operand");
+    if (!x || !shift || !scale || !xn) return cf_fail(nullptr, CF_ERR_ARG, "null operand");
     hipError_t e = ln_modulate_launch(x, shift, scale, (bf16*)xn, rows, d, d, (hipStream_t)stream);
-    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_ARG, "ln_modulate: %s", hipGetErrorString(e));
+    return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_ARG, "ln_modulate: %s", hipGetErrorString(e));
 }
 
 int cf_op_modvec(const void* blob, uint64_t w_off, uint64_t b_off, const float* t, float* m, int32_t n, int32_t K,
                  void* stream) {
-    if (!blob || !t || !m || (w_off % 16) || (K % 8)) return fail(nullptr, CF_ERR_ARG, "bad modvec operands");
+    if (!blob || !t || !m || (w_off % 16) || (K % 8)) return cf_fail(nullptr, CF_ERR_ARG, "bad modvec operands");
     hipError_t e = modvec_launch(flat_view(blob), w_off, b_off, t, m, 0, n, K, (hipStream_t)stream);
-    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "modvec: %s", hipGetErrorString(e));
+    return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "modvec: %s", hipGetErrorString(e));
 }
 
 int cf_op_checksum(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* host_out, void* stream) {
-    if (!data || !host_out) return fail(nullptr, CF_ERR_ARG, "null operand");
+    if (!data || !host_out) return cf_fail(nullptr, CF_ERR_ARG, "null operand");
     uint64_t* dev = nullptr;
-    if (hipMalloc((void**)&dev, 8) != hipSuccess) { (void)hipGetLastError(); return fail(nullptr, CF_ERR_NOMEM, "hipMalloc failed"); }
+    if (hipMalloc((void**)&dev, 8) != hipSuccess) { (void)hipGetLastError(); return cf_fail(nullptr, CF_ERR_NOMEM, "hipMalloc failed"); }
     hipError_t e = checksum_launch(data, bytes, first_word, dev, (hipStream_t)stream);
     if (e == hipSuccess) e = hipMemcpyAsync(host_out, dev, 8, hipMemcpyDeviceToHost, (hipStream_t)stream);
     if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
     (void)hipFree(dev);
-    return e == hipSuccess ? CF_OK : fail(nullptr, CF_ERR_HIP, "checksum: %s", hipGetErrorString(e));
+    return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "checksum: %s", hipGetErrorString(e));
 }
 
 }  // extern "C"
@@ -1197,7 +1203,7 @@ int fwd_dit(Fwd& F) {
         AttnArgs a{};
         a.Q = w.cQ; a.K = w.cK; a.Vt = w.cVt; a.O = w.c; a.o_hs = hd; a.o_qs = d;
         a.H = H; a.nq = nl; a.nk = lc; a.nk_pad = n_pad_of(lc); a.hd = hd; a.scale = 1.0f / sqrtf((float)hd);
-        if (const char* msg = attn_check(a)) return fail(c, CF_ERR_ARG, "%s", msg);
+        if (const char* msg = attn_check(a)) return cf_fail(c, CF_ERR_ARG, "%s", msg);
         ProfScope ps(c, F.s, K_CROSS_ATTN, 4.0 * H * (double)nl * lc * hd, 0);
         CF_HIP(c, attn_launch(a, F.s));
     }
