@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="memory-latency grid (r x chunk x contention) to stderr")
     ap.add_argument("--tune-budget-frac", type=float, default=0.5,
                     help="with --sweep: weight-memory budget, as a fraction of the stack's weights, handed to the tuner")
+    ap.add_argument("--scale-sweep", action="store_true",
+                    help="vary the sequence length of the config (frames for wan, image tokens for flux) and locate "
+                         "the workload at which the prefetch becomes hidden (Eq. 3-4); prints its own JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only", choices=["both", "resident", "offload"], default="both")
     return ap.parse_args()
@@ -87,11 +90,93 @@ def block_times(run, ios, torch, reps=5):
     return np.median(ms, axis=0)
 
 
+def scale_sweep(args):
+    """Sec. 4's scaling experiments on this machine: the same blocks at growing sequence lengths.
+    Per size: FLOPs of the share (library counters), per-block time resident and fully offloaded,
+    the first-order verdict (Eq. 3: hidden iff T_comp >= T_pref) and the measured one; then F* (Eq. 4)
+    from the measured compute and link rates and the size at which the measured exposure vanishes."""
+    import numpy as np
+    import torch
+    import workload as wl
+    from paper_2605_11335_amd.runner import BlockRunner, chunk_bytes_for
+
+    base = wl.CONFIGS[args.config]
+    L = args.blocks or 3
+    if base.kind == wl.KIND_DIT:
+        # Wan-like video: S = 220 (n + 3) tokens for n frames (App. C, Table 2); n = 121 gives 27280
+        sizes = [(f"{n} frames", 220 * (n + 3)) for n in (21, 41, 61, 81, 121, 161)]
+    else:
+        sizes = [(f"{k}x image tokens", base.n_txt + (base.n_total - base.n_txt) * k) for k in (1, 2, 4, 6, 8, 12)]
+    rows = []
+    streams = None                      # every size runs on the same three streams
+    for label, n_total in sizes:
+        n_total = n_total // (2 * base.sp_degree) * (2 * base.sp_degree)
+        cfg = base.with_(n_total=n_total, n_blocks=L, n_double=0)
+        run = BlockRunner(cfg, chunk_bytes=chunk_bytes_for(cfg), streams=streams)
+        streams = (run.compute, run.copy, run.comm)
+        try:
+            for b in range(L):
+                run.register_params(b, wl.gen_block_params(cfg, b))
+            bufs = [torch.randn((cfg.n_local, cfg.d), device=run.device).to(torch.bfloat16).float() for _ in range(L + 1)]
+            tens = []
+            for b in range(L):
+                t = run.make_io(wl.gen_block_inputs(cfg.with_(n_blocks=1), b))
+                tl = cfg.n_txt_local
+                if cfg.kind == wl.KIND_DOUBLE:
+                    t["x_txt"], t["x"], t["y_txt"], t["y"] = bufs[b][:tl], bufs[b][tl:], bufs[b + 1][:tl], bufs[b + 1][tl:]
+                else:
+                    t["x"], t["y"] = bufs[b], bufs[b + 1]
+                tens.append(t)
+            ios = [run.io_struct(t) for t in tens]
+
+            def arm(r, profile=False):
+                run.ctx.set_resident_fraction(r)
+                run.ctx.cf_kernel_times_reset()
+                run.ctx.cf_set_profiling(profile)
+                run.begin(0)
+                ms = time_steps(run, ios, args.steps if not profile else 2, 1, torch)
+                run.fwd(0, ios[0])
+                run.ctx.cf_sync()
+                kt = run.ctx.cf_kernel_times() if profile else None
+                run.ctx.cf_set_profiling(False)
+                return ms, kt
+            _, kt = arm(1.0, profile=True)
+            launches_steps = (2 + 1) * L + 1                       # blocks run while profiling
+            flops_blk = sum(k["flops"] for k in kt if not k["name"].startswith("modvec")) / launches_steps
+            res_ms, _ = arm(1.0)
+            off_ms, _ = arm(0.0)
+            rows.append({"size": label, "n_total": n_total, "flops_per_block": flops_blk,
+                         "resident_ms_per_block": res_ms / L, "offload_ms_per_block": off_ms / L,
+                         "exposed_ms_per_block": (off_ms - res_ms) / L, "blob_bytes": run.blob_bytes})
+            print("[scale] " + json.dumps(rows[-1]), file=sys.stderr)
+        finally:
+            run.close()
+            del run
+            torch.cuda.empty_cache()
+    # machine rates: compute rate from the largest size, link rate from the smallest (fully exposed) one
+    blob = rows[0]["blob_bytes"]
+    link = blob / (rows[0]["offload_ms_per_block"] * 1e-3)
+    comp_rate = rows[-1]["flops_per_block"] / (rows[-1]["resident_ms_per_block"] * 1e-3)
+    f_star = comp_rate * blob / link                               # Eq. 4 with measured eta_c * P_peak and eta_p * BW
+    for r in rows:
+        r["t_pref_ms"] = blob / link * 1e3
+        r["hidden_by_eq3"] = bool(r["resident_ms_per_block"] >= r["t_pref_ms"])
+        r["exposed_fraction_of_prefetch"] = r["exposed_ms_per_block"] / r["t_pref_ms"]
+        r["hidden_measured"] = bool(r["exposed_fraction_of_prefetch"] <= 0.15)
+        r["flops_over_f_star"] = r["flops_per_block"] / f_star
+    out = {"metric": "prefetch exposure vs workload size (Eq. 3-4)", "config": {"workload": f"{base.name}: {L} blocks per size"},
+           "n_gpus": 1, "dtype": "bf16", "data": "synthetic", "link_gbs": link / 1e9, "compute_tflops_at_largest": comp_rate / 1e12,
+           "f_star_tflop": f_star / 1e12, "i_star_flop_per_byte": comp_rate / link, "sizes": rows}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.scale_sweep:
+        return scale_sweep(args)
     import numpy as np
     import torch
     import workload as wl

@@ -198,9 +198,13 @@ int cf_register_block(cf_ctx* ctx, int32_t block, const void* host_blob, uint64_
 int set_resident_fraction(cf_ctx* ctx, double r, double* actual);
 
 /* ---- Sec. 2.2 step 3 + Sec. 3.2: start the asynchronous chunk-by-chunk prefetch of `block`
- * into staging slot block%2 on copy_stream.  The copy first waits (on the GPU) for the slot's
- * previous tenant to finish computing.  CF_ERR_STATE if that tenant was prefetched but its
- * dit_block_fwd has not been issued yet. */
+ * into one of the two staging slots (they alternate per call) on copy_stream.  The copy first
+ * waits (on the GPU) for the slot's previous tenant to finish computing.  CF_ERR_STATE if that
+ * tenant was prefetched but its dit_block_fwd has not been issued yet.
+ * copy_stream and the compute stream must run concurrently: HIP multiplexes streams onto a few
+ * hardware queues (4 by default), in creation order, and two streams that land on the same queue
+ * execute one after the other -- the prefetch then hides behind nothing.  A process that creates
+ * many streams should create these two back to back, or reuse one pair. */
 int chunked_prefetch_begin(cf_ctx* ctx, int32_t block, void* copy_stream);
 
 /* ---- Sec. 2.2 step 1, at chunk granularity: make compute_stream wait (on the GPU) until chunk

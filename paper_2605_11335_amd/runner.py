@@ -44,7 +44,11 @@ def _dev_bf16(bits: np.ndarray, device) -> torch.Tensor:
 
 
 class BlockRunner:
-    def __init__(self, cfg, chunk_bytes: Optional[int] = None, device: str = "cuda:0", n_blocks: Optional[int] = None):
+    def __init__(self, cfg, chunk_bytes: Optional[int] = None, device: str = "cuda:0", n_blocks: Optional[int] = None,
+                 streams=None):
+        """streams: (compute, copy, comm) torch streams to use instead of new ones.  HIP multiplexes
+        streams onto a few hardware queues (4 by default); two streams that share a queue run one
+        after the other, so a process that builds several runners hands the same three to all."""
         self.cfg = cfg if n_blocks is None else cfg.with_(n_blocks=n_blocks)
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
@@ -54,9 +58,7 @@ class BlockRunner:
         self.total_blob_bytes = sum(self.blob_bytes_of)
         self.blob_bytes = self.blob_bytes_of[0]
         self.n_chunks = self.ctx.cf_n_chunks()
-        self.compute = torch.cuda.Stream(device=self.device)
-        self.copy = torch.cuda.Stream(device=self.device)
-        self.comm = torch.cuda.Stream(device=self.device)
+        self.compute, self.copy, self.comm = streams or tuple(torch.cuda.Stream(device=self.device) for _ in range(3))
         self.workspace = torch.empty(self.ctx.cf_workspace_bytes() + 256, dtype=torch.uint8, device=self.device)
         self.blobs: List[torch.Tensor] = []
         self.io_tensors: List[Dict[str, torch.Tensor]] = []
