@@ -62,6 +62,7 @@ typedef struct {
     int32_t n_txt_total;     /* text tokens leading the joint sequence (double-stream and mixed models), else 0 */
     int32_t l_ctx;           /* CF_DIT_CROSS: context length, else 0 */
     int32_t qk_rmsnorm;      /* per-head RMSNorm on q and k (learned weight, eps 1e-6) */
+    int32_t gelu_erf;        /* MLP activation: 0 = tanh approximation of GELU, 1 = x * Phi(x) with erf */
     uint64_t chunk_bytes;    /* C of Sec. 3.2; multiple of 256 */
 } cf_model_desc;
 
@@ -85,6 +86,10 @@ typedef struct {
     const uint16_t* peer_k;
     const uint16_t* peer_v;
     const uint16_t* peer_attn;   /* [n_local, H - H/P, hd] attention output of the other heads */
+    const float* rope_cos;       /* optional rotary position tables [n_local, hd/2] for this rank's rows */
+    const float* rope_sin;       /*   (text rows first): after the per-head norm, every head's q and k  */
+                                 /*   pairs (2i, 2i+1) are rotated by angle i of the row; both or neither; */
+                                 /*   peer_q / peer_k arrive rotated; not applied to cross-attention     */
     float* y;                    /* [n_local, d] (double-stream: image rows) residual stream out */
     float* y_txt;                /* double-stream: [n_txt_local, d] */
     uint16_t* send_q;            /* [H - H/P, n_local, hd] */
@@ -248,10 +253,10 @@ int cf_sync(cf_ctx* ctx);                                      /* hipDeviceSynch
 /* ---- single kernels, exposed so that each can be checked against the oracle in isolation.
  * All pointers are device memory; `blob` holds W (and bias) at the given byte offsets. */
 /* out[m,n] = A[m,:] . W[n,:] + bias[n]; features < n_split stored bf16 to out0[m*ld0+n], the rest
- * through GELU-tanh to out1[m*ld1 + n - n_split] (App. B linear layers). */
+ * through GELU (tanh form, or erf form if gelu_erf) to out1[m*ld1 + n - n_split] (App. B linear layers). */
 int cf_op_linear(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off,
                  int32_t M, int32_t N, int32_t K, int32_t n0, int32_t n1, int32_t n_split,
-                 uint16_t* out0, int32_t ld0, uint16_t* out1, int32_t ld1, void* stream);
+                 uint16_t* out0, int32_t ld0, uint16_t* out1, int32_t ld1, int32_t gelu_erf, void* stream);
 /* y = resid + gate * (A . W^T + bias), fp32 (gate NULL = 1). */
 int cf_op_linear_residual(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off,
                           int32_t M, int32_t N, int32_t K, const float* resid, const float* gate,

@@ -31,6 +31,7 @@ import math
 from typing import Dict, Optional, Sequence
 
 import numpy as np
+from scipy.special import erf as _erf
 
 LN_EPS = 1e-6
 RMS_EPS = 1e-6
@@ -96,8 +97,40 @@ def rmsnorm(x: np.ndarray, w: np.ndarray, eps: float = RMS_EPS) -> np.ndarray:
     return x / np.sqrt(ms + eps) * w
 
 
+def rope(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Rotary position embedding (not in the paper, which is silent on positions; the models it
+    runs rotate q and k): x [n, H, hd]; the pair (x[..., 2i], x[..., 2i+1]) of token row r is
+    rotated by the angle whose cosine and sine are cos[r, i], sin[r, i] -- the product of the
+    complex number x[2i] + j x[2i+1] with exp(j theta).  The same angles serve every head."""
+    a, b = x[..., 0::2], x[..., 1::2]
+    c, s_ = cos[:, None, :], sin[:, None, :]
+    out = np.empty_like(x)
+    out[..., 0::2] = a * c - b * s_
+    out[..., 1::2] = a * s_ + b * c
+    return out
+
+
+def _maybe_rope(q, k, inputs, row0=0):
+    """q, k [n, H, hd] of local rows row0.. -> rotated when the inputs carry tables."""
+    if "rope_cos" not in inputs:
+        return q, k
+    n = q.shape[0]
+    cos = np.asarray(inputs["rope_cos"], dtype=np.float64)[row0:row0 + n]
+    sin = np.asarray(inputs["rope_sin"], dtype=np.float64)[row0:row0 + n]
+    return rope(q, cos, sin), rope(k, cos, sin)
+
+
 def gelu_tanh(x: np.ndarray) -> np.ndarray:
     return 0.5 * x * (1.0 + np.tanh(math.sqrt(2.0 / math.pi) * (x + 0.044715 * x ** 3)))
+
+
+def gelu_erf(x: np.ndarray) -> np.ndarray:
+    """GELU proper: x * Phi(x), Phi the standard normal distribution function."""
+    return 0.5 * x * (1.0 + _erf(x / math.sqrt(2.0)))
+
+
+def _act(cfg):
+    return gelu_erf if getattr(cfg, "gelu_erf", False) else gelu_tanh
 
 
 def softmax_rows(s: np.ndarray) -> np.ndarray:
@@ -245,9 +278,10 @@ def single_stream_block(cfg, params: Dict[str, np.ndarray], inputs: Dict[str, np
     if cfg.qk_rmsnorm:
         q = rmsnorm(q, p["q_norm"])
         k = rmsnorm(k, p["k_norm"])
+    q, k = _maybe_rope(q, k, inputs)
 
     att = joint_attention_share(cfg, q, k, v, inputs, sel, send_rows, mc)
-    c = np.concatenate([att["attn"], gelu_tanh(u)], axis=1)
+    c = np.concatenate([att["attn"], _act(cfg)(u)], axis=1)
     y = xs + gate * linear(c, p["w2"], p["b2"], mc, "lin2")
     out = {"y": y}
     for key in ("send_q", "send_k", "send_v", "send_attn"):
@@ -285,6 +319,7 @@ def dit_block(cfg, params, inputs, rows=None, send_rows=None, mc=None) -> Dict[s
     if cfg.qk_rmsnorm:
         q = rmsnorm(q, p["q_norm"])
         k = rmsnorm(k, p["k_norm"])
+    q, k = _maybe_rope(q, k, inputs)          # self-attention only; the cross-attention below is not rotated
     att = joint_attention_share(cfg, q, k, v, inputs, sel, send_rows, mc)
     x1 = xs + g1 * linear(att["attn"], p["w_o"], p["b_o"], mc, "self_out")
 
@@ -300,7 +335,7 @@ def dit_block(cfg, params, inputs, rows=None, send_rows=None, mc=None) -> Dict[s
     x2 = x1 + linear(ac, p["w_co"], p["b_co"], mc, "cross_out")
 
     h2 = modulate(layernorm(x2), sh2, sc2)
-    up = gelu_tanh(linear(h2, p["w_up"], p["b_up"], mc, "ffn_up"))
+    up = _act(cfg)(linear(h2, p["w_up"], p["b_up"], mc, "ffn_up"))
     y = x2 + g2 * linear(up, p["w_down"], p["b_down"], mc, "ffn_down")
     out = {"y": y}
     for key in ("send_q", "send_k", "send_v", "send_attn"):
@@ -333,6 +368,7 @@ def double_stream_block(cfg, params, inputs, rows=None, send_rows=None, mc=None)
         if cfg.qk_rmsnorm:
             q = rmsnorm(q, p[f"{s}_q_norm"])
             k = rmsnorm(k, p[f"{s}_k_norm"])
+        q, k = _maybe_rope(q, k, inputs, 0 if s == "txt" else tl)      # table rows: text rows, then image rows
         qkv[s] = (q, k, v)
     q, k, v = (np.concatenate([qkv["txt"][i], qkv["img"][i]], axis=0) for i in range(3))
     att = joint_attention_share(cfg, q, k, v, inputs, sel, send_rows, mc)
@@ -348,7 +384,7 @@ def double_stream_block(cfg, params, inputs, rows=None, send_rows=None, mc=None)
         x0 = xs_[s][loc]
         x1 = x0 + g1 * linear(a[mask], p[f"{s}_w_o"], p[f"{s}_b_o"], mc, f"{s}_out")
         h2 = modulate(layernorm(x1), sh2, sc2)
-        up = gelu_tanh(linear(h2, p[f"{s}_w_up"], p[f"{s}_b_up"], mc, f"{s}_up"))
+        up = _act(cfg)(linear(h2, p[f"{s}_w_up"], p[f"{s}_b_up"], mc, f"{s}_up"))
         y_rows[mask] = x1 + g2 * linear(up, p[f"{s}_w_down"], p[f"{s}_b_down"], mc, f"{s}_down")
     out = {"y_rows": y_rows}
     if sel is None:

@@ -23,7 +23,7 @@ class cf_model_desc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("n_blocks", C.c_int32), ("d", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("f", C.c_int32), ("n_total", C.c_int32), ("sp_degree", C.c_int32),
                 ("sp_rank", C.c_int32), ("n_txt_total", C.c_int32), ("l_ctx", C.c_int32),
-                ("qk_rmsnorm", C.c_int32), ("chunk_bytes", C.c_uint64)]
+                ("qk_rmsnorm", C.c_int32), ("gelu_erf", C.c_int32), ("chunk_bytes", C.c_uint64)]
 
 
 class cf_tensor_slot(C.Structure):
@@ -33,6 +33,7 @@ class cf_tensor_slot(C.Structure):
 class cf_block_io(C.Structure):
     _fields_ = [("x", C.c_void_p), ("x_txt", C.c_void_p), ("temb", C.c_void_p), ("ctx", C.c_void_p),
                 ("peer_q", C.c_void_p), ("peer_k", C.c_void_p), ("peer_v", C.c_void_p), ("peer_attn", C.c_void_p),
+                ("rope_cos", C.c_void_p), ("rope_sin", C.c_void_p),
                 ("y", C.c_void_p), ("y_txt", C.c_void_p),
                 ("send_q", C.c_void_p), ("send_k", C.c_void_p), ("send_v", C.c_void_p), ("send_attn", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64)]
@@ -120,7 +121,7 @@ def lib() -> C.CDLL:
         _lib.cf_comm_end.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.cf_op_linear.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64, C.c_int64, C.c_int32, C.c_int32,
                                       C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
-                                      C.c_int32, C.c_void_p]
+                                      C.c_int32, C.c_int32, C.c_void_p]
         _lib.cf_op_linear_residual.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64, C.c_int64, C.c_int32,
                                                C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib.cf_op_attention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
@@ -153,7 +154,7 @@ def desc_from_config(cfg, chunk_bytes: int) -> cf_model_desc:
     return cf_model_desc(kind=cfg.kind, n_blocks=cfg.n_blocks, d=cfg.d, n_heads=cfg.n_heads, head_dim=cfg.head_dim,
                          f=cfg.f, n_total=cfg.n_total, sp_degree=cfg.sp_degree, sp_rank=cfg.sp_rank,
                          n_txt_total=cfg.n_txt, l_ctx=cfg.l_ctx, qk_rmsnorm=int(cfg.qk_rmsnorm),
-                         chunk_bytes=chunk_bytes)
+                         gelu_erf=int(cfg.gelu_erf), chunk_bytes=chunk_bytes)
 
 
 class Context:
@@ -335,12 +336,12 @@ def make_io(**tensors) -> cf_block_io:
 
 # ---- single kernels (device tensors are torch tensors; bf16 data as torch.bfloat16 or int16 views)
 def cf_op_linear(A, blob, w_off, bias_off, M, N, K, out0, out1=None, n_split=None, n0=0, n1=None, lda=None,
-                 ld0=None, ld1=None, stream=None):
+                 ld0=None, ld1=None, gelu_erf=False, stream=None):
     n1 = N if n1 is None else n1
     n_split = N if n_split is None else n_split
     _check(lib().cf_op_linear(_ptr(A), K if lda is None else lda, _ptr(blob), w_off, bias_off, M, N, K, n0, n1, n_split,
                               _ptr(out0), (n_split if ld0 is None else ld0), _ptr(out1),
-                              ((N - n_split) if ld1 is None else ld1), _stream_handle(stream)))
+                              ((N - n_split) if ld1 is None else ld1), int(gelu_erf), _stream_handle(stream)))
 
 
 def cf_op_linear_residual(A, blob, w_off, bias_off, M, N, K, resid, gate, y, lda=None, stream=None):

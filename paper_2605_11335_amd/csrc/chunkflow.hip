@@ -457,6 +457,7 @@ int run_linear(Fwd& F, int kid, const std::string& wname, const std::string& bna
     const TensorDesc &w = T(F, wname), &b = T(F, bname);
     CF_TRY(need(F, b));
     g.W = F.W;
+    g.act_erf = F.c->d.gelu_erf;
     g.w_off = w.off;
     g.bias_off = b.off;
     g.has_bias = 1;
@@ -563,6 +564,7 @@ RelayoutArgs relayout_for(Fwd& F, const bf16* src, int rows, int row0, const std
     r.Q = F.ws.Q; r.K = F.ws.K; r.Vt = F.ws.Vt;
     r.n_pad = n_pad_of(m.n_total);
     r.send_q = (bf16*)F.io->send_q; r.send_k = (bf16*)F.io->send_k; r.send_v = (bf16*)F.io->send_v;
+    r.rope_cos = F.io->rope_cos; r.rope_sin = F.io->rope_sin;
     return r;
 }
 
@@ -613,6 +615,7 @@ int check_desc(const cf_model_desc* m) {
             return cf_fail(nullptr, CF_ERR_ARG, "need 0 < n_txt_total < n_total, divisible by sp_degree");
     }
     if (m->kind == CF_DIT_CROSS && m->l_ctx <= 0) return cf_fail(nullptr, CF_ERR_ARG, "DiT block needs l_ctx > 0");
+    if (m->gelu_erf != 0 && m->gelu_erf != 1) return cf_fail(nullptr, CF_ERR_ARG, "gelu_erf must be 0 or 1");
     if (m->chunk_bytes == 0 || m->chunk_bytes % 256) return cf_fail(nullptr, CF_ERR_ARG, "chunk_bytes must be a positive multiple of 256");
     return CF_OK;
 }
@@ -866,6 +869,8 @@ int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute
     if (!io->workspace || io->workspace_bytes < c->ws_bytes || ((uintptr_t)io->workspace % 256))
         return cf_fail(c, CF_ERR_ARG, "workspace must be 256-byte aligned and at least %llu bytes", (unsigned long long)c->ws_bytes);
     if (((uintptr_t)io->x | (uintptr_t)io->y | (uintptr_t)io->temb) % 16) return cf_fail(c, CF_ERR_ARG, "x, y, temb must be 16-byte aligned");
+    if ((io->rope_cos == nullptr) != (io->rope_sin == nullptr)) return cf_fail(c, CF_ERR_ARG, "rope_cos and rope_sin go together");
+    if (((uintptr_t)io->rope_cos | (uintptr_t)io->rope_sin) % 16) return cf_fail(c, CF_ERR_ARG, "rope tables must be 16-byte aligned");
     const Plan& p = c->P(block);
     if (p.kind == CF_DOUBLE_STREAM && (!io->x_txt || !io->y_txt)) return cf_fail(c, CF_ERR_ARG, "double-stream needs x_txt and y_txt");
     if (p.kind == CF_DIT_CROSS && !io->ctx) return cf_fail(c, CF_ERR_ARG, "DiT block needs ctx");
@@ -1050,13 +1055,14 @@ static WView flat_view(const void* blob) { return WView{(const char*)blob, (cons
 
 int cf_op_linear(const uint16_t* A, int32_t lda, const void* blob, uint64_t w_off, int64_t bias_off, int32_t M, int32_t N,
                  int32_t K, int32_t n0, int32_t n1, int32_t n_split, uint16_t* out0, int32_t ld0, uint16_t* out1,
-                 int32_t ld1, void* stream) {
+                 int32_t ld1, int32_t gelu_erf, void* stream) {
     if (!A || !blob) return cf_fail(nullptr, CF_ERR_ARG, "null operand");
     GemmArgs g{};
     g.A = (const bf16*)A; g.lda = lda; g.W = flat_view(blob); g.w_off = w_off;
     g.has_bias = bias_off >= 0; g.bias_off = bias_off >= 0 ? (uint64_t)bias_off : 0;
     g.M = M; g.N = N; g.K = K; g.n0 = n0; g.n1 = n1; g.epi = EPI_SPLIT_GELU;
     g.out0 = (bf16*)out0; g.ld0 = ld0; g.n_split = n_split; g.out1 = (bf16*)out1; g.ld1 = ld1; g.col1_off = 0;
+    g.act_erf = gelu_erf != 0;
     if (const char* msg = gemm_check(g)) return cf_fail(nullptr, CF_ERR_ARG, "%s", msg);
     hipError_t e = gemm_launch(g, (hipStream_t)stream);
     return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "gemm launch: %s", hipGetErrorString(e));

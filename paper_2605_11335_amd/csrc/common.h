@@ -45,3 +45,6 @@ __device__ __forceinline__ float gelu_tanh_f32(float x) {
     const float en = __builtin_amdgcn_exp2f(u * -2.8853900817779268f);  // exp(-2u)
     return x * __builtin_amdgcn_rcpf(1.0f + en);
 }
+
+// x * Phi(x), the GELU the tanh form approximates
+__device__ __forceinline__ float gelu_erf_f32(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }

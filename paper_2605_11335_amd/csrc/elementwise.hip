@@ -158,20 +158,36 @@ __device__ __forceinline__ void qk_relayout_part(const RelayoutArgs& r, int bid,
         }
         if (col < 0) continue;
         uint4 u = *(const uint4*)(r.src + (size_t)row * r.ld + col + hh * r.hd + sub * 8);
-        if (r.has_norm && tns < 2) {
+        if ((r.has_norm || r.rope_cos) && tns < 2) {
             float f[8];
             unpack8(u, f);
-            float ss = 0.f;
+            if (r.has_norm) {
+                float ss = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
-            for (int o = lph >> 1; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-            const float rs = rsqrtf(ss / r.hd + 1e-6f);
-            const uint4 wu = *(const uint4*)wv_ptr(r.W, (tns == 0 ? r.qn_off : r.kn_off) + sub * 16);
-            float w[8];
-            unpack8(wu, w);
+                for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+                for (int o = lph >> 1; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+                const float rs = rsqrtf(ss / r.hd + 1e-6f);
+                const uint4 wu = *(const uint4*)wv_ptr(r.W, (tns == 0 ? r.qn_off : r.kn_off) + sub * 16);
+                float w[8];
+                unpack8(wu, w);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] = f[e] * rs * w[e];
+            }
+            if (r.rope_cos) {
+                // this lane's 8 elements are pairs sub*4 .. sub*4+3 of the head vector
+                const size_t ro = (size_t)lrow * (r.hd / 2) + sub * 4;
+                const float4 cs = *(const float4*)(r.rope_cos + ro), sn = *(const float4*)(r.rope_sin + ro);
+                const float c[4] = {cs.x, cs.y, cs.z, cs.w}, s4[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = f[2 * e], b = f[2 * e + 1];
+                    f[2 * e] = a * c[e] - b * s4[e];
+                    f[2 * e + 1] = a * s4[e] + b * c[e];
+                }
+            }
             bf16x8 o8;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o8[e] = (bf16)(f[e] * rs * w[e]);
+            for (int e = 0; e < 8; ++e) o8[e] = (bf16)f[e];
             *(bf16x8*)(dst + sub * 8) = o8;
         } else {
             *(uint4*)(dst + sub * 8) = u;

@@ -270,7 +270,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                     if (OUT_BF16) {
                         if (act) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f32(v[e]);
+                            for (int e = 0; e < 4; ++e) v[e] = g.act_erf ? gelu_erf_f32(v[e]) : gelu_tanh_f32(v[e]);
                         }
                         bf16x4 o;
 #pragma unroll

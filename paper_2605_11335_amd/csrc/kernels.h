@@ -16,9 +16,10 @@ struct GemmArgs {
     int n0, n1;         // output-feature panel covered by this launch
     int epi;
     // EPI_SPLIT_GELU: features [0, n_split) -> out0[m*ld0 + n] (bf16);
-    //                 features [n_split, N) -> gelu_tanh -> out1[m*ld1 + col1_off + n - n_split]
+    //                 features [n_split, N) -> GELU -> out1[m*ld1 + col1_off + n - n_split]
     bf16* out0; int ld0; int n_split;
     bf16* out1; int ld1; int col1_off;
+    int act_erf;        // the activation of out1: 0 = tanh form of GELU, 1 = erf form
     // EPI_GATE_RESID: y[m*ldy + n] = resid[m*ldy + n] + gate[n] * (acc + bias)   (fp32; gate NULL = 1)
     const float* resid; const float* gate; float* y; int ldy;
 };
@@ -65,6 +66,7 @@ struct RelayoutArgs {
     int h0, h_local;                  // heads kept for attention: [h0, h0 + h_local)
     int hd;
     WView W; uint64_t qn_off, kn_off; int has_norm;
+    const float *rope_cos, *rope_sin; // [n_local, hd/2] by local row, or NULL: rotate q,k pairs (2i, 2i+1) after the norm
     TokenMap map; int row0;           // src row i is local row row0 + i
     bf16 *Q, *K, *Vt;                 // [h_local, n_total, hd] x2, [h_local, hd, n_pad]
     int n_pad;

@@ -85,6 +85,9 @@ class BlockRunner:
         if "x_txt" in inputs:
             t["x_txt"] = f32(inputs["x_txt"])
             t["y_txt"] = torch.empty_like(t["x_txt"])
+        for k in ("rope_cos", "rope_sin"):
+            if k in inputs:
+                t[k] = f32(inputs[k])
         if "ctx" in inputs:
             # context is handed over in bf16 (its values are bf16-representable already: exact)
             t["ctx"] = f32(inputs["ctx"]).to(torch.bfloat16)

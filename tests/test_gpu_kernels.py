@@ -216,3 +216,29 @@ def test_linear_under_one_round_of_tiles():
     z = a.astype(np.float64) @ w.T + b
     assert_bf16_close(host_bits(out), z, extra_abs=1e-4)
     assert max_abs(y.cpu().numpy(), resid + g.astype(np.float64) * z) < 1e-3
+
+
+def test_linear_gelu_forms_are_told_apart():
+    """The epilogue's two activations (tanh form, erf form) against the oracle's: pre-activations
+    are spread over +-6 so that the region where the forms differ by several bf16 ulps (around
+    -2.5, where GELU itself is small) is populated; each output matches its own reference and
+    not the other's."""
+    M, N, K = 512, 512, 320
+    rng = np.random.default_rng(11)
+    a, ab = bf16_round(rng.normal(size=(M, K)))
+    w, wb = bf16_round(rng.normal(size=(N, K)) * 0.12)
+    buf = np.zeros(2 * N * K + 256, dtype=np.uint8)
+    buf[:2 * N * K] = wb.reshape(-1).view(np.uint8)
+    A, blob = dev_bits(ab), torch.from_numpy(buf).to(DEV)
+    z = a.astype(np.float64) @ w.astype(np.float64).T
+    outs = {}
+    for erf_form in (False, True):
+        out = torch.zeros((M, N), dtype=torch.int16, device=DEV)
+        B.cf_op_linear(A, blob, 0, -1, M, N, K, None, out, n_split=0, gelu_erf=erf_form)
+        torch.cuda.synchronize()
+        outs[erf_form] = bits_to_f64(host_bits(out))
+    refs = {False: ob.gelu_tanh(z), True: ob.gelu_erf(z)}
+    tol = lambda ref: 2.0 ** -8 * np.abs(ref) * 2 + 6e-5
+    for form in (False, True):
+        assert (np.abs(outs[form] - refs[form]) <= tol(refs[form])).all(), form
+        assert (np.abs(outs[form] - refs[not form]) > tol(refs[not form])).sum() > 100, form

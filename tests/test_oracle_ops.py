@@ -118,3 +118,40 @@ def test_linear_is_x_wT_plus_b():
 def test_widen_is_exact_bf16():
     bits = np.array([0x3F80, 0xBF80, 0x4049, 0x0000, 0x3C00], dtype=np.uint16)
     np.testing.assert_array_equal(ob.widen(bits), [1.0, -1.0, 3.140625, 0.0, 0.0078125])
+
+
+def test_rope_is_a_complex_rotation_of_consecutive_pairs():
+    """The oracle's rotary embedding against complex multiplication, hand values, and the property
+    that makes it a position embedding: with angles pos * omega_i the product q.k depends on the
+    difference of the positions only."""
+    rng = np.random.default_rng(5)
+    n, H, hd = 7, 3, 8
+    x = rng.normal(size=(n, H, hd))
+    ang = rng.uniform(0, 2 * np.pi, size=(n, hd // 2))
+    got = ob.rope(x, np.cos(ang), np.sin(ang))
+    z = (x[..., 0::2] + 1j * x[..., 1::2]) * np.exp(1j * ang)[:, None, :]
+    assert np.allclose(got[..., 0::2], z.real, atol=1e-14) and np.allclose(got[..., 1::2], z.imag, atol=1e-14)
+    # identity at angle zero; every pair keeps its length
+    assert np.array_equal(ob.rope(x, np.ones((n, hd // 2)), np.zeros((n, hd // 2))), x)
+    assert np.allclose(got[..., 0::2] ** 2 + got[..., 1::2] ** 2, x[..., 0::2] ** 2 + x[..., 1::2] ** 2)
+    # by hand: (1, 0) turned a quarter is (0, 1); (3, 4) turned a half is (-3, -4)
+    v = np.array([[[1.0, 0.0, 3.0, 4.0]]])
+    a = np.array([[np.pi / 2, np.pi]])
+    assert np.allclose(ob.rope(v, np.cos(a), np.sin(a)), [[[0.0, 1.0, -3.0, -4.0]]], atol=1e-15)
+    # relative positions
+    omega = 100.0 ** (-np.arange(hd // 2) / (hd // 2))
+    q, k = rng.normal(size=(1, 1, hd)), rng.normal(size=(1, 1, hd))
+    def score(m, nn):
+        am, an = (m * omega)[None], (nn * omega)[None]
+        return float((ob.rope(q, np.cos(am), np.sin(am)) * ob.rope(k, np.cos(an), np.sin(an))).sum())
+    assert score(5, 2) == pytest.approx(score(13, 10), rel=1e-12)
+    assert abs(score(5, 2) - score(5, 3)) > 1e-3
+
+
+def test_gelu_erf_against_library():
+    x = np.linspace(-6, 6, 2001)
+    want = F.gelu(torch.from_numpy(x)).numpy()                       # the library's exact form
+    assert np.allclose(ob.gelu_erf(x), want, atol=1e-15)
+    assert ob.gelu_erf(np.array([0.0]))[0] == 0.0
+    # the tanh form is an approximation of this one, good to about 5e-4
+    assert 1e-5 < np.abs(ob.gelu_erf(x) - ob.gelu_tanh(x)).max() < 1e-3

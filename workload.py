@@ -47,6 +47,8 @@ class BlockConfig:
     n_chunks: int = 8   # chunks per block the config asks for (chunk_bytes derived)
     temb_std: float = 1.0
     n_double: int = 0   # mixed model: the first n_double blocks are double-stream, the rest `kind`
+    rope: bool = False  # hand rotary position tables to the block (q, k rotated after the norm)
+    gelu_erf: bool = False  # MLP activation x * Phi(x) instead of its tanh approximation
 
     @property
     def n_local(self) -> int:
@@ -224,6 +226,11 @@ def gen_block_inputs(cfg: BlockConfig, block: int) -> Dict[str, np.ndarray]:
     out["temb"] = act("temb", (d,), cfg.temb_std)
     if cfg.kind == KIND_DIT:
         out["ctx"] = act("ctx", (cfg.l_ctx, d))
+    if cfg.rope:
+        # seeded angles, one per (local row, pair of head dimensions), the same for every head
+        ang = _rng(cfg.name, block, "rope").uniform(0.0, 2.0 * np.pi, size=(nl, hd // 2))
+        out["rope_cos"] = np.cos(ang).astype(np.float32)
+        out["rope_sin"] = np.sin(ang).astype(np.float32)
     if cfg.sp_degree > 1:
         out["peer_q"] = normal_bf16(cfg.name, block, "peer_q", (hl, nrem, hd), 1.0)
         out["peer_k"] = normal_bf16(cfg.name, block, "peer_k", (hl, nrem, hd), 1.0)
