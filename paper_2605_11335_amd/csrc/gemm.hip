@@ -21,6 +21,7 @@
 
 namespace {
 
+constexpr int EPI_SPLIT_GELU_ERF = 2;  // kernel variant of EPI_SPLIT_GELU with the erf form of the activation
 constexpr int BK = 64;                 // K slab (bf16 elements) = 128 bytes per LDS row
 constexpr int STAGES = 2;              // slabs resident in LDS: one being multiplied, one in flight
 constexpr int ROWB = BK * 2;           // bytes per LDS row
@@ -229,7 +230,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // register quad.  Bias / GELU / gate are applied there, then each wave transposes its quadrant
     // through its own slice of LDS so that global stores are 16 bytes per lane with 16 (or 8)
     // consecutive lanes covering one contiguous row segment.
-    constexpr bool OUT_BF16 = (EPI == EPI_SPLIT_GELU);
+    constexpr bool OUT_BF16 = (EPI != EPI_GATE_RESID);
+    constexpr bool ACT_ERF = (EPI == EPI_SPLIT_GELU_ERF);
     constexpr int PASSES = OUT_BF16 ? 1 : 2;               // fp32 rows are staged in two column halves
     constexpr int NTP = NT / PASSES;                       // 32-column tiles per pass
     constexpr int ELT = OUT_BF16 ? 2 : 4;
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                     if (OUT_BF16) {
                         if (act) {
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] = g.act_erf ? gelu_erf_f32(v[e]) : gelu_tanh_f32(v[e]);
+                            for (int e = 0; e < 4; ++e) v[e] = ACT_ERF ? gelu_erf_f32(v[e]) : gelu_tanh_f32(v[e]);
                         }
                         bf16x4 o;
 #pragma unroll
@@ -314,7 +316,7 @@ hipError_t launch(const GemmArgs& g, hipStream_t s) {
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.n1 - g.n0 + BN - 1) / BN;
     const size_t stage_bytes = (size_t)STAGES * (BM + BN) * ROWB;
-    const size_t epi_bytes = 4ull * (BM / 2) * (BN + (EPI == EPI_SPLIT_GELU ? 16 : 32));   // 4 x WM x PITCH
+    const size_t epi_bytes = 4ull * (BM / 2) * (BN + (EPI != EPI_GATE_RESID ? 16 : 32));   // 4 x WM x PITCH
     const size_t smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     static bool attr_set = false;
     if (!attr_set) {
@@ -368,6 +370,10 @@ int gemm_tile(const GemmArgs& g) {
 
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     const int t = gemm_tile(g);
+    // the erf form of the activation costs some forty VALU operations per element: it gets kernels
+    // of its own rather than a run-time choice inside the tanh one
+    if (g.epi == EPI_SPLIT_GELU && g.act_erf)
+        return t == 0 ? launch<256, 256, EPI_SPLIT_GELU_ERF>(g, s) : launch<128, 128, EPI_SPLIT_GELU_ERF>(g, s);
     if (g.epi == EPI_SPLIT_GELU) return t == 0 ? launch<256, 256, EPI_SPLIT_GELU>(g, s) : launch<128, 128, EPI_SPLIT_GELU>(g, s);
     return t == 0 ? launch<256, 256, EPI_GATE_RESID>(g, s) : launch<128, 128, EPI_GATE_RESID>(g, s);
 }
