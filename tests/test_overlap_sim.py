@@ -140,3 +140,25 @@ def test_tuner_picks_the_best_feasible_point():
             ctx.cf_tune(t_comp, link, cands, steps, memory_budget_bytes=budget, step_target_ms=target)
     finally:
         ctx.close()
+
+
+def test_simulation_argument_errors():
+    cfg = wl.CONFIGS["toy"]
+    ctx = make_context(cfg, 1 << 20)
+    try:
+        with pytest.raises(B.ChunkflowError):
+            ctx.cf_simulate(1.5, 0.1, 50.0)                      # fraction outside [0, 1]
+        with pytest.raises(B.ChunkflowError):
+            ctx.cf_simulate(0.5, 0.1, 0.0)                       # no link rate
+        with pytest.raises(B.ChunkflowError):
+            ctx.cf_simulate(0.5, 0.0, 50.0)                      # no compute time for the model's kind
+        with pytest.raises(B.ChunkflowError):
+            ctx.cf_simulate(0.5, 0.1, 50.0, chunk_overhead_us=-1.0)
+        with pytest.raises(B.ChunkflowError):
+            ctx.cf_tune(0.1, 50.0, [1000], 4, memory_budget_bytes=1 << 30)      # chunk size not a multiple of 256
+        # a model of one kind ignores the compute times of the others
+        only = ctx.cf_simulate(0.0, {0: 0.1}, 50.0)
+        more = ctx.cf_simulate(0.0, {0: 0.1, 1: 9.0, 2: 9.0}, 50.0)
+        assert only == more
+    finally:
+        ctx.close()
