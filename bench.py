@@ -134,14 +134,14 @@ def scale_sweep(args):
                 run.ctx.cf_kernel_times_reset()
                 run.ctx.cf_set_profiling(profile)
                 run.begin(0)
-                ms = time_steps(run, ios, args.steps if not profile else 2, 1, torch)
+                ms = time_steps(run, ios, args.steps if not profile else 2, max(3, args.warmup), torch)
                 run.fwd(0, ios[0])
                 run.ctx.cf_sync()
                 kt = run.ctx.cf_kernel_times() if profile else None
                 run.ctx.cf_set_profiling(False)
                 return ms, kt
             _, kt = arm(1.0, profile=True)
-            launches_steps = (2 + 1) * L + 1                       # blocks run while profiling
+            launches_steps = (2 + max(3, args.warmup)) * L + 1      # blocks run while profiling
             flops_blk = sum(k["flops"] for k in kt if not k["name"].startswith("modvec")) / launches_steps
             res_ms, _ = arm(1.0)
             off_ms, _ = arm(0.0)
@@ -337,7 +337,7 @@ def main():
             base_ms = None                # r = 1 step time of this contention mode
             pts = []
             for r in (1.0, 0.75, 0.5, 0.25, 0.0):
-                ms, act, s2 = arm(r, max(3, args.steps // 2), 1)
+                ms, act, s2 = arm(r, args.steps, max(2, args.warmup))
                 pts.append((r, ms, act, s2))
                 if r == 1.0:
                     base_ms = ms
@@ -359,7 +359,7 @@ def main():
         # the dial (Sec. 3.3): fastest resident fraction under a weight-memory budget, then measured
         budget = int(args.tune_budget_frac * blob_total)
         choice = run.ctx.cf_tune(t_comp, link / 1e9, [chunk_bytes], 16, memory_budget_bytes=budget)
-        ms, act, s2 = arm(choice["r"], max(3, args.steps // 2), 1)
+        ms, act, s2 = arm(choice["r"], args.steps, max(2, args.warmup))
         result["tune"] = {"budget_bytes": budget, "t_comp_ms_per_block": t_comp, "link_gbs": link / 1e9,
                           "chosen_r": choice["r"], "feasible": choice["feasible"],
                           "predicted_step_ms": choice["step_ms"], "measured_step_ms": ms,

@@ -172,9 +172,12 @@ int cf_blob_layout_of(const cf_ctx* ctx, int32_t block, cf_tensor_slot* out, int
 /* Host-only view of how dit_block_fwd cuts weight matrix `tensor` into panels of output features
  * when the first n_resident_chunks chunks are resident (Sec. 3.2/3.3): panel i covers rows
  * [row0[i], row1[i]) and may run once chunk wait_chunk[i] has landed (-1: no streamed chunk
- * needed).  Boundaries are multiples of `granule` rows except the last.  *n: capacity / count;
+ * needed).  m_rows = the tokens the layer is applied to: panels are whole 256-feature tiles,
+ * as many of the landed ones as fill the launch's rounds of workgroups (a poorly filled remainder
+ * stays with the next panel); m_rows = 0 plans the modulation matrix-vector product, whose
+ * panels are multiples of 8 rows.  The last panel ends with the matrix.  *n: capacity / count;
  * pass NULL arrays to query the count. */
-int cf_plan_panels(const cf_ctx* ctx, const char* tensor, int32_t granule, int32_t n_resident_chunks,
+int cf_plan_panels(const cf_ctx* ctx, const char* tensor, int32_t m_rows, int32_t n_resident_chunks,
                    int32_t* row0, int32_t* row1, int32_t* wait_chunk, int32_t* n);
 
 /* ---- overlap model at chunk granularity and the memory-latency dial (Sec. 3.1-3.3; host only).

@@ -205,11 +205,11 @@ class Context:
         _check(lib().cf_workspace_bytes(self._h, C.byref(v)), self._h)
         return v.value
 
-    def cf_plan_panels(self, tensor: str, granule: int, n_resident_chunks: int) -> List[tuple]:
+    def cf_plan_panels(self, tensor: str, m_rows: int, n_resident_chunks: int) -> List[tuple]:
         n = C.c_int32(0)
-        _check(lib().cf_plan_panels(self._h, tensor.encode(), granule, n_resident_chunks, None, None, None, C.byref(n)), self._h)
+        _check(lib().cf_plan_panels(self._h, tensor.encode(), m_rows, n_resident_chunks, None, None, None, C.byref(n)), self._h)
         r0, r1, w = (C.c_int32 * n.value)(), (C.c_int32 * n.value)(), (C.c_int32 * n.value)()
-        _check(lib().cf_plan_panels(self._h, tensor.encode(), granule, n_resident_chunks, r0, r1, w, C.byref(n)), self._h)
+        _check(lib().cf_plan_panels(self._h, tensor.encode(), m_rows, n_resident_chunks, r0, r1, w, C.byref(n)), self._h)
         return [(r0[i], r1[i], w[i]) for i in range(n.value)]
 
     # ---- overlap model

@@ -42,14 +42,6 @@ void add_tensor(Plan* c, const std::string& name, uint32_t rows, uint32_t cols) 
 
 }  // namespace
 
-// Rows of output features per panel of a linear layer on `m_rows` tokens.  A launch that covers
-// the chip less than once takes as long as one that covers it exactly once, so panels are made
-// of whole rounds: enough 256-wide feature tiles that, times the token tiles, there are 256.
-int cf_panel_granule(int m_rows) {
-    const int tiles_m = std::max(1, (m_rows + 255) / 256);
-    return 256 * ((256 + tiles_m - 1) / tiles_m);
-}
-
 void plan_layout(Plan* c, const cf_model_desc& m, int kind, uint64_t chunk_bytes) {
     const uint32_t d = m.d, f = m.f, hd = m.head_dim;
     *c = Plan{};
@@ -394,12 +386,30 @@ int need(Fwd& F, const TensorDesc& t) {
 // Panel plan of a weight matrix (pure host arithmetic): rows become usable chunk by chunk, so the
 // matrix is cut into panels [row0, row1), each tagged with the last chunk that must have landed
 // before it may run (-1: needs no streamed chunk beyond `already`).  Before blocking on a chunk
-// that is still streaming, everything whose bytes lie in earlier chunks forms a panel (rounded
-// down to `granule` rows so that launches stay tile-aligned).  `already` = highest chunk known
-// to be present (resident prefix or waited for earlier).
+// that is still streaming, rows whose bytes lie in earlier chunks form a panel.  `already` =
+// highest chunk known to be present (resident prefix or waited for earlier).
+//
+// How many of the usable rows go into the panel: every launch ends with a partly filled round of
+// workgroups, and a layer cut at arbitrary rows pays that once per panel (measured on the video
+// shares: three panels made the MLP-in layer 14 % slower than one launch).  For a linear layer
+// over m_rows tokens the panel is the largest number of whole 256-feature tiles whose launch fills
+// its rounds to 93 %; failing that the best-filled one if it reaches 75 %; failing that the rows
+// stay with the next panel.  m_rows = 0: the modulation matrix-vector product, 8 rows at a time.
 struct Panel { int row0, row1, wait; };
 
-std::vector<Panel> plan_panels(const cf_ctx* c, const TensorDesc& t, int granule, int already) {
+int panel_end(int m_rows, int row0, int avail) {
+    if (m_rows <= 0) return std::max(row0, avail / 8 * 8);
+    int best = 0;
+    double best_fill = 0;
+    for (int f = (avail - row0) / 256; f >= 1; --f) {
+        const double fill = gemm_fill(m_rows, 256 * f);
+        if (fill >= 0.93) return row0 + 256 * f;
+        if (fill > best_fill) best_fill = fill, best = f;
+    }
+    return best_fill >= 0.75 ? row0 + 256 * best : row0;
+}
+
+std::vector<Panel> plan_panels(const cf_ctx* c, const TensorDesc& t, int m_rows, int already) {
     std::vector<Panel> out;
     const uint64_t row_bytes = 2ull * t.cols;
     const int first = (int)(t.off / c->chunk_bytes), last = (int)((t.off + t.bytes() - 1) / c->chunk_bytes);
@@ -407,11 +417,11 @@ std::vector<Panel> plan_panels(const cf_ctx* c, const TensorDesc& t, int granule
     for (int k = first; k <= last; ++k) {
         if (k <= already) continue;
         const uint64_t lim = chunk_begin(c, k);
-        int avail = lim <= t.off ? 0 : (int)std::min<uint64_t>(t.rows, (lim - t.off) / row_bytes);
-        avail = avail / granule * granule;
-        if (avail > row0) {
-            out.push_back(Panel{row0, avail, pending_wait});
-            row0 = avail;
+        const int avail = lim <= t.off ? 0 : (int)std::min<uint64_t>(t.rows, (lim - t.off) / row_bytes);
+        const int end = avail > row0 ? panel_end(m_rows, row0, avail) : row0;
+        if (end > row0) {
+            out.push_back(Panel{row0, end, pending_wait});
+            row0 = end;
         }
         pending_wait = k;               // rows beyond `avail` need chunk k
     }
@@ -421,10 +431,10 @@ std::vector<Panel> plan_panels(const cf_ctx* c, const TensorDesc& t, int granule
 
 // Launch `fn(row0, row1)` over the panels of weight matrix t, each behind its chunk wait.
 template <class Fn>
-int panels(Fwd& F, const TensorDesc& t, int granule, Fn&& fn) {
+int panels(Fwd& F, const TensorDesc& t, int m_rows, Fn&& fn) {
     cf_ctx* c = F.c;
     const int n_res = c->P(F.block).n_res_chunks;
-    for (const Panel& p : plan_panels(c, t, granule, std::max(c->waited_upto, n_res - 1))) {
+    for (const Panel& p : plan_panels(c, t, m_rows, std::max(c->waited_upto, n_res - 1))) {
         if (p.wait > c->waited_upto && p.wait >= n_res) {
             CF_TRY(wait_chunk(c, F.block, p.wait, F.s));
             c->waited_upto = p.wait;
@@ -437,7 +447,7 @@ int panels(Fwd& F, const TensorDesc& t, int granule, Fn&& fn) {
 int run_modvec(Fwd& F, const std::string& wname, const std::string& bname, const float* t, float* out) {
     const TensorDesc &w = T(F, wname), &b = T(F, bname);
     CF_TRY(need(F, b));
-    return panels(F, w, 8, [&](int r0, int r1) -> int {
+    return panels(F, w, 0, [&](int r0, int r1) -> int {
         ProfScope ps(F.c, F.s, K_MODVEC, 2.0 * (r1 - r0) * w.cols, 2.0 * (r1 - r0) * w.cols);
         CF_HIP(F.c, modvec_launch(F.W, w.off, b.off, t, out, r0, r1, (int)w.cols, F.s));
         return CF_OK;
@@ -464,7 +474,7 @@ int run_linear(Fwd& F, int kid, const std::string& wname, const std::string& bna
     g.N = (int)w.rows;
     g.K = (int)w.cols;
     if (g.epi == EPI_SPLIT_GELU && g.n_split > g.N) g.n_split = g.N;
-    return panels(F, w, cf_panel_granule(g.M), [&](int r0, int r1) -> int {
+    return panels(F, w, g.M, [&](int r0, int r1) -> int {
         GemmArgs p = g;
         p.n0 = r0;
         p.n1 = r1;
@@ -746,13 +756,13 @@ int cf_blob_bytes(const cf_ctx* c, uint64_t* out) { return cf_blob_bytes_of(c, 0
 int cf_n_chunks(const cf_ctx* c, int32_t* out) { return cf_n_chunks_of(c, 0, out); }
 int cf_blob_layout(const cf_ctx* c, cf_tensor_slot* out, int32_t* n) { return cf_blob_layout_of(c, 0, out, n); }
 
-int cf_plan_panels(const cf_ctx* c, const char* tensor, int32_t granule, int32_t n_resident_chunks, int32_t* row0,
+int cf_plan_panels(const cf_ctx* c, const char* tensor, int32_t m_rows, int32_t n_resident_chunks, int32_t* row0,
                    int32_t* row1, int32_t* wait_chunk_out, int32_t* n) {
-    if (!c || !tensor || !n || granule <= 0) return CF_ERR_ARG;
+    if (!c || !tensor || !n || m_rows < 0) return CF_ERR_ARG;
     const TensorDesc* t = cf_find(c->P(0), tensor);
     if (!t) return cf_fail(c, CF_ERR_ARG, "no tensor named %s in the blob", tensor);
     if (n_resident_chunks < 0 || n_resident_chunks > c->P(0).n_chunks) return cf_fail(c, CF_ERR_ARG, "resident chunk count out of range");
-    const std::vector<Panel> plan = plan_panels(c, *t, granule, n_resident_chunks - 1);
+    const std::vector<Panel> plan = plan_panels(c, *t, m_rows, n_resident_chunks - 1);
     if (row0 && row1 && wait_chunk_out) {
         if (*n < (int)plan.size()) return cf_fail(c, CF_ERR_ARG, "need room for %d panels", (int)plan.size());
         for (size_t i = 0; i < plan.size(); ++i) { row0[i] = plan[i].row0; row1[i] = plan[i].row1; wait_chunk_out[i] = plan[i].wait; }

@@ -104,8 +104,6 @@ struct cf_ctx {
 const TensorDesc* cf_find(const Plan& p, const char* name);
 // records the message in the context (or, with none, for cf_last_error(NULL)) and returns `code`
 int cf_fail(const cf_ctx* c, int code, const char* fmt, ...);
-// rows of output features per panel of a linear layer applied to m_rows tokens
-int cf_panel_granule(int m_rows);
 // blob layout and chunk count of one block kind
 void plan_layout(Plan* p, const cf_model_desc& m, int kind, uint64_t chunk_bytes);
 

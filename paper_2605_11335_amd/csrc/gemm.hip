@@ -359,13 +359,30 @@ const char* gemm_check(const GemmArgs& g) {
 // relative efficiency of the shape (128x128 runs two workgroups per CU).  A 256-token x 128-feature
 // tile looked better than 128x128 with operands hot in the last-level cache but was the slowest of
 // the three inside a block, where every weight byte is read once, cold; it is not built.
-int gemm_tile(const GemmArgs& g) {
-    const long m256 = (g.M + 255) / 256, m128 = (g.M + 127) / 128;
-    const long n = g.n1 - g.n0, n256 = (n + 255) / 256, n128 = (n + 127) / 128;
+namespace {
+// cost of a launch over n output features in units of one round of 256x256 tiles on all CUs
+void tile_costs(int M, long n, double* c256, double* c128) {
+    const long m256 = (M + 255) / 256, m128 = (M + 127) / 128;
+    const long n256 = (n + 255) / 256, n128 = (n + 127) / 128;
     auto rounds = [](long tiles, long slots) { return (double)((tiles + slots - 1) / slots); };
-    const double c256 = rounds(m256 * n256, 256) * 1.0;
-    const double c128 = rounds(m128 * n128, 512) * 2.0 * 0.25 / 0.65;
+    *c256 = rounds(m256 * n256, 256) * 1.0;
+    *c128 = rounds(m128 * n128, 512) * 2.0 * 0.25 / 0.65;
+}
+}  // namespace
+
+int gemm_tile(const GemmArgs& g) {
+    double c256, c128;
+    tile_costs(g.M, g.n1 - g.n0, &c256, &c128);
     return c256 <= c128 ? 0 : 1;
+}
+
+// How well a launch over n output features uses the chip: work in rounds of 256x256 tiles divided
+// by the estimated cost of the tile shape gemm_tile would pick (1 = whole rounds of the big tile).
+double gemm_fill(int M, int n) {
+    double c256, c128;
+    tile_costs(M, n, &c256, &c128);
+    const double work = (double)((M + 255) / 256) * (double)((n + 255) / 256) / 256.0;
+    return work / std::min(c256, c128);
 }
 
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {

@@ -25,6 +25,7 @@ struct GemmArgs {
 };
 const char* gemm_check(const GemmArgs& g);
 int gemm_tile(const GemmArgs& g);      // tile gemm_launch will use: 0 = 256x256, 1 = 128x128
+double gemm_fill(int M, int n);        // share of the launched rounds of workgroups that n features x M tokens fill
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s);
 
 // Positions of this rank's tokens in the joint sequence: up to two contiguous segments

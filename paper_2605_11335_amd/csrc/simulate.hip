@@ -10,8 +10,8 @@
 //                   bytes of that chunk make possible -- and segment k starts when segment k-1
 //                   has ended and chunk k has landed (resident chunks never wait).
 // A segment's share of the block's compute time is the share of the block's matrix FLOPs that the
-// chunk completes: a linear layer runs in panels of whole row groups (cf_panel_granule), each as
-// soon as its last byte has landed; attention is attributed to the chunk that completes the QKV
+// chunk completes: a linear layer is taken in row groups of about one round of tiles (row_group),
+// each booked on the chunk that holds its last byte; attention is attributed to the chunk that completes the QKV
 // projection (cross-attention: the context K/V projection).  With one chunk per block and
 // nothing resident the step time is the sum over blocks of max(T_comp, T_pref).
 #include <algorithm>
@@ -33,6 +33,14 @@ double rows_of(const cf_model_desc& m, int kind, const std::string& name) {
     return nl;
 }
 
+// Rows of output features per row group of a linear layer on `m_rows` tokens: as many 256-wide
+// feature tiles as give 256 tiles (one per CU) together with the 256-row token tiles.  The
+// scheduler's panels are made of about such rounds.
+int row_group(int m_rows) {
+    const int tiles_m = std::max(1, (m_rows + 255) / 256);
+    return 256 * ((256 + tiles_m - 1) / tiles_m);
+}
+
 // per-chunk share of one block's compute (sums to 1)
 std::vector<double> segment_shares(const cf_model_desc& m, const Plan& p, uint64_t chunk_bytes) {
     std::vector<double> seg(p.n_chunks, 0.0);
@@ -42,9 +50,9 @@ std::vector<double> segment_shares(const cf_model_desc& m, const Plan& p, uint64
         if (t.rows <= 1) continue;                              // biases and norm weights: no matrix work
         const bool modvec = t.name.find("w_mod") != std::string::npos;
         const double act = modvec ? 1.0 : rows_of(m, p.kind, t.name);
-        // the scheduler launches a matrix in panels of whole row groups, each once its last byte
-        // has landed; the modulation matrix-vector product goes 8 rows at a time
-        const uint64_t G = modvec ? 8 : (uint64_t)cf_panel_granule((int)act), row_bytes = 2ull * t.cols;
+        // a row group counts once its last byte has landed; the modulation matrix-vector product
+        // goes 8 rows at a time
+        const uint64_t G = modvec ? 8 : (uint64_t)row_group((int)act), row_bytes = 2ull * t.cols;
         for (uint64_t r0 = 0; r0 < t.rows; r0 += G) {
             const uint64_t r1 = std::min<uint64_t>(t.rows, r0 + G);
             seg[(t.off + r1 * row_bytes - 1) / chunk_bytes] += 2.0 * act * (double)(r1 - r0) * t.cols;

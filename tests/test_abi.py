@@ -6,6 +6,8 @@ import re
 
 import numpy as np
 
+import itertools
+
 import pytest
 
 import workload as wl
@@ -107,7 +109,8 @@ def test_block_range_is_checked_without_a_gpu():
 def test_panel_plans_cover_every_row_once_behind_the_right_chunk(name, chunk_mib):
     """Host logic of the per-chunk consumer waits: for every weight matrix and every resident
     prefix, panels tile the rows exactly, are tile-aligned, and every byte of a panel lies in a
-    chunk that is resident or not later than the chunk the panel waits for."""
+    chunk that is resident or not later than the chunk the panel waits for; for several token
+    counts of the layer, since the panel ends depend on how the launch fills the chip."""
     cfg = wl.CONFIGS[name]
     cb = int(chunk_mib * (1 << 20)) // 256 * 256
     c = ctx_for(cfg, cb)
@@ -117,13 +120,14 @@ def test_panel_plans_cover_every_row_once_behind_the_right_chunk(name, chunk_mib
         if t["rows"] == 1:
             continue
         row_bytes = 2 * t["cols"]
-        for n_res in sorted({0, 1, n_chunks // 3, n_chunks // 2, n_chunks - 1, n_chunks}):
-            plan = c.cf_plan_panels(t["name"], 256, n_res)
+        for n_res, m_rows in itertools.product(sorted({0, 1, n_chunks // 3, n_chunks // 2, n_chunks - 1, n_chunks}),
+                                               (0, 1, cfg.n_local, 5 * cfg.n_local)):
+            plan = c.cf_plan_panels(t["name"], m_rows, n_res)
             assert plan[0][0] == 0 and plan[-1][1] == t["rows"]
             for (a0, a1, w), nxt in zip(plan, plan[1:] + [None]):
                 assert a0 < a1
                 if nxt is not None:
-                    assert a1 == nxt[0] and a1 % 256 == 0 and w < nxt[2]
+                    assert a1 == nxt[0] and a1 % (256 if m_rows else 8) == 0 and w < nxt[2]
                 last_byte = t["offset"] + a1 * row_bytes - 1
                 need = next(k for k, (s, e) in enumerate(bounds) if s <= last_byte < e)
                 assert need < n_res or need <= w, (t["name"], n_res, a0, a1, w, need)
@@ -131,6 +135,27 @@ def test_panel_plans_cover_every_row_once_behind_the_right_chunk(name, chunk_mib
                     assert w >= n_res        # never waits for a resident chunk
             if n_res == n_chunks:
                 assert plan == [(0, t["rows"], -1)]     # fully resident: one launch, no wait
+
+
+def test_panels_fill_their_rounds_of_workgroups():
+    """Every launch ends with a partly filled round of workgroups, so a layer is not cut wherever a
+    chunk ends.  Flux-like lin1 (84 feature tiles of 256) on 2304 tokens (9 token tiles): 28
+    feature tiles make 252 of the 256 workgroups of one round; although a 16 MiB chunk ends every
+    10.7 tiles, the first panel leaves at most 7 % of its rounds empty and no panel but the last
+    more than a quarter (such a remainder would have stayed with the next panel)."""
+    cfg = wl.CONFIGS["flux"]
+    c = ctx_for(cfg, 16 << 20)
+    plan = c.cf_plan_panels("w1", cfg.n_local, 0)
+    assert len(plan) >= 3
+    for i, (a0, a1, w) in enumerate(plan[:-1]):
+        tiles = (a1 - a0) // 256 * 9
+        launched = -(-tiles // 256) * 256
+        assert (a1 - a0) % 256 == 0 and launched - tiles <= (0.07 if i == 0 else 0.25) * launched, plan
+    # lin2 (12 feature tiles x 9 token tiles): no cut fills a round; one launch behind its last chunk
+    plan2 = c.cf_plan_panels("w2", cfg.n_local, 0)
+    assert len(plan2) == 1 and plan2[0][:2] == (0, cfg.d)
+    # the modulation product is cut at every chunk end
+    assert len(c.cf_plan_panels("w_mod", 0, 0)) >= 2 or c.cf_n_chunks() == 1
 
 
 def test_mixed_block_kinds_are_planned_per_block():
