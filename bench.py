@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", default="flux", choices=["toy", "flux", "wan", "hunyuan", "flux_mm", "toy_mm"])
     ap.add_argument("--blocks", type=int, default=0, help="override the number of blocks (0 = the config's)")
+    ap.add_argument("--batch", type=int, default=1, help="samples per forward (B of App. B); the headline workload is 1")
     ap.add_argument("--resident", type=float, default=0.0, help="resident fraction of the offloaded arm")
     ap.add_argument("--chunk-mib", type=float, default=0.0, help="chunk size in MiB (0 = the config's chunk count)")
     ap.add_argument("--contention", choices=["off", "on", "pause"], default="off",
@@ -90,6 +91,26 @@ def block_times(run, ios, torch, reps=5):
     return np.median(ms, axis=0)
 
 
+def chain_residual_buffers(cfg, run, tens, torch, wl):
+    """Chained residual stream: block l writes the buffer block l+1 reads.  One [B, n_local, d]
+    buffer per block boundary, a sample's rows being this rank's text rows then its image rows;
+    a double-stream block takes the two row ranges as two tensors, strided between samples."""
+    L, tl, nl, d = cfg.n_blocks, cfg.n_txt_local, cfg.n_local, cfg.d
+    lead = (cfg.batch,) if cfg.batch > 1 else ()
+    bufs = [torch.randn(lead + (nl, d), device=run.device).to(torch.bfloat16).float() for _ in range(L + 1)]
+    for b in range(L):
+        t = tens[b]
+        if cfg.kind_of(b) == wl.KIND_DOUBLE:
+            s0 = lambda buf: buf[0] if cfg.batch > 1 else buf
+            t["x_txt"], t["x"] = s0(bufs[b])[:tl], s0(bufs[b])[tl:]
+            t["y_txt"], t["y"] = s0(bufs[b + 1])[:tl], s0(bufs[b + 1])[tl:]
+            if cfg.batch > 1:
+                t["x_sample_stride"] = t["x_txt_sample_stride"] = nl * d
+        else:
+            t["x"], t["y"] = bufs[b], bufs[b + 1]
+    return bufs
+
+
 def scale_sweep(args):
     """Sec. 4's scaling experiments on this machine: the same blocks at growing sequence lengths.
     Per size: FLOPs of the share (library counters), per-block time resident and fully offloaded,
@@ -106,27 +127,23 @@ def scale_sweep(args):
         # Wan-like video: S = 220 (n + 3) tokens for n frames (App. C, Table 2); n = 121 gives 27280
         sizes = [(f"{n} frames", 220 * (n + 3)) for n in (21, 41, 61, 81, 121, 161)]
     else:
-        sizes = [(f"{k}x image tokens", base.n_txt + (base.n_total - base.n_txt) * k) for k in (1, 2, 4, 6, 8, 12)]
+        # Flux-like image model: the workload grows with the batch size B (Sec. 4.2)
+        sizes = [(f"batch {k}", k) for k in (1, 2, 4, 8, 12, 16)]
     rows = []
     streams = None                      # every size runs on the same three streams
-    for label, n_total in sizes:
-        n_total = n_total // (2 * base.sp_degree) * (2 * base.sp_degree)
-        cfg = base.with_(n_total=n_total, n_blocks=L, n_double=0)
+    for label, size in sizes:
+        if base.kind == wl.KIND_DIT:
+            n_total, batch = size // (2 * base.sp_degree) * (2 * base.sp_degree), 1
+        else:
+            n_total, batch = base.n_total, size
+        cfg = base.with_(n_total=n_total, n_blocks=L, n_double=0, batch=batch)
         run = BlockRunner(cfg, chunk_bytes=chunk_bytes_for(cfg), streams=streams)
         streams = (run.compute, run.copy, run.comm)
         try:
             for b in range(L):
                 run.register_params(b, wl.gen_block_params(cfg, b))
-            bufs = [torch.randn((cfg.n_local, cfg.d), device=run.device).to(torch.bfloat16).float() for _ in range(L + 1)]
-            tens = []
-            for b in range(L):
-                t = run.make_io(wl.gen_block_inputs(cfg.with_(n_blocks=1), b))
-                tl = cfg.n_txt_local
-                if cfg.kind == wl.KIND_DOUBLE:
-                    t["x_txt"], t["x"], t["y_txt"], t["y"] = bufs[b][:tl], bufs[b][tl:], bufs[b + 1][:tl], bufs[b + 1][tl:]
-                else:
-                    t["x"], t["y"] = bufs[b], bufs[b + 1]
-                tens.append(t)
+            tens = [run.make_io(wl.gen_block_inputs(cfg.with_(n_blocks=1), b)) for b in range(L)]
+            bufs = chain_residual_buffers(cfg, run, tens, torch, wl)
             ios = [run.io_struct(t) for t in tens]
 
             def arm(r, profile=False):
@@ -145,7 +162,7 @@ def scale_sweep(args):
             flops_blk = sum(k["flops"] for k in kt if not k["name"].startswith("modvec")) / launches_steps
             res_ms, _ = arm(1.0)
             off_ms, _ = arm(0.0)
-            rows.append({"size": label, "n_total": n_total, "flops_per_block": flops_blk,
+            rows.append({"size": label, "n_total": n_total, "batch": batch, "flops_per_block": flops_blk,
                          "resident_ms_per_block": res_ms / L, "offload_ms_per_block": off_ms / L,
                          "exposed_ms_per_block": (off_ms - res_ms) / L, "blob_bytes": run.blob_bytes})
             print("[scale] " + json.dumps(rows[-1]), file=sys.stderr)
@@ -182,7 +199,7 @@ def main():
     import workload as wl
     from paper_2605_11335_amd.runner import BlockRunner, chunk_bytes_for
 
-    cfg = wl.CONFIGS[args.config]
+    cfg = wl.CONFIGS[args.config].with_(batch=max(1, args.batch))
     if cfg.n_double and cfg.n_blocks > 12 and not args.blocks:
         args.blocks = 6          # the full MMDiT stack holds 24 GB of distinct seeded weights; keep its 1:2 mix
     if args.blocks:
@@ -196,17 +213,8 @@ def main():
     run = BlockRunner(cfg, chunk_bytes=chunk_bytes)
     for b in range(L):
         run.register_params(b, wl.gen_block_params(cfg.block_cfg(b), b))
-    # chained residual stream: block l writes the buffer block l+1 reads; the rows are this rank's
-    # text rows followed by its image rows, which a double-stream block sees as two tensors
     tens = [run.make_io(wl.gen_block_inputs(cfg.block_cfg(b), b)) for b in range(L)]
-    tl = cfg.n_txt_local
-    bufs = [torch.randn((cfg.n_local, cfg.d), device=run.device).to(torch.bfloat16).float() for _ in range(L + 1)]
-    for b in range(L):
-        if cfg.kind_of(b) == wl.KIND_DOUBLE:
-            tens[b]["x_txt"], tens[b]["x"] = bufs[b][:tl], bufs[b][tl:]
-            tens[b]["y_txt"], tens[b]["y"] = bufs[b + 1][:tl], bufs[b + 1][tl:]
-        else:
-            tens[b]["x"], tens[b]["y"] = bufs[b], bufs[b + 1]
+    bufs = chain_residual_buffers(cfg, run, tens, torch, wl)
     ios = [run.io_struct(t) for t in tens]
     blob_total = run.total_blob_bytes                      # weight bytes of the whole stack
     print(f"[bench] {cfg.name}: {L} blocks, blobs {blob_total/1e6:.1f} MB in all, chunks of "
@@ -219,7 +227,7 @@ def main():
         if mode == "off":
             run.ctx.cf_set_contention(None, None, 0, False)
             return
-        nbytes = cfg.n_local * cfg.d * 2          # one [n_local, d] bf16 tensor per all-to-all
+        nbytes = cfg.batch * cfg.n_local * cfg.d * 2          # one [B, n_local, d] bf16 tensor per all-to-all
         nbytes = nbytes // 512 * 512
         if comm_host is None:
             comm_host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
@@ -296,7 +304,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {L} blocks" + (f" ({cfg.n_double} double-stream + {L - cfg.n_double} single-stream)" if cfg.n_double else "") + f", d={cfg.d}, H={cfg.n_heads}x{cfg.head_dim}, f={cfg.f}, "
                                f"N={cfg.n_total}, Ulysses P={cfg.sp_degree} share (GEMMs on {cfg.n_local} tokens, "
-                               f"attention {cfg.h_local} heads over {cfg.n_total})",
+                               f"attention {cfg.h_local} heads over {cfg.n_total})" + (f", batch {cfg.batch}" if cfg.batch > 1 else ""),
                    "arm": "chunked offload" if do_off else "resident",
                    "chunk_bytes": chunk_bytes, "chunks_per_block": run.n_chunks, "blob_bytes": run.blob_bytes,
                    "blob_bytes_all_blocks": blob_total,
@@ -380,11 +388,11 @@ def main():
         scale = 1.0 if rows is None else cfg.n_local / 256.0
         total = 0.0
         for b in sorted({cfg.kinds.index(k) for k in set(cfg.kinds)}):      # first block of each kind
-            cb = cfg.block_cfg(b)
+            cb = cfg.block_cfg(b).with_(batch=1)          # one sample; a batch is that many independent samples
             params, inputs = wl.gen_block_params(cb, b), wl.gen_block_inputs(cb, b)
             t0 = time.perf_counter()
             ob.block_forward(cb, params, inputs, rows=rows, send_rows=(None if rows is None else np.arange(0)))
-            total += (time.perf_counter() - t0) * cfg.kinds.count(cb.kind)
+            total += (time.perf_counter() - t0) * cfg.kinds.count(cb.kind) * cfg.batch
         threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
         result["cpu_baseline"] = {"value": total * 1e3 * scale, "unit": "ms", "cores": threads, "kind": "oracle",
                                   "sample": f"{sample}, float64 NumPy, times the number of blocks of that kind per step"

@@ -63,6 +63,9 @@ typedef struct {
     int32_t l_ctx;           /* CF_DIT_CROSS: context length, else 0 */
     int32_t qk_rmsnorm;      /* per-head RMSNorm on q and k (learned weight, eps 1e-6) */
     int32_t gelu_erf;        /* MLP activation: 0 = tanh approximation of GELU, 1 = x * Phi(x) with erf */
+    int32_t batch;           /* B of App. B: independent samples per forward, each with its own timestep  */
+                             /*   embedding; 0 or 1 = one sample.  Linear layers run on B * n_local rows,  */
+                             /*   attention per sample; the weights are fetched once for the whole batch   */
     uint64_t chunk_bytes;    /* C of Sec. 3.2; multiple of 256 */
 } cf_model_desc;
 
@@ -76,7 +79,10 @@ typedef struct {
 
 /* Device buffers of one block invocation.  Peer buffers stand in for what the two Ulysses
  * exchanges around attention deliver; send buffers receive what this rank would have sent.
- * With sp_degree == 1 all peer/send pointers are ignored.  Send pointers may be NULL. */
+ * With sp_degree == 1 all peer/send pointers are ignored.  Send pointers may be NULL.
+ * With batch = B > 1 every tensor below except the rotary tables gains a leading dimension B
+ * (sample after sample, dense: x is [B, n_local, d], temb [B, d], peer_q [B, H/P, N - n_local, hd],
+ * ...); the residual streams alone may be strided between samples (x_sample_stride). */
 typedef struct {
     const float* x;              /* [n_local, d] (double-stream: the image rows) residual stream in */
     const float* x_txt;          /* double-stream: [n_txt_local, d] */
@@ -98,6 +104,10 @@ typedef struct {
     uint16_t* send_attn;         /* [H/P, N - n_local, hd] */
     void* workspace;             /* >= cf_workspace_bytes, 256-byte aligned */
     uint64_t workspace_bytes;
+    int64_t x_sample_stride;     /* batch > 1: elements from one sample's x (and y) to the next; 0 = dense.      */
+    int64_t x_txt_sample_stride; /*   same for x_txt / y_txt.  With both set to n_local * d, x_txt = buf and     */
+                                 /*   x = buf + n_txt_local * d view one [B, n_local, d] buffer of text-then-    */
+                                 /*   image rows, the layout single-stream blocks of a mixed model take as x     */
 } cf_block_io;
 
 typedef struct {

@@ -163,16 +163,17 @@ def segment_shares(cfg, layout, blob_bytes, chunk_bytes):
     that completes the context K/V projection."""
     n_chunks = -(-blob_bytes // chunk_bytes)
     seg = [0.0] * n_chunks
-    nl = cfg.n_total / cfg.sp_degree
-    tl = cfg.n_txt / cfg.sp_degree
+    batch = getattr(cfg, "batch", 1)        # App. B: every term is linear in the batch size B
+    nl = batch * cfg.n_total / cfg.sp_degree
+    tl = batch * cfg.n_txt / cfg.sp_degree
     for name, off, rows, cols in layout:
         if rows == 1:
             continue
         if name.endswith("w_mod"):
-            act, group = 1.0, 8
+            act, group = float(batch), 8
         else:
             if cfg.kind == 1:
-                act = cfg.l_ctx if name == "w_ckv" else nl
+                act = batch * cfg.l_ctx if name == "w_ckv" else nl
             elif cfg.kind == 2:
                 act = tl if name.startswith("txt_") else nl - tl
             else:
@@ -184,9 +185,9 @@ def segment_shares(cfg, layout, blob_bytes, chunk_bytes):
             seg[(off + r1 * 2 * cols - 1) // chunk_bytes] += 2.0 * act * (r1 - r0) * cols
         end = off + 2 * rows * cols
         if name in ("w1", "w_qkv", "img_w_qkv"):
-            seg[(end - 1) // chunk_bytes] += 4.0 * (cfg.n_heads / cfg.sp_degree) * cfg.n_total * cfg.n_total * cfg.head_dim
+            seg[(end - 1) // chunk_bytes] += 4.0 * batch * (cfg.n_heads / cfg.sp_degree) * cfg.n_total * cfg.n_total * cfg.head_dim
         if name == "w_ckv":
-            seg[(end - 1) // chunk_bytes] += 4.0 * cfg.n_heads * nl * cfg.l_ctx * cfg.head_dim
+            seg[(end - 1) // chunk_bytes] += 4.0 * cfg.n_heads * nl * cfg.l_ctx * cfg.head_dim      # nl holds the batch
     total = sum(seg)
     return [v / total for v in seg]
 

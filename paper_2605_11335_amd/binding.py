@@ -23,7 +23,7 @@ class cf_model_desc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("n_blocks", C.c_int32), ("d", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("f", C.c_int32), ("n_total", C.c_int32), ("sp_degree", C.c_int32),
                 ("sp_rank", C.c_int32), ("n_txt_total", C.c_int32), ("l_ctx", C.c_int32),
-                ("qk_rmsnorm", C.c_int32), ("gelu_erf", C.c_int32), ("chunk_bytes", C.c_uint64)]
+                ("qk_rmsnorm", C.c_int32), ("gelu_erf", C.c_int32), ("batch", C.c_int32), ("chunk_bytes", C.c_uint64)]
 
 
 class cf_tensor_slot(C.Structure):
@@ -36,7 +36,8 @@ class cf_block_io(C.Structure):
                 ("rope_cos", C.c_void_p), ("rope_sin", C.c_void_p),
                 ("y", C.c_void_p), ("y_txt", C.c_void_p),
                 ("send_q", C.c_void_p), ("send_k", C.c_void_p), ("send_v", C.c_void_p), ("send_attn", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_uint64),
+                ("x_sample_stride", C.c_int64), ("x_txt_sample_stride", C.c_int64)]
 
 
 class cf_stats_t(C.Structure):
@@ -154,7 +155,7 @@ def desc_from_config(cfg, chunk_bytes: int) -> cf_model_desc:
     return cf_model_desc(kind=cfg.kind, n_blocks=cfg.n_blocks, d=cfg.d, n_heads=cfg.n_heads, head_dim=cfg.head_dim,
                          f=cfg.f, n_total=cfg.n_total, sp_degree=cfg.sp_degree, sp_rank=cfg.sp_rank,
                          n_txt_total=cfg.n_txt, l_ctx=cfg.l_ctx, qk_rmsnorm=int(cfg.qk_rmsnorm),
-                         gelu_erf=int(cfg.gelu_erf), chunk_bytes=chunk_bytes)
+                         gelu_erf=int(cfg.gelu_erf), batch=int(getattr(cfg, "batch", 1)), chunk_bytes=chunk_bytes)
 
 
 class Context:
@@ -323,10 +324,14 @@ class Context:
 
 
 def make_io(**tensors) -> cf_block_io:
-    """cf_block_io from torch device tensors (by field name); `workspace` is a uint8 tensor."""
+    """cf_block_io from torch device tensors (by field name); `workspace` is a uint8 tensor;
+    x_sample_stride / x_txt_sample_stride are plain integers."""
     io = cf_block_io()
     for k, t in tensors.items():
         if t is None:
+            continue
+        if k.endswith("_sample_stride"):
+            setattr(io, k, int(t))
             continue
         setattr(io, k, t.data_ptr())
         if k == "workspace":

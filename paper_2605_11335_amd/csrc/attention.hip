@@ -230,7 +230,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
     const float inv = 1.0f / l_tot;
     const int q = q0 + lj;
     if (q < a.nq) {
-        bf16* op = a.O + (size_t)h * a.o_hs + (size_t)q * a.o_qs;
+        const int hps = a.hps ? a.hps : a.H;            // heads per sample of a batch
+        bf16* op = a.O + (size_t)(h / hps) * a.o_bs + (size_t)(h % hps) * a.o_hs + (size_t)q * a.o_qs;
 #pragma unroll
         for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -277,7 +278,8 @@ const char* attn_check(const AttnArgs& a) {
     if (a.nk_pad % 64 || a.nk_pad < a.nk) return "attention: nk_pad must be a multiple of 64 covering nk";
     if (!a.Q || !a.K || !a.Vt || !a.O) return "attention: null operand";
     if (((uintptr_t)a.Q | (uintptr_t)a.K | (uintptr_t)a.Vt) % 16) return "attention: operands must be 16-byte aligned";
-    if (((uintptr_t)a.O % 8) || (a.o_hs % 4) || (a.o_qs % 4)) return "attention: output must be 8-byte aligned";
+    if (((uintptr_t)a.O % 8) || (a.o_hs % 4) || (a.o_qs % 4) || (a.o_bs % 4)) return "attention: output must be 8-byte aligned";
+    if (a.hps < 0 || (a.hps && a.H % a.hps)) return "attention: H must be whole samples of hps heads";
     if ((long)((a.nq + 127) / 128) * a.H > 0x7fffffffL) return "attention: grid too large";
     return nullptr;
 }

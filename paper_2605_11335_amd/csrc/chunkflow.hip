@@ -115,31 +115,38 @@ struct Ws {
 
 inline int n_pad_of(int n) { return (n + 63) / 64 * 64; }
 
+inline int batch_of(const cf_model_desc& m) { return m.batch > 0 ? m.batch : 1; }
+
+// every per-token buffer holds the whole batch, sample after sample
 Ws carve(const cf_model_desc& m, int kind, char* base) {
     Ws w;
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { char* p = base + off; off = align_up(off + bytes, 256); return p; };
-    const uint64_t nl = m.n_total / m.sp_degree, d = m.d, f = m.f, N = m.n_total, hd = m.head_dim;
-    const uint64_t hl = m.n_heads / m.sp_degree;
+    const uint64_t B = batch_of(m);
+    const uint64_t nl = B * (m.n_total / m.sp_degree), d = m.d, f = m.f, N = m.n_total, hd = m.head_dim;
+    const uint64_t hl = B * (m.n_heads / m.sp_degree), lc = B * (uint64_t)m.l_ctx;
     const int nmod = kind == CF_SINGLE_STREAM ? 3 : (kind == CF_DIT_CROSS ? 6 : 12);
-    w.mod = (float*)take(4ull * nmod * d);
+    w.mod = (float*)take(4ull * B * nmod * d);
     w.xn = (bf16*)take(2 * nl * d);
     w.qkv = (bf16*)take(2 * nl * 3 * d);
     w.c = (bf16*)take(2 * nl * (kind == CF_SINGLE_STREAM ? d + f : d));
     w.Q = (bf16*)take(2 * hl * N * hd);
     w.K = (bf16*)take(2 * hl * N * hd);
     w.Vt = (bf16*)take(2 * hl * hd * n_pad_of(N));
-    if (m.sp_degree > 1) w.O = (bf16*)take(2 * hl * N * hd);
+    // attention output on the full sequence, when it cannot be written straight into the rows of the
+    // output projection's operand: other ranks' rows are among it, or the two streams' rows of a
+    // batched double-stream block lie in separate regions
+    if (m.sp_degree > 1 || (kind == CF_DOUBLE_STREAM && B > 1)) w.O = (bf16*)take(2 * hl * N * hd);
     if (kind != CF_SINGLE_STREAM) {
         w.x1 = (float*)take(4 * nl * d);
         w.up = (bf16*)take(2 * nl * f);
     }
     if (kind == CF_DIT_CROSS) {
         w.x2 = (float*)take(4 * nl * d);
-        w.ckv = (bf16*)take(2ull * m.l_ctx * 2 * d);
+        w.ckv = (bf16*)take(2ull * lc * 2 * d);
         w.cQ = (bf16*)take(2 * nl * d);
-        w.cK = (bf16*)take(2ull * m.l_ctx * d);
-        w.cVt = (bf16*)take(2ull * d * n_pad_of(m.l_ctx));
+        w.cK = (bf16*)take(2ull * lc * d);
+        w.cVt = (bf16*)take(2ull * B * d * n_pad_of(m.l_ctx));
     }
     w.total = off;
     return w;
@@ -444,20 +451,25 @@ int panels(Fwd& F, const TensorDesc& t, int m_rows, Fn&& fn) {
     return CF_OK;
 }
 
-int run_modvec(Fwd& F, const std::string& wname, const std::string& bname, const float* t, float* out) {
+// modulation vectors of every sample: t is [batch, d], out + b*out_bs receives sample b's
+int run_modvec(Fwd& F, const std::string& wname, const std::string& bname, const float* t, float* out, long out_bs) {
     const TensorDesc &w = T(F, wname), &b = T(F, bname);
     CF_TRY(need(F, b));
+    const int B = batch_of(F.c->d);
     return panels(F, w, 0, [&](int r0, int r1) -> int {
-        ProfScope ps(F.c, F.s, K_MODVEC, 2.0 * (r1 - r0) * w.cols, 2.0 * (r1 - r0) * w.cols);
-        CF_HIP(F.c, modvec_launch(F.W, w.off, b.off, t, out, r0, r1, (int)w.cols, F.s));
+        ProfScope ps(F.c, F.s, K_MODVEC, 2.0 * B * (r1 - r0) * w.cols, 2.0 * (r1 - r0) * w.cols);
+        CF_HIP(F.c, modvec_launch(F.W, w.off, b.off, t, out, r0, r1, (int)w.cols, B, out_bs, F.s));
         return CF_OK;
     });
 }
 
-int run_ln_mod(Fwd& F, const float* x, const float* shift, const float* scale, bf16* out, int rows) {
+// `rows` rows of the whole batch, rows_per_sample of them per sample (0: one sample); sample b is read at
+// x + b*x_bs and modulated with shift + b*mod_bs, scale + b*mod_bs
+int run_ln_mod(Fwd& F, const float* x, const float* shift, const float* scale, bf16* out, int rows, int rows_per_sample,
+               long x_bs, long mod_bs) {
     if (rows <= 0) return CF_OK;
     ProfScope ps(F.c, F.s, K_LN, 0, 6.0 * rows * F.c->d.d);
-    CF_HIP(F.c, ln_modulate_launch(x, shift, scale, out, rows, F.c->d.d, F.c->d.d, F.s));
+    CF_HIP(F.c, ln_modulate_launch(x, shift, scale, out, rows, F.c->d.d, F.c->d.d, rows_per_sample, x_bs, mod_bs, F.s));
     return CF_OK;
 }
 
@@ -518,41 +530,69 @@ int emulate_collectives(Fwd& F, int n) {
     return cf_comm_end_impl(c, c->comm_stream, F.s);
 }
 
+// Where the attention rows of the local tokens go (operand of the output projection): sample b's rows
+// of the map's first segment at dst + b*bs0, of the second at dst1 + b*bs1 (dst1 NULL: they follow the
+// first segment, bs0 then spans the whole sample); leading dimension ld.
+struct AttnOut {
+    bf16* dst; bf16* dst1; int ld; long bs0, bs1;
+};
+
 // q/k/v of the local rows (already in ws.qkv) -> attention over the joint sequence -> rows of all
-// heads for the local tokens in `dst` (leading dimension ld)
-int run_joint_attention(Fwd& F, const RelayoutArgs* parts, int n_parts, bf16* dst, int ld) {
+// heads for the local tokens.  `parts` describe sample 0; sample b's rows follow densely
+// (b * rows * ld further), its operands and peer/send buffers one sample further each.
+int run_joint_attention(Fwd& F, const RelayoutArgs* parts, int n_parts, const AttnOut& out) {
     cf_ctx* c = F.c;
     const cf_model_desc& m = c->d;
-    const int P = m.sp_degree, hl = m.n_heads / P, h0 = m.sp_rank * hl, hd = m.head_dim;
+    const int P = m.sp_degree, hl = m.n_heads / P, h0 = m.sp_rank * hl, hd = m.head_dim, B = batch_of(m);
     const TokenMap map = token_map(m);
     const int npad = n_pad_of(m.n_total);
+    const size_t n_rem = (size_t)(map.n_total - map.n_local);
     const cf_block_io* io = F.io;
     if (P > 1 && (!io->peer_q || !io->peer_k || !io->peer_v || !io->peer_attn))
         return cf_fail(c, CF_ERR_ARG, "sp_degree > 1 needs peer_q, peer_k, peer_v and peer_attn");
-    {
+    const size_t op_bs = (size_t)hl * m.n_total * hd, vt_bs = (size_t)hl * hd * npad;        // Q,K / Vt per sample
+    const size_t peer_bs = (size_t)hl * n_rem * hd, send_bs = (size_t)(m.n_heads - hl) * map.n_local * hd;
+    for (int b = 0; b < B; ++b) {
+        RelayoutArgs pb[2];
         double bytes = 0;
-        for (int i = 0; i < n_parts; ++i) bytes += 2.0 * 2 * parts[i].rows * 3.0 * m.d;
-        if (P > 1) bytes += 2.0 * 2 * 3 * hl * (double)(map.n_total - map.n_local) * hd;
+        for (int i = 0; i < n_parts; ++i) {
+            RelayoutArgs& r = pb[i];
+            r = parts[i];
+            r.src += (size_t)b * r.rows * r.ld;
+            r.Q += b * op_bs; r.K += b * op_bs; r.Vt += b * vt_bs;
+            if (r.send_q) r.send_q += b * send_bs;
+            if (r.send_k) r.send_k += b * send_bs;
+            if (r.send_v) r.send_v += b * send_bs;
+            bytes += 2.0 * 2 * r.rows * 3.0 * m.d;
+        }
+        if (P > 1) bytes += 2.0 * 2 * 3 * hl * (double)n_rem * hd;
         ProfScope ps(c, F.s, K_RELAYOUT, 0, bytes);
-        CF_HIP(c, pre_attention_launch(parts, n_parts, P > 1 ? (const bf16*)io->peer_q : nullptr,
-                                       P > 1 ? (const bf16*)io->peer_k : nullptr, P > 1 ? (const bf16*)io->peer_v : nullptr, F.s));
+        CF_HIP(c, pre_attention_launch(pb, n_parts, P > 1 ? (const bf16*)io->peer_q + b * peer_bs : nullptr,
+                                       P > 1 ? (const bf16*)io->peer_k + b * peer_bs : nullptr,
+                                       P > 1 ? (const bf16*)io->peer_v + b * peer_bs : nullptr, F.s));
     }
     CF_TRY(emulate_collectives(F, 3));
-    AttnArgs a;
+    const bool direct = P == 1 && !out.dst1;        // attention writes the projection operand itself
+    AttnArgs a{};
     a.Q = F.ws.Q; a.K = F.ws.K; a.Vt = F.ws.Vt;
-    a.H = hl; a.nq = m.n_total; a.nk = m.n_total; a.nk_pad = npad; a.hd = hd;
+    a.H = B * hl; a.hps = hl; a.nq = m.n_total; a.nk = m.n_total; a.nk_pad = npad; a.hd = hd;
     a.scale = 1.0f / sqrtf((float)hd);
-    if (P == 1) { a.O = dst; a.o_hs = hd; a.o_qs = ld; }
-    else { a.O = F.ws.O; a.o_hs = (long)m.n_total * hd; a.o_qs = hd; }
+    if (direct) { a.O = out.dst; a.o_hs = hd; a.o_qs = out.ld; a.o_bs = out.bs0; }
+    else { a.O = F.ws.O; a.o_hs = (long)m.n_total * hd; a.o_qs = hd; a.o_bs = (long)op_bs; }
     if (const char* msg = attn_check(a)) return cf_fail(c, CF_ERR_ARG, "%s", msg);
     {
-        ProfScope ps(c, F.s, K_ATTN, 4.0 * hl * (double)m.n_total * m.n_total * hd, 0);
+        ProfScope ps(c, F.s, K_ATTN, 4.0 * B * hl * (double)m.n_total * m.n_total * hd, 0);
         CF_HIP(c, attn_launch(a, F.s));
     }
-    if (P > 1) {
-        ProfScope ps(c, F.s, K_GATHER, 0, 2.0 * 2 * ((double)hl * m.n_total + (double)map.n_local * (m.n_heads - hl)) * hd);
-        CF_HIP(c, attn_gather_launch(F.ws.O, (const bf16*)io->peer_attn, dst, ld, (bf16*)io->send_attn, m.n_heads, h0,
-                                     hl, hd, map, F.s));
+    if (!direct) {
+        const size_t pa_bs = (size_t)map.n_local * (m.n_heads - hl) * hd;
+        for (int b = 0; b < B; ++b) {
+            ProfScope ps(c, F.s, K_GATHER, 0, 2.0 * 2 * ((double)hl * m.n_total + (double)map.n_local * (m.n_heads - hl)) * hd);
+            CF_HIP(c, attn_gather_launch(F.ws.O + b * op_bs, P > 1 ? (const bf16*)io->peer_attn + b * pa_bs : nullptr,
+                                         out.dst + b * out.bs0, out.dst1 ? out.dst1 + b * out.bs1 : nullptr, out.ld,
+                                         io->send_attn ? (bf16*)io->send_attn + b * peer_bs : nullptr, m.n_heads, h0, hl, hd,
+                                         map, F.s));
+        }
     }
     return emulate_collectives(F, 1);
 }
@@ -578,27 +618,38 @@ RelayoutArgs relayout_for(Fwd& F, const bf16* src, int rows, int row0, const std
     return r;
 }
 
+// sample strides of the caller's residual streams (elements); 0 in the io struct = dense
+long x_stride(const cf_block_io* io, long dense) { return io->x_sample_stride ? (long)io->x_sample_stride : dense; }
+long x_txt_stride(const cf_block_io* io, long dense) { return io->x_txt_sample_stride ? (long)io->x_txt_sample_stride : dense; }
+
+// batch bookkeeping of a residual epilogue: rows per sample and the sample strides of gate, resid, y
+GemmArgs batched(GemmArgs g, int batch, int rows_per_sample, long gate_bs, long resid_bs, long y_bs) {
+    if (batch > 1) { g.rows_per_sample = rows_per_sample; g.gate_bs = gate_bs; g.resid_bs = resid_bs; g.y_bs = y_bs; }
+    return g;
+}
+
 // ---- MM-DiT single-stream block (App. B)
 int fwd_single(Fwd& F) {
     cf_ctx* c = F.c;
     const cf_model_desc& m = c->d;
-    const int d = m.d, f = m.f, nl = m.n_total / m.sp_degree;
+    const int d = m.d, f = m.f, nl = m.n_total / m.sp_degree, B = batch_of(m), rows = B * nl, rps = B > 1 ? nl : 0;
     const cf_block_io* io = F.io;
-    CF_TRY(run_modvec(F, "w_mod", "b_mod", io->temb, F.ws.mod));
+    const long mod_bs = 3L * d, xs = x_stride(io, (long)nl * d);
+    CF_TRY(run_modvec(F, "w_mod", "b_mod", io->temb, F.ws.mod, mod_bs));
     const float *shift = F.ws.mod, *scale = F.ws.mod + d, *gate = F.ws.mod + 2 * d;
-    CF_TRY(run_ln_mod(F, io->x, shift, scale, F.ws.xn, nl));
+    CF_TRY(run_ln_mod(F, io->x, shift, scale, F.ws.xn, rows, rps, xs, mod_bs));
     if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, "q_norm"))); CF_TRY(need(F, T(F, "k_norm"))); }
     GemmArgs g{};
-    g.A = F.ws.xn; g.lda = d; g.M = nl; g.epi = EPI_SPLIT_GELU;
+    g.A = F.ws.xn; g.lda = d; g.M = rows; g.epi = EPI_SPLIT_GELU;
     g.out0 = F.ws.qkv; g.ld0 = 3 * d; g.n_split = 3 * d;
     g.out1 = F.ws.c; g.ld1 = d + f; g.col1_off = d;
     CF_TRY(run_linear(F, K_LIN1, "w1", "b1", g));
     RelayoutArgs r = relayout_for(F, F.ws.qkv, nl, 0, "q_norm", "k_norm");
-    CF_TRY(run_joint_attention(F, &r, 1, F.ws.c, d + f));
+    CF_TRY(run_joint_attention(F, &r, 1, AttnOut{F.ws.c, nullptr, d + f, (long)nl * (d + f), 0}));
     GemmArgs h{};
-    h.A = F.ws.c; h.lda = d + f; h.M = nl; h.epi = EPI_GATE_RESID;
+    h.A = F.ws.c; h.lda = d + f; h.M = rows; h.epi = EPI_GATE_RESID;
     h.resid = io->x; h.gate = gate; h.y = io->y; h.ldy = d;
-    return run_linear(F, K_LIN2, "w2", "b2", h);
+    return run_linear(F, K_LIN2, "w2", "b2", batched(h, B, nl, mod_bs, xs, xs));
 }
 
 int fwd_dit(Fwd& F);
@@ -626,6 +677,8 @@ int check_desc(const cf_model_desc* m) {
     }
     if (m->kind == CF_DIT_CROSS && m->l_ctx <= 0) return cf_fail(nullptr, CF_ERR_ARG, "DiT block needs l_ctx > 0");
     if (m->gelu_erf != 0 && m->gelu_erf != 1) return cf_fail(nullptr, CF_ERR_ARG, "gelu_erf must be 0 or 1");
+    if (m->batch < 0 || m->batch > 1024) return cf_fail(nullptr, CF_ERR_ARG, "batch must be in [0, 1024] (0 = 1)");
+    if ((int64_t)std::max(1, m->batch) * (m->n_total / m->sp_degree) > (1 << 30)) return cf_fail(nullptr, CF_ERR_ARG, "batch * n_local too large");
     if (m->chunk_bytes == 0 || m->chunk_bytes % 256) return cf_fail(nullptr, CF_ERR_ARG, "chunk_bytes must be a positive multiple of 256");
     return CF_OK;
 }
@@ -884,6 +937,15 @@ int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute
     const Plan& p = c->P(block);
     if (p.kind == CF_DOUBLE_STREAM && (!io->x_txt || !io->y_txt)) return cf_fail(c, CF_ERR_ARG, "double-stream needs x_txt and y_txt");
     if (p.kind == CF_DIT_CROSS && !io->ctx) return cf_fail(c, CF_ERR_ARG, "DiT block needs ctx");
+    {
+        // sample strides of the residual streams: 0 = dense, else at least one sample, 16-byte granular
+        const int64_t nl = c->d.n_total / c->d.sp_degree, tl = c->d.n_txt_total / c->d.sp_degree;
+        const int64_t x_rows = p.kind == CF_DOUBLE_STREAM ? nl - tl : nl;
+        if (io->x_sample_stride && (io->x_sample_stride < x_rows * c->d.d || io->x_sample_stride % 4))
+            return cf_fail(c, CF_ERR_ARG, "x_sample_stride must be 0 or a multiple of 4 that covers one sample's rows");
+        if (io->x_txt_sample_stride && (io->x_txt_sample_stride < tl * c->d.d || io->x_txt_sample_stride % 4))
+            return cf_fail(c, CF_ERR_ARG, "x_txt_sample_stride must be 0 or a multiple of 4 that covers one sample's rows");
+    }
     if (!c->host[block]) return cf_fail(c, CF_ERR_STATE, "block %d has no registered host blob", block);
     CF_TRY(ensure_device(c));
     const int s = c->block_slot[block];
@@ -1105,14 +1167,14 @@ int cf_op_attention(const uint16_t* Q, const uint16_t* K, const uint16_t* Vt, ui
 int cf_op_ln_modulate(const float* x, const float* shift, const float* scale, uint16_t* xn, int32_t rows, int32_t d,
                       void* stream) {
     if (!x || !shift || !scale || !xn) return cf_fail(nullptr, CF_ERR_ARG, "null operand");
-    hipError_t e = ln_modulate_launch(x, shift, scale, (bf16*)xn, rows, d, d, (hipStream_t)stream);
+    hipError_t e = ln_modulate_launch(x, shift, scale, (bf16*)xn, rows, d, d, 0, 0, 0, (hipStream_t)stream);
     return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_ARG, "ln_modulate: %s", hipGetErrorString(e));
 }
 
 int cf_op_modvec(const void* blob, uint64_t w_off, uint64_t b_off, const float* t, float* m, int32_t n, int32_t K,
                  void* stream) {
     if (!blob || !t || !m || (w_off % 16) || (K % 8)) return cf_fail(nullptr, CF_ERR_ARG, "bad modvec operands");
-    hipError_t e = modvec_launch(flat_view(blob), w_off, b_off, t, m, 0, n, K, (hipStream_t)stream);
+    hipError_t e = modvec_launch(flat_view(blob), w_off, b_off, t, m, 0, n, K, 1, 0, (hipStream_t)stream);
     return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "modvec: %s", hipGetErrorString(e));
 }
 
@@ -1180,54 +1242,58 @@ int fwd_dit(Fwd& F) {
     cf_ctx* c = F.c;
     const cf_model_desc& m = c->d;
     const int d = m.d, f = m.f, nl = m.n_total / m.sp_degree, H = m.n_heads, hd = m.head_dim, lc = m.l_ctx;
+    const int B = batch_of(m), rows = B * nl, rps = B > 1 ? nl : 0;
     const cf_block_io* io = F.io;
     Ws& w = F.ws;
-    CF_TRY(run_modvec(F, "w_mod", "b_mod", io->temb, w.mod));
+    const long mod_bs = 6L * d, xs = x_stride(io, (long)nl * d), dense = (long)nl * d;
+    CF_TRY(run_modvec(F, "w_mod", "b_mod", io->temb, w.mod, mod_bs));
     const float *sh1 = w.mod, *sc1 = w.mod + d, *g1 = w.mod + 2 * d, *sh2 = w.mod + 3 * d, *sc2 = w.mod + 4 * d,
                 *g2 = w.mod + 5 * d;
     // self-attention
-    CF_TRY(run_ln_mod(F, io->x, sh1, sc1, w.xn, nl));
+    CF_TRY(run_ln_mod(F, io->x, sh1, sc1, w.xn, rows, rps, xs, mod_bs));
     if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, "q_norm"))); CF_TRY(need(F, T(F, "k_norm"))); }
-    CF_TRY(run_linear(F, K_QKV, "w_qkv", "b_qkv", plain_linear(w.xn, d, nl, w.qkv, 3 * d)));
+    CF_TRY(run_linear(F, K_QKV, "w_qkv", "b_qkv", plain_linear(w.xn, d, rows, w.qkv, 3 * d)));
     RelayoutArgs r = relayout_for(F, w.qkv, nl, 0, "q_norm", "k_norm");
-    CF_TRY(run_joint_attention(F, &r, 1, w.c, d));
-    CF_TRY(run_linear(F, K_OUT, "w_o", "b_o", resid_linear(w.c, d, nl, io->x, g1, w.x1, d)));
+    CF_TRY(run_joint_attention(F, &r, 1, AttnOut{w.c, nullptr, d, dense, 0}));
+    CF_TRY(run_linear(F, K_OUT, "w_o", "b_o", batched(resid_linear(w.c, d, rows, io->x, g1, w.x1, d), B, nl, mod_bs, xs, dense)));
     // cross-attention: queries from the local tokens (all heads), keys/values from the context
     CF_TRY(need(F, T(F, "ln_c_w")));
     CF_TRY(need(F, T(F, "ln_c_b")));
     {
-        ProfScope ps(c, F.s, K_LN, 0, 6.0 * nl * d);
-        CF_HIP(c, ln_affine_launch(w.x1, F.W, T(F, "ln_c_w").off, T(F, "ln_c_b").off, w.xn, nl, d, F.s));
+        ProfScope ps(c, F.s, K_LN, 0, 6.0 * rows * d);
+        CF_HIP(c, ln_affine_launch(w.x1, F.W, T(F, "ln_c_w").off, T(F, "ln_c_b").off, w.xn, rows, d, F.s));
     }
     if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, "cq_norm"))); CF_TRY(need(F, T(F, "ck_norm"))); }
-    CF_TRY(run_linear(F, K_CROSS_Q, "w_cq", "b_cq", plain_linear(w.xn, d, nl, w.qkv, d)));
-    CF_TRY(run_linear(F, K_CROSS_KV, "w_ckv", "b_ckv", plain_linear((const bf16*)io->ctx, d, lc, w.ckv, 2 * d)));
-    {
+    CF_TRY(run_linear(F, K_CROSS_Q, "w_cq", "b_cq", plain_linear(w.xn, d, rows, w.qkv, d)));
+    CF_TRY(run_linear(F, K_CROSS_KV, "w_ckv", "b_ckv", plain_linear((const bf16*)io->ctx, d, B * lc, w.ckv, 2 * d)));
+    const int lpad = n_pad_of(lc);
+    for (int b = 0; b < B; ++b) {
         RelayoutArgs rq{};
-        rq.src = w.qkv; rq.ld = d; rq.rows = nl; rq.col_q = 0; rq.col_k = -1; rq.col_v = -1;
+        rq.src = w.qkv + (size_t)b * nl * d; rq.ld = d; rq.rows = nl; rq.col_q = 0; rq.col_k = -1; rq.col_v = -1;
         rq.n_heads = H; rq.h0 = 0; rq.h_local = H; rq.hd = hd; rq.W = F.W; rq.has_norm = m.qk_rmsnorm;
         if (m.qk_rmsnorm) { rq.qn_off = T(F, "cq_norm").off; rq.kn_off = T(F, "ck_norm").off; }
-        rq.map = identity_map(nl); rq.row0 = 0; rq.Q = w.cQ; rq.K = nullptr; rq.Vt = nullptr; rq.n_pad = 0;
+        rq.map = identity_map(nl); rq.row0 = 0; rq.Q = w.cQ + (size_t)b * nl * d; rq.K = nullptr; rq.Vt = nullptr; rq.n_pad = 0;
         RelayoutArgs rk = rq;
-        rk.src = w.ckv; rk.ld = 2 * d; rk.rows = lc; rk.col_q = -1; rk.col_k = 0; rk.col_v = d;
-        rk.map = identity_map(lc); rk.Q = nullptr; rk.K = w.cK; rk.Vt = w.cVt; rk.n_pad = n_pad_of(lc);
+        rk.src = w.ckv + (size_t)b * lc * 2 * d; rk.ld = 2 * d; rk.rows = lc; rk.col_q = -1; rk.col_k = 0; rk.col_v = d;
+        rk.map = identity_map(lc); rk.Q = nullptr; rk.K = w.cK + (size_t)b * lc * d; rk.Vt = w.cVt + (size_t)b * d * lpad;
+        rk.n_pad = lpad;
         ProfScope ps(c, F.s, K_RELAYOUT, 0, 2.0 * 2 * ((double)nl * d + 2.0 * lc * d));
         CF_HIP(c, relayout_launch(rq, F.s));
         CF_HIP(c, relayout_launch(rk, F.s));
     }
     {
         AttnArgs a{};
-        a.Q = w.cQ; a.K = w.cK; a.Vt = w.cVt; a.O = w.c; a.o_hs = hd; a.o_qs = d;
-        a.H = H; a.nq = nl; a.nk = lc; a.nk_pad = n_pad_of(lc); a.hd = hd; a.scale = 1.0f / sqrtf((float)hd);
+        a.Q = w.cQ; a.K = w.cK; a.Vt = w.cVt; a.O = w.c; a.o_hs = hd; a.o_qs = d; a.o_bs = dense;
+        a.H = B * H; a.hps = H; a.nq = nl; a.nk = lc; a.nk_pad = lpad; a.hd = hd; a.scale = 1.0f / sqrtf((float)hd);
         if (const char* msg = attn_check(a)) return cf_fail(c, CF_ERR_ARG, "%s", msg);
-        ProfScope ps(c, F.s, K_CROSS_ATTN, 4.0 * H * (double)nl * lc * hd, 0);
+        ProfScope ps(c, F.s, K_CROSS_ATTN, 4.0 * B * H * (double)nl * lc * hd, 0);
         CF_HIP(c, attn_launch(a, F.s));
     }
-    CF_TRY(run_linear(F, K_CROSS_OUT, "w_co", "b_co", resid_linear(w.c, d, nl, w.x1, nullptr, w.x2, d)));
+    CF_TRY(run_linear(F, K_CROSS_OUT, "w_co", "b_co", resid_linear(w.c, d, rows, w.x1, nullptr, w.x2, d)));
     // FFN
-    CF_TRY(run_ln_mod(F, w.x2, sh2, sc2, w.xn, nl));
-    CF_TRY(run_linear(F, K_UP, "w_up", "b_up", gelu_linear(w.xn, d, nl, w.up, f)));
-    return run_linear(F, K_DOWN, "w_down", "b_down", resid_linear(w.up, f, nl, w.x2, g2, io->y, d));
+    CF_TRY(run_ln_mod(F, w.x2, sh2, sc2, w.xn, rows, rps, dense, mod_bs));
+    CF_TRY(run_linear(F, K_UP, "w_up", "b_up", gelu_linear(w.xn, d, rows, w.up, f)));
+    return run_linear(F, K_DOWN, "w_down", "b_down", batched(resid_linear(w.up, f, rows, w.x2, g2, io->y, d), B, nl, mod_bs, dense, xs));
 }
 
 // ---- MM-DiT double-stream block (App. B): per-stream weights, joint attention over the
@@ -1235,34 +1301,45 @@ int fwd_dit(Fwd& F) {
 int fwd_double(Fwd& F) {
     cf_ctx* c = F.c;
     const cf_model_desc& m = c->d;
-    const int d = m.d, f = m.f, nl = m.n_total / m.sp_degree, tl = m.n_txt_total / m.sp_degree;
+    const int d = m.d, f = m.f, nl = m.n_total / m.sp_degree, tl = m.n_txt_total / m.sp_degree, B = batch_of(m);
     const cf_block_io* io = F.io;
     Ws& w = F.ws;
     static const char* st[2] = {"txt", "img"};
     auto nm = [](const char* s, const char* t) { return std::string(s) + "_" + t; };
-    const int row0[2] = {0, tl}, rows[2] = {tl, nl - tl};
+    // workspace rows: all samples' text rows, then all samples' image rows
+    const int per[2] = {tl, nl - tl};                       // rows of one sample
+    const int row0[2] = {0, B * tl}, rows[2] = {B * tl, B * (nl - tl)};
+    const int rps[2] = {B > 1 ? per[0] : 0, B > 1 ? per[1] : 0};
     const float* xin[2] = {io->x_txt, io->x};
     float* yout[2] = {io->y_txt, io->y};
-    for (int s = 0; s < 2; ++s) CF_TRY(run_modvec(F, nm(st[s], "w_mod"), nm(st[s], "b_mod"), io->temb, w.mod + 6 * d * s));
+    const long xs[2] = {x_txt_stride(io, (long)per[0] * d), x_stride(io, (long)per[1] * d)};
+    const long dense[2] = {(long)per[0] * d, (long)per[1] * d};
+    const long mod_bs = 12L * d;
+    for (int s = 0; s < 2; ++s) CF_TRY(run_modvec(F, nm(st[s], "w_mod"), nm(st[s], "b_mod"), io->temb, w.mod + 6 * d * s, mod_bs));
     auto mod = [&](int s, int i) { return w.mod + 6 * d * s + i * d; };
-    for (int s = 0; s < 2; ++s) CF_TRY(run_ln_mod(F, xin[s], mod(s, 0), mod(s, 1), w.xn + (size_t)row0[s] * d, rows[s]));
+    for (int s = 0; s < 2; ++s)
+        CF_TRY(run_ln_mod(F, xin[s], mod(s, 0), mod(s, 1), w.xn + (size_t)row0[s] * d, rows[s], rps[s], xs[s], mod_bs));
     RelayoutArgs parts[2];
     for (int s = 0; s < 2; ++s) {
         if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, nm(st[s], "q_norm")))); CF_TRY(need(F, T(F, nm(st[s], "k_norm")))); }
         CF_TRY(run_linear(F, K_QKV, nm(st[s], "w_qkv"), nm(st[s], "b_qkv"),
                           plain_linear(w.xn + (size_t)row0[s] * d, d, rows[s], w.qkv + (size_t)row0[s] * 3 * d, 3 * d)));
-        parts[s] = relayout_for(F, w.qkv + (size_t)row0[s] * 3 * d, rows[s], row0[s], nm(st[s], "q_norm"), nm(st[s], "k_norm"));
+        parts[s] = relayout_for(F, w.qkv + (size_t)row0[s] * 3 * d, per[s], s ? tl : 0, nm(st[s], "q_norm"), nm(st[s], "k_norm"));
     }
-    CF_TRY(run_joint_attention(F, parts, 2, w.c, d));
+    // one sample: its image rows follow its text rows in w.c; a batch: the streams' regions are apart
+    CF_TRY(run_joint_attention(F, parts, 2, B > 1 ? AttnOut{w.c, w.c + (size_t)row0[1] * d, d, dense[0], dense[1]}
+                                                  : AttnOut{w.c, nullptr, d, (long)nl * d, 0}));
     for (int s = 0; s < 2; ++s)
         CF_TRY(run_linear(F, K_OUT, nm(st[s], "w_o"), nm(st[s], "b_o"),
-                          resid_linear(w.c + (size_t)row0[s] * d, d, rows[s], xin[s], mod(s, 2), w.x1 + (size_t)row0[s] * d, d)));
+                          batched(resid_linear(w.c + (size_t)row0[s] * d, d, rows[s], xin[s], mod(s, 2), w.x1 + (size_t)row0[s] * d, d),
+                                  B, per[s], mod_bs, xs[s], dense[s])));
     for (int s = 0; s < 2; ++s) {
-        CF_TRY(run_ln_mod(F, w.x1 + (size_t)row0[s] * d, mod(s, 3), mod(s, 4), w.xn + (size_t)row0[s] * d, rows[s]));
+        CF_TRY(run_ln_mod(F, w.x1 + (size_t)row0[s] * d, mod(s, 3), mod(s, 4), w.xn + (size_t)row0[s] * d, rows[s], rps[s], dense[s], mod_bs));
         CF_TRY(run_linear(F, K_UP, nm(st[s], "w_up"), nm(st[s], "b_up"),
                           gelu_linear(w.xn + (size_t)row0[s] * d, d, rows[s], w.up + (size_t)row0[s] * f, f)));
         CF_TRY(run_linear(F, K_DOWN, nm(st[s], "w_down"), nm(st[s], "b_down"),
-                          resid_linear(w.up + (size_t)row0[s] * f, f, rows[s], w.x1 + (size_t)row0[s] * d, mod(s, 5), yout[s], d)));
+                          batched(resid_linear(w.up + (size_t)row0[s] * f, f, rows[s], w.x1 + (size_t)row0[s] * d, mod(s, 5), yout[s], d),
+                                  B, per[s], mod_bs, dense[s], xs[s])));
     }
     return CF_OK;
 }

@@ -37,7 +37,9 @@ __device__ __forceinline__ int remote_pos(const TokenMap& m, int i) {
 // is accumulated in the same lane order whatever rows share its wave.
 constexpr int MV_ROWS = 4;
 __global__ __launch_bounds__(256) void modvec_kernel(WView W, uint64_t w_off, uint64_t b_off, const float* __restrict__ t,
-                                                     float* __restrict__ m, int n0, int n1, int K) {
+                                                     float* __restrict__ m, int n0, int n1, int K, long m_bs) {
+    t += (size_t)blockIdx.y * K;                 // one sample of the batch per grid row
+    m += (size_t)blockIdx.y * m_bs;
     const int lane = threadIdx.x & 63;
     const int n = n0 + (blockIdx.x * 4 + (threadIdx.x >> 6)) * MV_ROWS;
     if (n >= n1) return;
@@ -71,11 +73,16 @@ __global__ __launch_bounds__(256) void modvec_kernel(WView W, uint64_t w_off, ui
 template <int NJ, bool AFFINE>
 __global__ __launch_bounds__(256) void ln_kernel(const float* __restrict__ x, const float* __restrict__ shift,
                                                  const float* __restrict__ scale, WView W, uint64_t w_off,
-                                                 uint64_t b_off, bf16* __restrict__ out, int rows, int d, int ld_out) {
+                                                 uint64_t b_off, bf16* __restrict__ out, int rows, int d, int ld_out,
+                                                 int rows_per_sample, long x_bs, long mod_bs) {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
-    const float* xr = x + (size_t)row * d;
+    // a batch stacks samples along the rows: each has its own modulation vectors and may sit at its own stride
+    int smp = 0, ri = row;
+    if (rows_per_sample) { smp = row / rows_per_sample; ri = row - smp * rows_per_sample; }
+    const float* xr = x + (size_t)smp * x_bs + (size_t)ri * d;
+    if (!AFFINE) { shift += (size_t)smp * mod_bs; scale += (size_t)smp * mod_bs; }
     float4 v[NJ];
     float s = 0.f;
 #pragma unroll
@@ -117,11 +124,12 @@ __global__ __launch_bounds__(256) void ln_kernel(const float* __restrict__ x, co
 
 template <bool AFFINE>
 hipError_t ln_dispatch(const float* x, const float* shift, const float* scale, const WView& W, uint64_t w_off,
-                       uint64_t b_off, bf16* out, int rows, int d, int ld_out, hipStream_t s) {
+                       uint64_t b_off, bf16* out, int rows, int d, int ld_out, int rows_per_sample, long x_bs, long mod_bs,
+                       hipStream_t s) {
     if (rows <= 0) return hipSuccess;
-    if (d % 256 || d > 4096) return hipErrorInvalidValue;
+    if (d % 256 || d > 4096 || rows_per_sample < 0 || (x_bs % 4) || (mod_bs % 4)) return hipErrorInvalidValue;
     const dim3 grid((rows + 3) / 4), blk(256);
-#define CF_LN_CASE(NJ) case NJ: hipLaunchKernelGGL((ln_kernel<NJ, AFFINE>), grid, blk, 0, s, x, shift, scale, W, w_off, b_off, out, rows, d, ld_out); break;
+#define CF_LN_CASE(NJ) case NJ: hipLaunchKernelGGL((ln_kernel<NJ, AFFINE>), grid, blk, 0, s, x, shift, scale, W, w_off, b_off, out, rows, d, ld_out, rows_per_sample, x_bs, mod_bs); break;
     switch (d / 256) {
         CF_LN_CASE(1) CF_LN_CASE(2) CF_LN_CASE(3) CF_LN_CASE(4) CF_LN_CASE(6) CF_LN_CASE(8) CF_LN_CASE(12) CF_LN_CASE(16)
         default: return hipErrorInvalidValue;
@@ -305,9 +313,12 @@ __global__ __launch_bounds__(256) void pre_attention_kernel(PreAttnArgs a) {
 
 // attention output on the full sequence -> projection operand rows + send buffer; peer heads in
 __global__ __launch_bounds__(256) void attn_gather_kernel(const bf16* __restrict__ O, const bf16* __restrict__ peer_attn,
-                                                          bf16* __restrict__ dst, int ld, bf16* __restrict__ send_attn,
-                                                          int n_heads, int h0, int h_local, int hd, TokenMap map) {
+                                                          bf16* __restrict__ dst, bf16* __restrict__ dst1, int ld,
+                                                          bf16* __restrict__ send_attn, int n_heads, int h0, int h_local,
+                                                          int hd, TokenMap map) {
     const int cpr = hd / 8;
+    // local row i of the first segment sits at dst + i*ld, of the second at dst1 + (i - len0)*ld
+    auto row_ptr = [&](int i) { return i < map.len0 ? dst + (size_t)i * ld : dst1 + (size_t)(i - map.len0) * ld; };
     const int n_rem = map.n_total - map.n_local;
     const long n_loc = (long)h_local * map.n_local * cpr;
     const long n_snd = send_attn ? (long)h_local * n_rem * cpr : 0;
@@ -319,7 +330,7 @@ __global__ __launch_bounds__(256) void attn_gather_kernel(const bf16* __restrict
             const int h = rest % h_local;
             const int i = rest / h_local;
             const bf16* s = O + ((size_t)h * map.n_total + local_pos(map, i)) * hd + c * 8;
-            *(uint4*)(dst + (size_t)i * ld + (h0 + h) * hd + c * 8) = *(const uint4*)s;
+            *(uint4*)(row_ptr(i) + (h0 + h) * hd + c * 8) = *(const uint4*)s;
         } else if (q < n_loc + n_snd) {
             const long qq = q - n_loc;
             const int c = qq % cpr;
@@ -336,7 +347,7 @@ __global__ __launch_bounds__(256) void attn_gather_kernel(const bf16* __restrict
             const int i = rest / (n_heads - h_local);
             const int hh = ho < h0 ? ho : ho + h_local;
             const bf16* s = peer_attn + ((size_t)i * (n_heads - h_local) + ho) * hd + c * 8;
-            *(uint4*)(dst + (size_t)i * ld + hh * hd + c * 8) = *(const uint4*)s;
+            *(uint4*)(row_ptr(i) + hh * hd + c * 8) = *(const uint4*)s;
         }
     }
 }
@@ -376,22 +387,23 @@ inline int grid_for(long items, int per_block, int cap = 256 * 16) {
 }  // namespace
 
 hipError_t modvec_launch(const WView& W, uint64_t w_off, uint64_t b_off, const float* t, float* m, int n0, int n1,
-                         int K, hipStream_t s) {
+                         int K, int batch, long m_bs, hipStream_t s) {
     if (n1 <= n0) return hipSuccess;
-    if (K % 8) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(modvec_kernel, dim3((n1 - n0 + 4 * MV_ROWS - 1) / (4 * MV_ROWS)), dim3(256), 0, s, W, w_off, b_off, t, m, n0, n1, K);
+    if (K % 8 || batch < 1 || batch > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(modvec_kernel, dim3((n1 - n0 + 4 * MV_ROWS - 1) / (4 * MV_ROWS), batch), dim3(256), 0, s, W, w_off, b_off, t, m, n0,
+                       n1, K, m_bs);
     return hipGetLastError();
 }
 
 hipError_t ln_modulate_launch(const float* x, const float* shift, const float* scale, bf16* xn, int rows, int d,
-                              int ld_out, hipStream_t s) {
+                              int ld_out, int rows_per_sample, long x_bs, long mod_bs, hipStream_t s) {
     WView none{nullptr, nullptr, 0};
-    return ln_dispatch<false>(x, shift, scale, none, 0, 0, xn, rows, d, ld_out, s);
+    return ln_dispatch<false>(x, shift, scale, none, 0, 0, xn, rows, d, ld_out, rows_per_sample, x_bs, mod_bs, s);
 }
 
 hipError_t ln_affine_launch(const float* x, const WView& W, uint64_t w_off, uint64_t b_off, bf16* xn, int rows, int d,
                             hipStream_t s) {
-    return ln_dispatch<true>(x, nullptr, nullptr, W, w_off, b_off, xn, rows, d, d, s);
+    return ln_dispatch<true>(x, nullptr, nullptr, W, w_off, b_off, xn, rows, d, d, 0, 0, 0, s);
 }
 
 hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf16* peer_q, const bf16* peer_k,
@@ -432,11 +444,12 @@ hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf
 
 hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s) { return pre_attention_launch(&r, 1, nullptr, nullptr, nullptr, s); }
 
-hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, int ld, bf16* send_attn,
+hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, bf16* dst1, int ld, bf16* send_attn,
                               int n_heads, int h0, int h_local, int hd, TokenMap map, hipStream_t s) {
     const int cpr = hd / 8;
     const long total = (long)h_local * map.n_total * cpr + (long)map.n_local * (n_heads - h_local) * cpr;
-    hipLaunchKernelGGL(attn_gather_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, O_full, peer_attn, dst, ld,
+    if (!dst1) dst1 = dst + (size_t)map.len0 * ld;
+    hipLaunchKernelGGL(attn_gather_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, O_full, peer_attn, dst, dst1, ld,
                        send_attn, n_heads, h0, h_local, hd, map);
     return hipGetLastError();
 }

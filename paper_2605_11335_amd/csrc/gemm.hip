@@ -257,11 +257,6 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                     b[2] = __uint_as_float(bb.y << 16);
                     b[3] = __uint_as_float(bb.y & 0xffff0000u);
                 }
-                float gt[4] = {1.f, 1.f, 1.f, 1.f};
-                if (!OUT_BF16 && g.gate) {
-                    const float4 t = *(const float4*)(g.gate + n);
-                    gt[0] = t.x; gt[1] = t.y; gt[2] = t.z; gt[3] = t.w;
-                }
                 const bool act = OUT_BF16 && n >= g.n_split;
 #pragma unroll
                 for (int j = 0; j < MT; ++j) {
@@ -279,9 +274,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                         for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
                         *(bf16x4*)dst = o;
                     } else {
-                        float4 o;
-                        o.x = gt[0] * v[0]; o.y = gt[1] * v[1]; o.z = gt[2] * v[2]; o.w = gt[3] * v[3];
-                        *(float4*)dst = o;
+                        *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
                     }
                 }
             }
@@ -300,11 +293,18 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
                                               : g.out1 + (size_t)m * g.ld1 + g.col1_off + (n - g.n_split);
                     *(uint4*)dst = val;
                 } else {
-                    const float4 rr = *(const float4*)(g.resid + (size_t)m * g.ldy + n);
+                    // the gate belongs to the row's sample; product rounded before the sum
+                    int b = 0, i = m;
+                    if (g.rows_per_sample) { b = m / g.rows_per_sample; i = m - b * g.rows_per_sample; }
+                    const float4 rr = *(const float4*)(g.resid + (size_t)b * g.resid_bs + (size_t)i * g.ldy + n);
+                    float4 gt = make_float4(1.f, 1.f, 1.f, 1.f);
+                    if (g.gate) gt = *(const float4*)(g.gate + (size_t)b * g.gate_bs + n);
                     float4 o;
-                    o.x = rr.x + __uint_as_float(val.x); o.y = rr.y + __uint_as_float(val.y);
-                    o.z = rr.z + __uint_as_float(val.z); o.w = rr.w + __uint_as_float(val.w);
-                    *(float4*)(g.y + (size_t)m * g.ldy + n) = o;
+                    o.x = __fadd_rn(rr.x, __fmul_rn(gt.x, __uint_as_float(val.x)));
+                    o.y = __fadd_rn(rr.y, __fmul_rn(gt.y, __uint_as_float(val.y)));
+                    o.z = __fadd_rn(rr.z, __fmul_rn(gt.z, __uint_as_float(val.z)));
+                    o.w = __fadd_rn(rr.w, __fmul_rn(gt.w, __uint_as_float(val.w)));
+                    *(float4*)(g.y + (size_t)b * g.y_bs + (size_t)i * g.ldy + n) = o;
                 }
             }
         }
@@ -338,6 +338,7 @@ const char* gemm_check(const GemmArgs& g) {
     if (g.n0 < 0 || g.n1 > g.N || g.n0 >= g.n1 || (g.n0 % 8) || (g.n1 % 8)) return "gemm: bad feature panel";
     if (g.lda < g.K || (g.lda % 8)) return "gemm: lda must be >= K and a multiple of 8";
     if ((uint64_t)g.lda * 512 >= (1ull << 32)) return "gemm: lda too large for 32-bit offsets inside a tile";
+    if ((uint64_t)g.M * g.lda * 2 >= (1ull << 32)) return "gemm: activations beyond 4 GiB (32-bit buffer range)";
     if ((g.w_off % 16) || (g.has_bias && (g.bias_off % 16))) return "gemm: weight/bias offsets must be 16-byte aligned";
     if (((uintptr_t)g.A) % 16) return "gemm: A must be 16-byte aligned";
     if (g.epi == EPI_SPLIT_GELU) {
@@ -348,6 +349,9 @@ const char* gemm_check(const GemmArgs& g) {
     } else if (g.epi == EPI_GATE_RESID) {
         if (!g.resid || !g.y || (g.ldy % 4) || ((uintptr_t)g.y % 16) || ((uintptr_t)g.resid % 16)) return "gemm: bad residual/output";
         if (g.gate && ((uintptr_t)g.gate % 16)) return "gemm: gate must be 16-byte aligned";
+        if (g.rows_per_sample < 0 || (g.rows_per_sample && g.M % g.rows_per_sample)) return "gemm: M must be whole samples";
+        if (g.rows_per_sample && ((g.gate_bs % 4) || (g.resid_bs % 4) || (g.y_bs % 4) || g.gate_bs < 0 || g.resid_bs < 0 || g.y_bs < 0))
+            return "gemm: sample strides must be non-negative multiples of 4 elements";
     } else {
         return "gemm: unknown epilogue";
     }

@@ -22,6 +22,10 @@ struct GemmArgs {
     int act_erf;        // the activation of out1: 0 = tanh form of GELU, 1 = erf form
     // EPI_GATE_RESID: y[m*ldy + n] = resid[m*ldy + n] + gate[n] * (acc + bias)   (fp32; gate NULL = 1)
     const float* resid; const float* gate; float* y; int ldy;
+    // A batch of samples stacked along M (rows_per_sample > 0): row m is row i = m % rows_per_sample of
+    // sample b = m / rows_per_sample; it uses gate + b*gate_bs and sits at b*resid_bs + i*ldy in resid,
+    // b*y_bs + i*ldy in y (strides in elements).  rows_per_sample = 0: one sample, strides unused.
+    int rows_per_sample; long gate_bs, resid_bs, y_bs;
 };
 const char* gemm_check(const GemmArgs& g);
 int gemm_tile(const GemmArgs& g);      // tile gemm_launch will use: 0 = 256x256, 1 = 128x128
@@ -39,22 +43,25 @@ struct AttnArgs {
     const bf16* Q;      // [H, nq, hd] head-major
     const bf16* K;      // [H, nk, hd]
     const bf16* Vt;     // [H, hd, nk_pad] keys contiguous, pad columns zero
-    bf16* O;            // element (h, q, :) at O + h*o_hs + q*o_qs
-    long o_hs, o_qs;
+    bf16* O;            // element (h, q, :) at O + (h / hps)*o_bs + (h % hps)*o_hs + q*o_qs
+    long o_hs, o_qs, o_bs;
     int H, nq, nk, nk_pad, hd;
+    int hps;            // heads per sample (a batch is H / hps samples of hps heads each); 0 = H
     float scale;        // 1/sqrt(hd)
 };
 const char* attn_check(const AttnArgs& a);
 hipError_t attn_launch(const AttnArgs& a, hipStream_t s);
 
-// m[n] = sum_k W[n,k] t[k] + b[n]  (fp32 out), rows [n0, n1)
+// m[b][n] = sum_k W[n,k] t[b][k] + bias[n]  (fp32 out), rows [n0, n1), for `batch` vectors t + b*K -> m + b*m_bs
 hipError_t modvec_launch(const WView& W, uint64_t w_off, uint64_t b_off, const float* t, float* m,
-                         int n0, int n1, int K, hipStream_t s);
+                         int n0, int n1, int K, int batch, long m_bs, hipStream_t s);
 
 // xn = LN(x) * (1 + scale) + shift  (fp32 in, bf16 out); with ln_w/ln_b (blob offsets, has_affine)
 // instead: xn = LN(x) * w + b.
+// Row r of a batch is row r % rows_per_sample of sample b = r / rows_per_sample: read at x + b*x_bs, modulated
+// with shift + b*mod_bs, scale + b*mod_bs; written densely to xn + r*ld_out.
 hipError_t ln_modulate_launch(const float* x, const float* shift, const float* scale, bf16* xn,
-                              int rows, int d, int ld_out, hipStream_t s);
+                              int rows, int d, int ld_out, int rows_per_sample, long x_bs, long mod_bs, hipStream_t s);
 hipError_t ln_affine_launch(const float* x, const WView& W, uint64_t w_off, uint64_t b_off, bf16* xn,
                             int rows, int d, hipStream_t s);
 
@@ -82,8 +89,9 @@ hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf
                                 const bf16* peer_v, hipStream_t s);
 
 // After attention on the full sequence: local rows of the local heads and peer_attn (other heads)
-// into the [n_local, ld] operand of the output projection; remote rows into send_attn.
-hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, int ld,
+// into the [n_local, ld] operand of the output projection; remote rows into send_attn.  Local
+// rows of the second segment of the map go to dst1 when given (NULL: they follow the first in dst).
+hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, bf16* dst1, int ld,
                               bf16* send_attn, int n_heads, int h0, int h_local, int hd,
                               TokenMap map, hipStream_t s);
 

@@ -24,10 +24,11 @@ namespace {
 
 // activation rows a weight matrix multiplies, by tensor name
 double rows_of(const cf_model_desc& m, int kind, const std::string& name) {
-    const double nl = (double)m.n_total / m.sp_degree;
-    if (kind == CF_DIT_CROSS) return name == "w_ckv" ? (double)m.l_ctx : nl;
+    const double B = m.batch > 0 ? m.batch : 1;
+    const double nl = B * m.n_total / m.sp_degree;
+    if (kind == CF_DIT_CROSS) return name == "w_ckv" ? B * m.l_ctx : nl;
     if (kind == CF_DOUBLE_STREAM) {
-        const double tl = (double)m.n_txt_total / m.sp_degree;
+        const double tl = B * m.n_txt_total / m.sp_degree;
         return name.rfind("txt_", 0) == 0 ? tl : nl - tl;
     }
     return nl;
@@ -44,12 +45,13 @@ int row_group(int m_rows) {
 // per-chunk share of one block's compute (sums to 1)
 std::vector<double> segment_shares(const cf_model_desc& m, const Plan& p, uint64_t chunk_bytes) {
     std::vector<double> seg(p.n_chunks, 0.0);
+    const double B = m.batch > 0 ? m.batch : 1;
     const double nl = (double)m.n_total / m.sp_degree, hl = (double)m.n_heads / m.sp_degree;
     const char* attn_after = p.kind == CF_SINGLE_STREAM ? "w1" : (p.kind == CF_DIT_CROSS ? "w_qkv" : "img_w_qkv");
     for (const TensorDesc& t : p.tensors) {
         if (t.rows <= 1) continue;                              // biases and norm weights: no matrix work
         const bool modvec = t.name.find("w_mod") != std::string::npos;
-        const double act = modvec ? 1.0 : rows_of(m, p.kind, t.name);
+        const double act = modvec ? B : rows_of(m, p.kind, t.name);
         // a row group counts once its last byte has landed; the modulation matrix-vector product
         // goes 8 rows at a time
         const uint64_t G = modvec ? 8 : (uint64_t)row_group((int)act), row_bytes = 2ull * t.cols;
@@ -58,8 +60,8 @@ std::vector<double> segment_shares(const cf_model_desc& m, const Plan& p, uint64
             seg[(t.off + r1 * row_bytes - 1) / chunk_bytes] += 2.0 * act * (double)(r1 - r0) * t.cols;
         }
         const uint64_t last = (t.off + t.bytes() - 1) / chunk_bytes;
-        if (t.name == attn_after) seg[last] += 4.0 * hl * (double)m.n_total * m.n_total * m.head_dim;
-        if (t.name == "w_ckv") seg[last] += 4.0 * m.n_heads * nl * m.l_ctx * m.head_dim;
+        if (t.name == attn_after) seg[last] += 4.0 * B * hl * (double)m.n_total * m.n_total * m.head_dim;
+        if (t.name == "w_ckv") seg[last] += 4.0 * B * m.n_heads * nl * m.l_ctx * m.head_dim;
     }
     double sum = 0;
     for (double v : seg) sum += v;

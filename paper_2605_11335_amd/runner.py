@@ -96,9 +96,10 @@ class BlockRunner:
                 t[k] = _dev_bf16(inputs[k], dev)
             hl, ho, hd = cfg.h_local, cfg.n_heads - cfg.h_local, cfg.head_dim
             nl, nrem = cfg.n_local, cfg.n_total - cfg.n_local
+            lead = (cfg.batch,) if cfg.batch > 1 else ()
             for k in ("send_q", "send_k", "send_v"):
-                t[k] = torch.zeros((ho, nl, hd), dtype=torch.int16, device=dev)
-            t["send_attn"] = torch.zeros((hl, nrem, hd), dtype=torch.int16, device=dev)
+                t[k] = torch.zeros(lead + (ho, nl, hd), dtype=torch.int16, device=dev)
+            t["send_attn"] = torch.zeros(lead + (hl, nrem, hd), dtype=torch.int16, device=dev)
         return t
 
     def io_struct(self, t: Dict[str, torch.Tensor]) -> B.cf_block_io:

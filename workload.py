@@ -49,6 +49,7 @@ class BlockConfig:
     n_double: int = 0   # mixed model: the first n_double blocks are double-stream, the rest `kind`
     rope: bool = False  # hand rotary position tables to the block (q, k rotated after the norm)
     gelu_erf: bool = False  # MLP activation x * Phi(x) instead of its tanh approximation
+    batch: int = 1      # B: independent samples per forward (own activations, timestep embedding, peers)
 
     @property
     def n_local(self) -> int:
@@ -204,19 +205,27 @@ def gen_block_params(cfg: BlockConfig, block: int) -> Dict[str, np.ndarray]:
             for name, shape, std, mean in param_specs(cfg)}
 
 
-def gen_block_inputs(cfg: BlockConfig, block: int) -> Dict[str, np.ndarray]:
+def gen_block_inputs(cfg: BlockConfig, block: int, sample: int = None) -> Dict[str, np.ndarray]:
     """Activations entering one block on this rank, plus the seeded stand-ins for what the
     Ulysses all-to-alls would have delivered from the other ranks.
 
     x, temb, (x_txt), (ctx): float32 arrays with bf16-representable values.
     peer_q/k/v: [h_local, n_total - n_local, head_dim] bf16 bits (q,k unit-variance like
     RMS-normalised projections; v half that).  peer_attn: [n_local, H - h_local, head_dim].
+
+    With cfg.batch > 1 and no `sample`, every array but the rotary tables is the stack of the
+    samples' arrays along a new leading axis; `sample` = b gives sample b alone (sample 0 of a
+    batch is the batch-1 input).
     """
+    if sample is None and cfg.batch > 1:
+        per = [gen_block_inputs(cfg, block, b) for b in range(cfg.batch)]
+        return {k: (per[0][k] if k.startswith("rope_") else np.stack([p[k] for p in per])) for k in per[0]}
     d, hd = cfg.d, cfg.head_dim
     nl, hl = cfg.n_local, cfg.h_local
     nrem = cfg.n_total - nl
     out: Dict[str, np.ndarray] = {}
-    act = lambda t, shape, std=1.0: bf16_bits_to_f32(normal_bf16(cfg.name, block, t, shape, std))
+    tag = lambda t: t if not sample else f"{t}#{sample}"
+    act = lambda t, shape, std=1.0: bf16_bits_to_f32(normal_bf16(cfg.name, block, tag(t), shape, std))
     if cfg.kind == KIND_DOUBLE:
         tl = cfg.n_txt_local
         out["x"] = act("x", (nl - tl, d))
@@ -227,15 +236,15 @@ def gen_block_inputs(cfg: BlockConfig, block: int) -> Dict[str, np.ndarray]:
     if cfg.kind == KIND_DIT:
         out["ctx"] = act("ctx", (cfg.l_ctx, d))
     if cfg.rope:
-        # seeded angles, one per (local row, pair of head dimensions), the same for every head
+        # seeded angles, one per (local row, pair of head dimensions), the same for every head and sample
         ang = _rng(cfg.name, block, "rope").uniform(0.0, 2.0 * np.pi, size=(nl, hd // 2))
         out["rope_cos"] = np.cos(ang).astype(np.float32)
         out["rope_sin"] = np.sin(ang).astype(np.float32)
     if cfg.sp_degree > 1:
-        out["peer_q"] = normal_bf16(cfg.name, block, "peer_q", (hl, nrem, hd), 1.0)
-        out["peer_k"] = normal_bf16(cfg.name, block, "peer_k", (hl, nrem, hd), 1.0)
-        out["peer_v"] = normal_bf16(cfg.name, block, "peer_v", (hl, nrem, hd), 0.5)
-        out["peer_attn"] = normal_bf16(cfg.name, block, "peer_attn", (nl, cfg.n_heads - hl, hd), 0.5)
+        out["peer_q"] = normal_bf16(cfg.name, block, tag("peer_q"), (hl, nrem, hd), 1.0)
+        out["peer_k"] = normal_bf16(cfg.name, block, tag("peer_k"), (hl, nrem, hd), 1.0)
+        out["peer_v"] = normal_bf16(cfg.name, block, tag("peer_v"), (hl, nrem, hd), 0.5)
+        out["peer_attn"] = normal_bf16(cfg.name, block, tag("peer_attn"), (nl, cfg.n_heads - hl, hd), 0.5)
     return out
 
 
