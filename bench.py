@@ -39,8 +39,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="flux", choices=["toy", "flux", "wan", "hunyuan", "flux_mm", "toy_mm"])
+    ap.add_argument("--config", default="flux", choices=["toy", "flux", "wan", "hunyuan", "flux_mm", "hunyuan_mm", "toy_mm"])
     ap.add_argument("--blocks", type=int, default=0, help="override the number of blocks (0 = the config's)")
+    ap.add_argument("--shared-weights", action="store_true",
+                    help="one seeded host blob per block kind, registered for every block of that kind: lets the full "
+                         "57/60-block stacks run (every block still has its own resident copy and its own transfers)")
     ap.add_argument("--batch", type=int, default=1, help="samples per forward (B of App. B); the headline workload is 1")
     ap.add_argument("--resident", type=float, default=0.0, help="resident fraction of the offloaded arm")
     ap.add_argument("--chunk-mib", type=float, default=0.0, help="chunk size in MiB (0 = the config's chunk count)")
@@ -200,7 +203,7 @@ def main():
     from paper_2605_11335_amd.runner import BlockRunner, chunk_bytes_for
 
     cfg = wl.CONFIGS[args.config].with_(batch=max(1, args.batch))
-    if cfg.n_double and cfg.n_blocks > 12 and not args.blocks:
+    if cfg.n_double and cfg.n_blocks > 12 and not args.blocks and not args.shared_weights:
         args.blocks = 6          # the full MMDiT stack holds 24 GB of distinct seeded weights; keep its 1:2 mix
     if args.blocks:
         # a mixed stack keeps its proportion of double-stream blocks
@@ -211,9 +214,20 @@ def main():
 
     t_setup = time.perf_counter()
     run = BlockRunner(cfg, chunk_bytes=chunk_bytes)
+    first_of_kind = {}
     for b in range(L):
-        run.register_params(b, wl.gen_block_params(cfg.block_cfg(b), b))
-    tens = [run.make_io(wl.gen_block_inputs(cfg.block_cfg(b), b)) for b in range(L)]
+        k = cfg.kind_of(b)
+        if args.shared_weights and k in first_of_kind:
+            run.register_blob(b, run.blobs[first_of_kind[k]])
+        else:
+            run.register_params(b, wl.gen_block_params(cfg.block_cfg(b), b))
+            first_of_kind.setdefault(k, b)
+    if args.shared_weights:
+        # activations too: one seeded set of inputs per kind (peer tensors of a video share are 0.5 GB each)
+        per_kind = {k: run.make_io(wl.gen_block_inputs(cfg.block_cfg(b), b)) for k, b in first_of_kind.items()}
+        tens = [dict(per_kind[cfg.kind_of(b)]) for b in range(L)]
+    else:
+        tens = [run.make_io(wl.gen_block_inputs(cfg.block_cfg(b), b)) for b in range(L)]
     bufs = chain_residual_buffers(cfg, run, tens, torch, wl)
     ios = [run.io_struct(t) for t in tens]
     blob_total = run.total_blob_bytes                      # weight bytes of the whole stack
@@ -307,7 +321,7 @@ def main():
                                f"attention {cfg.h_local} heads over {cfg.n_total})" + (f", batch {cfg.batch}" if cfg.batch > 1 else ""),
                    "arm": "chunked offload" if do_off else "resident",
                    "chunk_bytes": chunk_bytes, "chunks_per_block": run.n_chunks, "blob_bytes": run.blob_bytes,
-                   "blob_bytes_all_blocks": blob_total,
+                   "blob_bytes_all_blocks": blob_total, "shared_weights": bool(args.shared_weights),
                    "resident_fraction": actual_r if do_off else 1.0, "contention": args.contention},
         "offload_ms": off_ms, "resident_ms": res_ms,
         "offload_over_resident": (off_ms / res_ms) if (do_res and do_off) else None,

@@ -74,6 +74,14 @@ class BlockRunner:
         self.blobs[block] = blob
         return blob
 
+    def register_blob(self, block: int, blob: torch.Tensor) -> None:
+        """Register an already packed pinned blob (several blocks of one kind may share one: what
+        travels over the link and what stays resident is per block either way)."""
+        self.ctx.cf_register_block(block, blob)
+        while len(self.blobs) <= block:
+            self.blobs.append(None)
+        self.blobs[block] = blob
+
     # ---- activations
     def make_io(self, inputs: Dict[str, np.ndarray]) -> Dict[str, torch.Tensor]:
         cfg, dev = self.cfg, self.device

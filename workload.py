@@ -107,6 +107,11 @@ CONFIGS: Dict[str, BlockConfig] = {
     "flux_mm": BlockConfig("flux_mm", KIND_SINGLE, n_blocks=57, d=3072, n_heads=24, head_dim=128, f=12288,
                            n_total=4608, sp_degree=2, n_txt=512, qk_rmsnorm=True, n_chunks=8,
                            temb_std=_temb_std(3072), n_double=19),
+    # The composition of a HunyuanVideo-like denoiser (App. C, Table 1): 20 double-stream blocks,
+    # then 40 single-stream blocks over the same 118800 video + 256 text tokens, P=2.
+    "hunyuan_mm": BlockConfig("hunyuan_mm", KIND_SINGLE, n_blocks=60, d=3072, n_heads=24, head_dim=128, f=12288,
+                              n_total=118800 + 256, sp_degree=2, n_txt=256, qk_rmsnorm=True, n_chunks=8,
+                              temb_std=_temb_std(3072), n_double=20),
     # The same composition small enough for the CPU oracle in seconds.
     "toy_mm": BlockConfig("toy_mm", KIND_SINGLE, n_blocks=3, d=512, n_heads=8, head_dim=64, f=2048,
                           n_total=640, sp_degree=2, n_txt=128, qk_rmsnorm=True, n_chunks=4, temb_std=1.0,
