@@ -10,6 +10,9 @@
 #include "context.h"
 
 static std::string g_create_err;
+// The prefetch worker reports into a string of its own: the context's message belongs to the
+// caller's thread, which may be failing a call of its own at the same moment.
+static thread_local std::string* t_err_sink = nullptr;
 
 int cf_fail(const cf_ctx* c, int code, const char* fmt, ...) {
     char buf[512];
@@ -17,7 +20,9 @@ int cf_fail(const cf_ctx* c, int code, const char* fmt, ...) {
     va_start(ap, fmt);
     vsnprintf(buf, sizeof buf, fmt, ap);
     va_end(ap);
-    if (c) c->err = buf; else g_create_err = buf;
+    if (t_err_sink) *t_err_sink = buf;
+    else if (c) c->err = buf;
+    else g_create_err = buf;
     return code;
 }
 
@@ -242,6 +247,8 @@ int enqueue_block_copies(cf_ctx* c, int block, int s, hipStream_t copy, bool bou
 
 void worker_main(cf_ctx* c) {
     (void)hipSetDevice(c->device);
+    std::string my_err;
+    t_err_sink = &my_err;
     for (;;) {
         PrefetchJob job;
         {
@@ -252,15 +259,13 @@ void worker_main(cf_ctx* c) {
             c->jobs.pop_front();
             c->worker_busy = true;
         }
-        std::string saved = c->err;
         int rc = enqueue_block_copies(c, job.block, job.slot, job.copy, true);
         {
             std::lock_guard<std::mutex> lk(c->mu);
             if (rc != CF_OK) {
-                c->worker_err = c->err;
+                c->worker_err = my_err;
                 c->enq_count[job.slot] = c->max_chunks;   // never leave the consumer waiting
             }
-            c->err = saved;
             c->worker_busy = false;
         }
         c->cv.notify_all();
