@@ -271,6 +271,21 @@ def main():
             out[k["name"]] = e
         return out
 
+    def breakdown(ktimes, n_steps, step_ms):
+        """Step-time breakdown in the form of Sec. 4.3: kernels, time parked on chunk events (the
+        exposed prefetch), time parked on emulated collectives, and the rest (launch gaps, event
+        overhead), per step of the profiled pass."""
+        waits = {"prefetch_stall": 0.0, "collective_wait": 0.0}
+        comp = 0.0
+        for k in ktimes:
+            if k["name"] in waits:
+                waits[k["name"]] += k["total_ms"] / n_steps
+            else:
+                comp += k["total_ms"] / n_steps
+        return {"step_ms_profiled": step_ms, "compute_ms": comp, "prefetch_stall_ms": waits["prefetch_stall"],
+                "collective_wait_ms": waits["collective_wait"],
+                "other_ms": step_ms - comp - waits["prefetch_stall"] - waits["collective_wait"]}
+
     set_contention(args.contention)
     total_steps = args.steps + args.warmup
     do_res, do_off = args.only in ("both", "resident"), args.only in ("both", "offload")
@@ -337,6 +352,8 @@ def main():
                      "avg_launch_ms": dom_ms, "flops_per_launch": dom_flops, "launches": dom["launches"],
                      "traffic": TRAFFIC.get((cfg.name, dom["name"]))},
         "kernels_resident_arm": table(kt_res, total_steps), "kernels_offload_arm": table(kt_off, total_steps),
+        "breakdown_resident_arm": breakdown(kt_res, total_steps, res_prof_ms) if do_res else None,
+        "breakdown_offload_arm": breakdown(kt_off, total_steps, off_prof_ms) if do_off else None,
     }
 
     # ---- overlap-model view of this machine (Eq. 1-4 with the measured eta's)

@@ -289,31 +289,20 @@ void worker_stop(cf_ctx* c) {
     c->worker_stop = false;
 }
 
-// device-side wait for chunk k of `block` on stream s
-int wait_chunk(cf_ctx* c, int block, int k, hipStream_t s) {
-    if (k < c->P(block).n_res_chunks) return CF_OK;
-    const int sl = c->block_slot[block];
-    if (sl < 0 || c->slot_tenant[sl] != block || c->slot_state[sl] == SLOT_EMPTY)
-        return cf_fail(c, CF_ERR_STATE, "block %d: chunk %d awaited but its prefetch was not begun", block, k);
-    if (c->worker.joinable()) {
-        std::unique_lock<std::mutex> lk(c->mu);
-        c->cv.wait(lk, [&] { return c->enq_count[sl] > k; });
-        if (!c->worker_err.empty()) return cf_fail(c, CF_ERR_HIP, "prefetch worker: %s", c->worker_err.c_str());
-    }
-    CF_HIP(c, hipStreamWaitEvent(s, c->chunk_ev[sl][k], 0));
-    return CF_OK;
-}
-
 // ------------------------------------------------------------------------------------------
 // profiling: hipEvent pair around each kernel launch, resolved lazily
 // ------------------------------------------------------------------------------------------
 enum Kid {
     K_MODVEC, K_LN, K_LIN1, K_QKV, K_RELAYOUT, K_ATTN, K_GATHER, K_LIN2, K_OUT, K_UP, K_DOWN,
-    K_CROSS_Q, K_CROSS_KV, K_CROSS_ATTN, K_CROSS_OUT, K_COUNT
+    K_CROSS_Q, K_CROSS_KV, K_CROSS_ATTN, K_CROSS_OUT,
+    // not kernels: time the compute stream spends parked on a chunk's event (the exposed prefetch of
+    // Sec. 4.3's breakdown) and on an emulated collective's completion
+    K_CHUNK_WAIT, K_COMM_WAIT, K_COUNT
 };
 const char* kKidName[K_COUNT] = {"modvec", "ln_modulate", "gemm_lin1", "gemm_qkv", "pre_attention",
                                  "attention", "attn_gather", "gemm_lin2", "gemm_out", "gemm_up", "gemm_down",
-                                 "gemm_cross_q", "gemm_cross_kv", "cross_attention", "gemm_cross_out"};
+                                 "gemm_cross_q", "gemm_cross_kv", "cross_attention", "gemm_cross_out",
+                                 "prefetch_stall", "collective_wait"};
 
 hipEvent_t prof_event(cf_ctx* c) {
     if (!c->ev_pool.empty()) { hipEvent_t e = c->ev_pool.back(); c->ev_pool.pop_back(); return e; }
@@ -364,6 +353,23 @@ int prof_resolve(cf_ctx* c) {
     c->prof_pending.clear();
     return CF_OK;
 }
+
+// device-side wait for chunk k of `block` on stream s
+int wait_chunk(cf_ctx* c, int block, int k, hipStream_t s) {
+    if (k < c->P(block).n_res_chunks) return CF_OK;
+    const int sl = c->block_slot[block];
+    if (sl < 0 || c->slot_tenant[sl] != block || c->slot_state[sl] == SLOT_EMPTY)
+        return cf_fail(c, CF_ERR_STATE, "block %d: chunk %d awaited but its prefetch was not begun", block, k);
+    if (c->worker.joinable()) {
+        std::unique_lock<std::mutex> lk(c->mu);
+        c->cv.wait(lk, [&] { return c->enq_count[sl] > k; });
+        if (!c->worker_err.empty()) return cf_fail(c, CF_ERR_HIP, "prefetch worker: %s", c->worker_err.c_str());
+    }
+    ProfScope ps(c, s, K_CHUNK_WAIT, 0, 0);
+    CF_HIP(c, hipStreamWaitEvent(s, c->chunk_ev[sl][k], 0));
+    return CF_OK;
+}
+
 
 // ------------------------------------------------------------------------------------------
 // forward building blocks
@@ -1216,6 +1222,7 @@ int cf_comm_end_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute) {
         CF_HIP(c, hipEventRecord(c->comm_done_ev, comm));
         if (c->pause_resume) c->pause_flag = true;
     }
+    ProfScope ps(c, compute, K_COMM_WAIT, 0, 0);
     CF_HIP(c, hipStreamWaitEvent(compute, c->comm_done_ev, 0));
     return CF_OK;
 }
