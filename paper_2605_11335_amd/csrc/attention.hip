@@ -19,9 +19,14 @@
 
 namespace {
 
-__device__ __forceinline__ void lds_load16(const void* gptr, void* lds) {
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)gptr,
-                                     (void __attribute__((address_space(3)))*)lds, 16, 0, 0);
+// One wave-load: 64 lanes x 16 bytes from global memory straight into 1 KiB of consecutive LDS.
+// The address is base + voff (per lane) + soff (uniform, advanced per tile); lanes whose offset
+// lies past the resource's size fetch zeros, which takes care of the ragged last K tile.
+__device__ __forceinline__ void lds_bload16(__amdgpu_buffer_rsrc_t rsrc, uint32_t voff, uint32_t soff, void* lds) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void __attribute__((address_space(3)))*)lds, 16, voff, soff, 0, 0);
+}
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint64_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, (int)(bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes), 0x00020000);
 }
 
 constexpr int BKV = 64;    // keys per tile
@@ -66,33 +71,37 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
 
     // ---- tile copies go global -> LDS directly: one load writes the wave's 64 x 16 bytes to
     // consecutive LDS addresses (1 KiB = 1024/KROW key rows, or 8 V^T rows); the 16-byte chunk a
-    // lane fetches is the one whose swizzled slot it fills.
+    // lane fetches is the one whose swizzled slot it fills.  Per-lane offsets are computed once; a
+    // tile only advances the uniform offset, so the copies cost no vector instructions per tile.
+    // Key rows past nk read zeros (their scores are masked below); V^T rows are padded to nk_pad.
     const int uw = __builtin_amdgcn_readfirstlane(wave);
     constexpr int K_RPL = 1024 / KROW;          // key rows per wave-load
-    const bf16* t_src[LPW];                     // wave-load j = jj * NW + wave: K loads first, then V^T
-    int t_row[LPW];                             // key row of a K load (clamped per tile), -1 for V^T
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_rsrc(a.K + (size_t)h * a.nk * HD, (uint64_t)a.nk * KROW);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_rsrc(a.Vt + (size_t)h * HD * a.nk_pad, (uint64_t)HD * a.nk_pad * 2);
+    uint32_t t_voff[LPW];                       // wave-load j = jj * NW + wave: K loads first, then V^T
 #pragma unroll
     for (int jj = 0; jj < LPW; ++jj) {
         const int j = jj * NW + uw;
         if (j < KL) {
             const int key = j * K_RPL + lane / KCH;
-            t_row[jj] = key;
-            t_src[jj] = a.K + (size_t)h * a.nk * HD + ((lane % KCH) ^ kswz(key)) * 8;
+            t_voff[jj] = (uint32_t)key * KROW + (((lane % KCH) ^ kswz(key)) << 4);
         } else {
             const int row = min(j - KL, VL - 1) * 8 + (lane >> 3);
-            t_row[jj] = -1;
-            t_src[jj] = a.Vt + ((size_t)h * HD + row) * a.nk_pad + ((lane & 7) ^ vswz(row)) * 8;
+            t_voff[jj] = (uint32_t)row * (uint32_t)a.nk_pad * 2 + (((lane & 7) ^ vswz(row)) << 4);
         }
     }
     auto issue_tile = [&](int t, int buf) {
-        const int k0 = t * BKV;
+        const uint32_t k_soff = (uint32_t)t * (BKV * KROW), v_soff = (uint32_t)t * (BKV * 2);
 #pragma unroll
         for (int jj = 0; jj < LPW; ++jj) {
+            // with KL a multiple of NW a wave-load's role is known at compile time
+            constexpr bool kStatic = KL % NW == 0;
             const int j = jj * NW + uw;         // wave-uniform
-            if (j < KL)
-                lds_load16(t_src[jj] + (size_t)min(k0 + t_row[jj], a.nk - 1) * HD, sK + buf * K_TILE + j * 1024);
-            else if (j < KL + VL)
-                lds_load16(t_src[jj] + k0, sV + buf * V_TILE + (j - KL) * 1024);
+            const bool is_k = kStatic ? jj < KL / NW : j < KL;
+            if (is_k)
+                lds_bload16(k_rsrc, t_voff[jj], k_soff, sK + buf * K_TILE + j * 1024);
+            else if (kStatic || j < KL + VL)
+                lds_bload16(v_rsrc, t_voff[jj], v_soff, sV + buf * V_TILE + (j - KL) * 1024);
         }
     };
 
@@ -276,6 +285,7 @@ const char* attn_check(const AttnArgs& a) {
     if (a.hd != 64 && a.hd != 128) return "attention: head_dim must be 64 or 128";
     if (a.H <= 0 || a.nq <= 0 || a.nk <= 0) return "attention: empty shape";
     if (a.nk_pad % 64 || a.nk_pad < a.nk) return "attention: nk_pad must be a multiple of 64 covering nk";
+    if ((uint64_t)a.nk_pad * a.hd * 2 >= (1ull << 32)) return "attention: a head's keys exceed the 4 GiB buffer range";
     if (!a.Q || !a.K || !a.Vt || !a.O) return "attention: null operand";
     if (((uintptr_t)a.Q | (uintptr_t)a.K | (uintptr_t)a.Vt) % 16) return "attention: operands must be 16-byte aligned";
     if (((uintptr_t)a.O % 8) || (a.o_hs % 4) || (a.o_qs % 4) || (a.o_bs % 4)) return "attention: output must be 8-byte aligned";
