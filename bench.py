@@ -277,11 +277,12 @@ def main():
         overhead), per step of the profiled pass."""
         waits = {"prefetch_stall": 0.0, "collective_wait": 0.0}
         comp = 0.0
+        per_step = L / (n_steps * L + 1.0)          # the counters also hold the one block that drains the last prefetch
         for k in ktimes:
             if k["name"] in waits:
-                waits[k["name"]] += k["total_ms"] / n_steps
+                waits[k["name"]] += k["total_ms"] * per_step / L
             else:
-                comp += k["total_ms"] / n_steps
+                comp += k["total_ms"] * per_step / L
         return {"step_ms_profiled": step_ms, "compute_ms": comp, "prefetch_stall_ms": waits["prefetch_stall"],
                 "collective_wait_ms": waits["collective_wait"],
                 "other_ms": step_ms - comp - waits["prefetch_stall"] - waits["collective_wait"]}
