@@ -280,9 +280,9 @@ def main():
         per_step = L / (n_steps * L + 1.0)          # the counters also hold the one block that drains the last prefetch
         for k in ktimes:
             if k["name"] in waits:
-                waits[k["name"]] += k["total_ms"] * per_step / L
+                waits[k["name"]] += k["total_ms"] * per_step
             else:
-                comp += k["total_ms"] * per_step / L
+                comp += k["total_ms"] * per_step
         return {"step_ms_profiled": step_ms, "compute_ms": comp, "prefetch_stall_ms": waits["prefetch_stall"],
                 "collective_wait_ms": waits["collective_wait"],
                 "other_ms": step_ms - comp - waits["prefetch_stall"] - waits["collective_wait"]}
