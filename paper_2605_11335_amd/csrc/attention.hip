@@ -14,6 +14,8 @@
 // B-operand layout of the second contraction (8 consecutive k per lane), so P^T is a pure
 // register repack.  V is kept transposed in HBM ([head, d, key]) so that its A-operand rows
 // are contiguous 16-byte reads as well.
+#include <type_traits>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -120,8 +122,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
     issue_tile(0, 0);
     __syncthreads();                            // (waits for the LDS-DMA, then the barrier)
 
-    for (int t = 0; t < NT; ++t) {
-        const int buf = t & 1;
+    // one tile; the LDS buffer is a compile-time constant so that fragment addresses are a per-lane
+    // register plus an immediate (the loop below takes tiles in pairs)
+    auto tile = [&](int t, auto buf_c) __attribute__((always_inline)) {
+        constexpr int buf = decltype(buf_c)::value;
         if (t + 1 < NT) issue_tile(t + 1, buf ^ 1);
         const char* cK = sK + buf * K_TILE;
         const char* cV = sV + buf * V_TILE;
@@ -232,6 +236,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
         }
 
         __syncthreads();                        // tile t+1 has landed, tile t may be overwritten
+    };
+    for (int t = 0; t < NT; t += 2) {
+        tile(t, std::integral_constant<int, 0>{});
+        if (t + 1 < NT) tile(t + 1, std::integral_constant<int, 1>{});
     }
 
     // ---- normalise and store: lane = query, register quad = 4 consecutive d
