@@ -508,6 +508,44 @@ int run_linear(Fwd& F, int kid, const std::string& wname, const std::string& bna
     });
 }
 
+// Two independent linear layers (the two streams of a double-stream block; the query and the context
+// projections of a cross-attention).  When neither needs a chunk that has not been waited for yet they
+// go out as one launch, so that the small one's few workgroups ride along with the large one's instead
+// of holding the chip for the length of their K loop; otherwise (weights still streaming) each takes
+// its own panel launches as usual.
+int run_linear_pair(Fwd& F, int kid, const std::string (&wname)[2], const std::string (&bname)[2], const GemmArgs (&g_in)[2]) {
+    cf_ctx* c = F.c;
+    const int have = std::max(c->waited_upto, c->P(F.block).n_res_chunks - 1);
+    bool pair = g_in[0].M > 0 && g_in[1].M > 0;
+    GemmArgs g[2];
+    for (int i = 0; i < 2 && pair; ++i) {
+        const TensorDesc &w = T(F, wname[i]), &b = T(F, bname[i]);
+        const int last = (int)((std::max(w.off + w.bytes(), b.off + b.bytes()) - 1) / c->chunk_bytes);
+        if (last > have) pair = false;
+        g[i] = g_in[i];
+        g[i].W = F.W;
+        g[i].act_erf = c->d.gelu_erf;
+        g[i].w_off = w.off;
+        g[i].bias_off = b.off;
+        g[i].has_bias = 1;
+        g[i].N = (int)w.rows;
+        g[i].K = (int)w.cols;
+        g[i].n0 = 0;
+        g[i].n1 = g[i].N;
+        if (g[i].epi == EPI_SPLIT_GELU && g[i].n_split > g[i].N) g[i].n_split = g[i].N;
+    }
+    const int tile = pair ? gemm_pair_tile(g[0], g[1]) : -1;
+    if (tile < 0) {
+        CF_TRY(run_linear(F, kid, wname[0], bname[0], g_in[0]));
+        return run_linear(F, kid, wname[1], bname[1], g_in[1]);
+    }
+    for (int i = 0; i < 2; ++i)
+        if (const char* msg = gemm_check(g[i])) return cf_fail(c, CF_ERR_ARG, "%s (%s)", msg, wname[i].c_str());
+    ProfScope ps(c, F.s, kid, 2.0 * g[0].M * g[0].N * g[0].K + 2.0 * g[1].M * g[1].N * g[1].K, 0, tile);
+    CF_HIP(c, gemm_launch_pair(g[0], g[1], F.s));
+    return CF_OK;
+}
+
 TokenMap token_map(const cf_model_desc& m) {
     TokenMap t;
     t.n_total = m.n_total;
@@ -1276,8 +1314,12 @@ int fwd_dit(Fwd& F) {
         CF_HIP(c, ln_affine_launch(w.x1, F.W, T(F, "ln_c_w").off, T(F, "ln_c_b").off, w.xn, rows, d, F.s));
     }
     if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, "cq_norm"))); CF_TRY(need(F, T(F, "ck_norm"))); }
-    CF_TRY(run_linear(F, K_CROSS_Q, "w_cq", "b_cq", plain_linear(w.xn, d, rows, w.qkv, d)));
-    CF_TRY(run_linear(F, K_CROSS_KV, "w_ckv", "b_ckv", plain_linear((const bf16*)io->ctx, d, B * lc, w.ckv, 2 * d)));
+    {
+        // the query projection of the local tokens and the K/V projection of the context are independent
+        const std::string wn[2] = {"w_cq", "w_ckv"}, bn[2] = {"b_cq", "b_ckv"};
+        const GemmArgs g[2] = {plain_linear(w.xn, d, rows, w.qkv, d), plain_linear((const bf16*)io->ctx, d, B * lc, w.ckv, 2 * d)};
+        CF_TRY(run_linear_pair(F, K_CROSS_Q, wn, bn, g));
+    }
     const int lpad = n_pad_of(lc);
     for (int b = 0; b < B; ++b) {
         RelayoutArgs rq{};
@@ -1332,26 +1374,44 @@ int fwd_double(Fwd& F) {
     for (int s = 0; s < 2; ++s)
         CF_TRY(run_ln_mod(F, xin[s], mod(s, 0), mod(s, 1), w.xn + (size_t)row0[s] * d, rows[s], rps[s], xs[s], mod_bs));
     RelayoutArgs parts[2];
+    auto names = [&](const char* t, std::string (&out)[2]) { out[0] = nm(st[0], t); out[1] = nm(st[1], t); };
+    std::string wn[2], bn[2];
+    {
+        const GemmArgs g[2] = {plain_linear(w.xn + (size_t)row0[0] * d, d, rows[0], w.qkv + (size_t)row0[0] * 3 * d, 3 * d),
+                               plain_linear(w.xn + (size_t)row0[1] * d, d, rows[1], w.qkv + (size_t)row0[1] * 3 * d, 3 * d)};
+        names("w_qkv", wn); names("b_qkv", bn);
+        CF_TRY(run_linear_pair(F, K_QKV, wn, bn, g));
+    }
     for (int s = 0; s < 2; ++s) {
         if (m.qk_rmsnorm) { CF_TRY(need(F, T(F, nm(st[s], "q_norm")))); CF_TRY(need(F, T(F, nm(st[s], "k_norm")))); }
-        CF_TRY(run_linear(F, K_QKV, nm(st[s], "w_qkv"), nm(st[s], "b_qkv"),
-                          plain_linear(w.xn + (size_t)row0[s] * d, d, rows[s], w.qkv + (size_t)row0[s] * 3 * d, 3 * d)));
         parts[s] = relayout_for(F, w.qkv + (size_t)row0[s] * 3 * d, per[s], s ? tl : 0, nm(st[s], "q_norm"), nm(st[s], "k_norm"));
     }
     // one sample: its image rows follow its text rows in w.c; a batch: the streams' regions are apart
     CF_TRY(run_joint_attention(F, parts, 2, B > 1 ? AttnOut{w.c, w.c + (size_t)row0[1] * d, d, dense[0], dense[1]}
                                                   : AttnOut{w.c, nullptr, d, (long)nl * d, 0}));
+    {
+        GemmArgs g[2];
+        for (int s = 0; s < 2; ++s)
+            g[s] = batched(resid_linear(w.c + (size_t)row0[s] * d, d, rows[s], xin[s], mod(s, 2), w.x1 + (size_t)row0[s] * d, d),
+                           B, per[s], mod_bs, xs[s], dense[s]);
+        names("w_o", wn); names("b_o", bn);
+        CF_TRY(run_linear_pair(F, K_OUT, wn, bn, g));
+    }
     for (int s = 0; s < 2; ++s)
-        CF_TRY(run_linear(F, K_OUT, nm(st[s], "w_o"), nm(st[s], "b_o"),
-                          batched(resid_linear(w.c + (size_t)row0[s] * d, d, rows[s], xin[s], mod(s, 2), w.x1 + (size_t)row0[s] * d, d),
-                                  B, per[s], mod_bs, xs[s], dense[s])));
-    for (int s = 0; s < 2; ++s) {
         CF_TRY(run_ln_mod(F, w.x1 + (size_t)row0[s] * d, mod(s, 3), mod(s, 4), w.xn + (size_t)row0[s] * d, rows[s], rps[s], dense[s], mod_bs));
-        CF_TRY(run_linear(F, K_UP, nm(st[s], "w_up"), nm(st[s], "b_up"),
-                          gelu_linear(w.xn + (size_t)row0[s] * d, d, rows[s], w.up + (size_t)row0[s] * f, f)));
-        CF_TRY(run_linear(F, K_DOWN, nm(st[s], "w_down"), nm(st[s], "b_down"),
-                          batched(resid_linear(w.up + (size_t)row0[s] * f, f, rows[s], w.x1 + (size_t)row0[s] * d, mod(s, 5), yout[s], d),
-                                  B, per[s], mod_bs, dense[s], xs[s])));
+    {
+        GemmArgs g[2];
+        for (int s = 0; s < 2; ++s) g[s] = gelu_linear(w.xn + (size_t)row0[s] * d, d, rows[s], w.up + (size_t)row0[s] * f, f);
+        names("w_up", wn); names("b_up", bn);
+        CF_TRY(run_linear_pair(F, K_UP, wn, bn, g));
+    }
+    {
+        GemmArgs g[2];
+        for (int s = 0; s < 2; ++s)
+            g[s] = batched(resid_linear(w.up + (size_t)row0[s] * f, f, rows[s], w.x1 + (size_t)row0[s] * d, mod(s, 5), yout[s], d),
+                           B, per[s], mod_bs, dense[s], xs[s]);
+        names("w_down", wn); names("b_down", bn);
+        CF_TRY(run_linear_pair(F, K_DOWN, wn, bn, g));
     }
     return CF_OK;
 }

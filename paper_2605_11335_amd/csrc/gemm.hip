@@ -56,8 +56,9 @@ __device__ __forceinline__ void slab_handover() {
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// One workgroup's tile of one problem: workgroup `bid` of the `nblk` that problem owns.
 template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+__device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, uint32_t bid, uint32_t nblk) {
     constexpr int WM = BM / 2, WN = BN / 2;        // wave quadrant
     constexpr int MT = WM / 32, NT = WN / 32;      // 32x32 MFMA tiles per wave
     constexpr int A_LOADS = BM * CHUNKS / 256;     // 16-byte global loads per thread per slab
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
     // logical tile: XCD-contiguous id, then groups of GM row-tiles walked feature-tile-major
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.n1 - g.n0 + BN - 1) / BN;
-    const uint32_t lid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const uint32_t lid = xcd_contiguous_id(bid, nblk);
     constexpr int GM = 8;
     const int group = lid / (GM * tiles_n);
     const int first_m = group * GM;
@@ -312,12 +313,36 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
 }
 
 template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmArgs g) {
+    gemm_tile_body<BM, BN, EPI>(g, blockIdx.x, gridDim.x);
+}
+
+// Two independent problems of one tile shape and epilogue in one launch (the text and image streams
+// of a double-stream block, App. B): a small problem's workgroups ride along with the large one's
+// instead of holding the chip for the length of their K loop.  The first problem's share of the grid
+// is padded to a multiple of 8 so that both keep the block-index-to-XCD correspondence.
+struct GemmPair {
+    GemmArgs g[2];
+    uint32_t tiles0, tiles0_pad;
+};
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void gemm_pair_kernel(GemmPair p) {
+    if (blockIdx.x < p.tiles0) gemm_tile_body<BM, BN, EPI>(p.g[0], blockIdx.x, p.tiles0);
+    else if (blockIdx.x >= p.tiles0_pad) gemm_tile_body<BM, BN, EPI>(p.g[1], blockIdx.x - p.tiles0_pad, gridDim.x - p.tiles0_pad);
+}
+
+template <int BM, int BN, int EPI>
+size_t gemm_smem() {
+    const size_t stage_bytes = (size_t)STAGES * (BM + BN) * ROWB;
+    const size_t epi_bytes = 4ull * (BM / 2) * (BN + (EPI != EPI_GATE_RESID ? 16 : 32));   // 4 x WM x PITCH
+    return stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+}
+
+template <int BM, int BN, int EPI>
 hipError_t launch(const GemmArgs& g, hipStream_t s) {
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.n1 - g.n0 + BN - 1) / BN;
-    const size_t stage_bytes = (size_t)STAGES * (BM + BN) * ROWB;
-    const size_t epi_bytes = 4ull * (BM / 2) * (BN + (EPI != EPI_GATE_RESID ? 16 : 32));   // 4 x WM x PITCH
-    const size_t smem = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
+    const size_t smem = gemm_smem<BM, BN, EPI>();
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_kernel<BM, BN, EPI>,
@@ -326,6 +351,26 @@ hipError_t launch(const GemmArgs& g, hipStream_t s) {
         attr_set = true;
     }
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, EPI>), dim3(tiles_m * tiles_n), dim3(256), smem, s, g);
+    return hipGetLastError();
+}
+
+template <int BM, int BN, int EPI>
+hipError_t launch_pair(const GemmArgs& g0, const GemmArgs& g1, hipStream_t s) {
+    auto tiles = [](const GemmArgs& g) { return (uint32_t)(((g.M + BM - 1) / BM) * ((g.n1 - g.n0 + BN - 1) / BN)); };
+    GemmPair p;
+    p.g[0] = g0;
+    p.g[1] = g1;
+    p.tiles0 = tiles(g0);
+    p.tiles0_pad = (p.tiles0 + 7u) & ~7u;
+    const size_t smem = gemm_smem<BM, BN, EPI>();
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_pair_kernel<BM, BN, EPI>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_pair_kernel<BM, BN, EPI>), dim3(p.tiles0_pad + tiles(g1)), dim3(256), smem, s, p);
     return hipGetLastError();
 }
 
@@ -397,4 +442,22 @@ hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
         return t == 0 ? launch<256, 256, EPI_SPLIT_GELU_ERF>(g, s) : launch<128, 128, EPI_SPLIT_GELU_ERF>(g, s);
     if (g.epi == EPI_SPLIT_GELU) return t == 0 ? launch<256, 256, EPI_SPLIT_GELU>(g, s) : launch<128, 128, EPI_SPLIT_GELU>(g, s);
     return t == 0 ? launch<256, 256, EPI_GATE_RESID>(g, s) : launch<128, 128, EPI_GATE_RESID>(g, s);
+}
+
+// Tile shape both problems of a pair run with, or -1 if they cannot share a launch (different
+// epilogues).  Shapes that would pick different tiles alone take the larger problem's choice.
+int gemm_pair_tile(const GemmArgs& g0, const GemmArgs& g1) {
+    if (g0.epi != g1.epi || g0.act_erf != g1.act_erf) return -1;
+    const GemmArgs& big = (double)g0.M * (g0.n1 - g0.n0) >= (double)g1.M * (g1.n1 - g1.n0) ? g0 : g1;
+    return gemm_tile(big);
+}
+
+hipError_t gemm_launch_pair(const GemmArgs& g0, const GemmArgs& g1, hipStream_t s) {
+    const int t = gemm_pair_tile(g0, g1);
+    if (t < 0) return hipErrorInvalidValue;
+    if (g0.epi == EPI_SPLIT_GELU && g0.act_erf)
+        return t == 0 ? launch_pair<256, 256, EPI_SPLIT_GELU_ERF>(g0, g1, s) : launch_pair<128, 128, EPI_SPLIT_GELU_ERF>(g0, g1, s);
+    if (g0.epi == EPI_SPLIT_GELU)
+        return t == 0 ? launch_pair<256, 256, EPI_SPLIT_GELU>(g0, g1, s) : launch_pair<128, 128, EPI_SPLIT_GELU>(g0, g1, s);
+    return t == 0 ? launch_pair<256, 256, EPI_GATE_RESID>(g0, g1, s) : launch_pair<128, 128, EPI_GATE_RESID>(g0, g1, s);
 }

@@ -31,6 +31,9 @@ const char* gemm_check(const GemmArgs& g);
 int gemm_tile(const GemmArgs& g);      // tile gemm_launch will use: 0 = 256x256, 1 = 128x128
 double gemm_fill(int M, int n);        // share of the launched rounds of workgroups that n features x M tokens fill
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s);
+// two independent problems in one launch; gemm_pair_tile: the tile shape they share (as gemm_tile), -1 = cannot pair
+int gemm_pair_tile(const GemmArgs& g0, const GemmArgs& g1);
+hipError_t gemm_launch_pair(const GemmArgs& g0, const GemmArgs& g1, hipStream_t s);
 
 // Positions of this rank's tokens in the joint sequence: up to two contiguous segments
 // (text rows, image rows).  Local row i < len0 sits at pos0 + i, else at pos1 + (i - len0).
