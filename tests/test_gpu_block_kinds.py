@@ -77,6 +77,37 @@ def test_double_stream_block_small(P, rank):
     run_case(cfg, r=0.3)
 
 
+def _block_outputs(cfg, r):
+    params, inputs = wl.gen_block_params(cfg, 0), wl.gen_block_inputs(cfg, 0)
+    run = BlockRunner(cfg, n_blocks=1)
+    try:
+        run.ctx.set_resident_fraction(r)
+        run.register_params(0, params)
+        t = run.make_io(inputs)
+        run.run_block(0, t)
+        return {k: v.cpu().numpy().copy() for k, v in t.items() if k in ("y", "y_txt", "send_q", "send_k", "send_v", "send_attn")}
+    finally:
+        run.close()
+
+
+@pytest.mark.parametrize("kind", [wl.KIND_DIT, wl.KIND_DOUBLE])
+def test_paired_launches_change_no_bit(kind):
+    """With every chunk resident the two streams' layers of a double-stream block, and the query /
+    context projections of the cross-attention, go out as one launch per pair; while the weights stream
+    every layer has its own panel launches.  Same tiles, same k order: the outputs are identical, and
+    the resident (paired) arm matches the oracle like the streamed one."""
+    if kind == wl.KIND_DIT:
+        cfg = wl.BlockConfig("mini_dit", wl.KIND_DIT, n_blocks=1, d=512, n_heads=4, head_dim=128, f=1024,
+                             n_total=588, sp_degree=2, sp_rank=1, l_ctx=77, qk_rmsnorm=True, n_chunks=6)
+    else:
+        cfg = wl.BlockConfig("mini_double", wl.KIND_DOUBLE, n_blocks=1, d=512, n_heads=8, head_dim=64, f=1024,
+                             n_total=660, sp_degree=2, sp_rank=0, n_txt=60, qk_rmsnorm=True, n_chunks=9)
+    run_case(cfg, r=1.0)
+    paired, streamed = _block_outputs(cfg, 1.0), _block_outputs(cfg, 0.0)
+    for k in paired:
+        assert np.array_equal(paired[k].view(np.uint8), streamed[k].view(np.uint8)), k
+
+
 def test_wan_share_full_size_row_sample():
     """C3: 27280 video tokens, cross-attention to 512 text tokens, P=2 share."""
     run_case(wl.CONFIGS["wan"].with_(n_blocks=1), n_rows=192)
