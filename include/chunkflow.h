@@ -258,7 +258,10 @@ int cf_read_block(cf_ctx* ctx, int32_t block, void* host_out, void* stream);
 
 int cf_stats(cf_ctx* ctx, cf_stats_t* out);
 int cf_stats_reset(cf_ctx* ctx);
-int cf_set_profiling(cf_ctx* ctx, int32_t on);                 /* hipEvent pair around every kernel */
+/* Profiling puts a hipEvent pair around every kernel launch and around every wait of the compute
+ * stream on a chunk event ("prefetch_stall": the exposed prefetch of Sec. 4.3's breakdown) or on a
+ * collective's completion ("collective_wait"); cf_kernel_times returns one record per name. */
+int cf_set_profiling(cf_ctx* ctx, int32_t on);
 int cf_kernel_times(cf_ctx* ctx, cf_kernel_time* out, int32_t* n);   /* syncs; *n capacity/count */
 int cf_kernel_times_reset(cf_ctx* ctx);
 int cf_sync(cf_ctx* ctx);                                      /* hipDeviceSynchronize */
