@@ -121,6 +121,7 @@ typedef struct {
     uint64_t pauses;             /* chunk launches that were made to wait for a collective        */
     uint64_t model_resident_bytes;/* resident bytes summed over all blocks                          */
     uint64_t model_blob_bytes;   /* blob bytes summed over all blocks                              */
+    uint64_t blocks_one_wait;    /* block forwards that waited once for all their chunks (see below) */
 } cf_stats_t;
 
 /* Per-kernel timing collected while profiling is on (cf_set_profiling). */
@@ -256,6 +257,13 @@ int cf_checksum_block(cf_ctx* ctx, int32_t block, uint64_t* host_out, void* stre
 /* copy the device image of `block` back to host_out[blob_bytes] (for byte-exact comparison) */
 int cf_read_block(cf_ctx* ctx, int32_t block, void* host_out, void* stream);
 
+/* Per-chunk consumer waits pay off while the link is the bottleneck; once a block kind's prefetch is
+ * hidden (Sec. 3.1: its weights had landed before the block started, observed on the previous block of
+ * that kind) a wait per chunk only costs stream bubbles and splits the layers into panels for nothing.
+ * With adaptive waits on (the default) such a block waits once, for its last chunk, as the plain
+ * layerwise loop of Sec. 2.2 does, and goes back to per-chunk waits as soon as a prefetch is seen to
+ * land late.  Results do not depend on the mode.  Not used together with the pause/resume worker. */
+int cf_set_adaptive_waits(cf_ctx* ctx, int32_t on);
 int cf_stats(cf_ctx* ctx, cf_stats_t* out);
 int cf_stats_reset(cf_ctx* ctx);
 /* Profiling puts a hipEvent pair around every kernel launch and around every wait of the compute

@@ -44,7 +44,8 @@ class cf_stats_t(C.Structure):
     _fields_ = [("h2d_bytes", C.c_uint64), ("h2d_chunks", C.c_uint64), ("resident_bytes", C.c_uint64),
                 ("blob_bytes", C.c_uint64), ("weight_memory_bytes", C.c_uint64),
                 ("comm_bytes_h2d", C.c_uint64), ("comm_bytes_d2h", C.c_uint64), ("pauses", C.c_uint64),
-                ("model_resident_bytes", C.c_uint64), ("model_blob_bytes", C.c_uint64)]
+                ("model_resident_bytes", C.c_uint64), ("model_blob_bytes", C.c_uint64),
+                ("blocks_one_wait", C.c_uint64)]
 
 
 class cf_kernel_time(C.Structure):
@@ -71,7 +72,7 @@ EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_ch
            "cf_set_block_kinds", "cf_block_kind_of", "cf_blob_bytes_of", "cf_n_chunks_of", "cf_blob_layout_of",
            "cf_workspace_bytes", "cf_plan_panels", "cf_simulate", "cf_tune", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
            "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
-           "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling",
+           "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling", "cf_set_adaptive_waits",
            "cf_kernel_times", "cf_kernel_times_reset", "cf_sync", "cf_op_linear", "cf_op_linear_residual",
            "cf_op_attention", "cf_op_ln_modulate", "cf_op_modvec", "cf_op_checksum"]
 
@@ -102,6 +103,7 @@ def lib() -> C.CDLL:
                 fn.restype = C.c_int
         _lib.set_resident_fraction.argtypes = [C.c_void_p, C.c_double, C.POINTER(C.c_double)]
         _lib.cf_set_contention.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64, C.c_int32]
+        _lib.cf_set_adaptive_waits.argtypes = [C.c_void_p, C.c_int32]
         _lib.cf_plan_panels.argtypes = [C.c_void_p, C.c_char_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(C.c_int32)]
         _lib.cf_register_block.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64]
@@ -308,6 +310,9 @@ class Context:
 
     def cf_set_profiling(self, on: bool) -> None:
         _check(lib().cf_set_profiling(self._h, int(on)), self._h)
+
+    def cf_set_adaptive_waits(self, on: bool) -> None:
+        _check(lib().cf_set_adaptive_waits(self._h, int(on)), self._h)
 
     def cf_kernel_times(self) -> List[dict]:
         n = C.c_int32(64)

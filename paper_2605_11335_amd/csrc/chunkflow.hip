@@ -166,7 +166,8 @@ int ensure_device(cf_ctx* c) {
     for (int s = 0; s < 2; ++s) {
         c->chunk_ev[s].resize(c->max_chunks);
         for (auto& e : c->chunk_ev[s]) CF_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        CF_HIP(c, hipEventCreateWithFlags(&c->done_ev[s], hipEventDisableTiming));
+        CF_HIP(c, hipEventCreate(&c->done_ev[s]));          // with timestamps: compared with land_ev
+        CF_HIP(c, hipEventCreate(&c->land_ev[s]));
     }
     CF_HIP(c, hipEventCreateWithFlags(&c->comm_ready_ev, hipEventDisableTiming));
     CF_HIP(c, hipEventCreateWithFlags(&c->comm_done_ev, hipEventDisableTiming));
@@ -182,6 +183,7 @@ void free_weights(cf_ctx* c) {
         c->slot_tenant[s] = -1;
         c->slot_state[s] = SLOT_EMPTY;
         c->done_valid[s] = false;
+        c->land_valid[s] = false;
         c->enq_count[s] = 0;
     }
     c->next_slot = 0;
@@ -242,6 +244,8 @@ int enqueue_block_copies(cf_ctx* c, int block, int s, hipStream_t copy, bool bou
         }
         c->cv.notify_all();
     }
+    CF_HIP(c, hipEventRecord(c->land_ev[s], copy));
+    c->land_valid[s] = true;
     return CF_OK;
 }
 
@@ -787,6 +791,7 @@ int cf_destroy(cf_ctx* c) {
         for (int s = 0; s < 2; ++s) {
             for (auto e : c->chunk_ev[s]) (void)hipEventDestroy(e);
             (void)hipEventDestroy(c->done_ev[s]);
+            (void)hipEventDestroy(c->land_ev[s]);
         }
         (void)hipEventDestroy(c->comm_ready_ev);
         (void)hipEventDestroy(c->comm_done_ev);
@@ -946,6 +951,18 @@ int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
     // block of queued work, so it never starves, and the runtime's queues never fill up -- a host
     // that is blocked inside the runtime mid-step would leave the copy stream idle.
     if (c->done_valid[s ^ 1]) CF_HIP(c, hipEventSynchronize(c->done_ev[s ^ 1]));
+    // The block that just finished (other slot) ran right before this slot's last tenant.  Had that tenant's
+    // weights landed by then, its prefetch was hidden (Sec. 3.1) and blocks of its kind need one wait, not one
+    // per chunk.  Evaluated before the slot's events are recorded anew.
+    if (c->adaptive_waits && !c->pause_resume && c->slot_tenant[s] >= 0 && c->land_valid[s] && c->done_valid[s ^ 1] &&
+        c->slot_state[s] == SLOT_CONSUMED && c->slot_fwd_seq[s ^ 1] + 1 == c->slot_fwd_seq[s]) {
+        bool hidden = false;
+        float ms = 0.f;
+        if (hipEventQuery(c->land_ev[s]) == hipSuccess && hipEventElapsedTime(&ms, c->land_ev[s], c->done_ev[s ^ 1]) == hipSuccess)
+            hidden = ms > 0.05f;
+        (void)hipGetLastError();
+        c->hidden_kind[c->block_kind[c->slot_tenant[s]]] = hidden;
+    }
     c->next_slot ^= 1;
     if (c->slot_tenant[s] >= 0 && c->block_slot[c->slot_tenant[s]] == s) c->block_slot[c->slot_tenant[s]] = -1;
     c->slot_tenant[s] = block;
@@ -1004,6 +1021,13 @@ int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute
 
     Fwd F{c, block, (hipStream_t)compute_stream, view_of(c, block), io, carve(c->d, p.kind, (char*)io->workspace)};
     c->waited_upto = p.n_res_chunks - 1;
+    if (streamed && c->adaptive_waits && !c->pause_resume && c->hidden_kind[p.kind]) {
+        // blocks of this kind have been finding their weights in place: wait once, for the last chunk, and
+        // launch every layer whole (Sec. 2.2's plain wait-then-forward)
+        CF_TRY(wait_chunk(c, block, p.n_chunks - 1, (hipStream_t)compute_stream));
+        c->waited_upto = p.n_chunks - 1;
+        c->stats.blocks_one_wait++;
+    }
     int rc;
     switch (p.kind) {
         case CF_SINGLE_STREAM: rc = fwd_single(F); break;
@@ -1014,6 +1038,7 @@ int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute
     if (streamed) {
         CF_TRY(chunked_prefetch_wait(c, block, -1, compute_stream));   // no-op unless a tail chunk fed nothing
         CF_HIP(c, hipEventRecord(c->done_ev[s], (hipStream_t)compute_stream));
+        c->slot_fwd_seq[s] = ++c->fwd_seq;
         c->done_valid[s] = true;
         c->slot_state[s] = SLOT_CONSUMED;
     }
@@ -1130,6 +1155,13 @@ int cf_stats_reset(cf_ctx* c) {
     if (!c) return CF_ERR_ARG;
     std::lock_guard<std::mutex> lk(c->mu);
     c->stats = cf_stats_t{};
+    return CF_OK;
+}
+
+int cf_set_adaptive_waits(cf_ctx* c, int32_t on) {
+    if (!c) return CF_ERR_ARG;
+    c->adaptive_waits = on != 0;
+    for (bool& h : c->hidden_kind) h = false;
     return CF_OK;
 }
 

@@ -73,6 +73,14 @@ struct cf_ctx {
     hipEvent_t done_ev[2] = {nullptr, nullptr};
     bool done_valid[2] = {false, false};
     int waited_upto = -1;               // highest chunk the current forward already waited for
+    // One wait per block when the prefetch is hidden anyway: land_ev[s] follows the last chunk copy into
+    // slot s; comparing it with the end of the block that ran before the slot's tenant tells whether that
+    // tenant's weights had landed before it started (Sec. 3.1: T_pref <= T_comp), per block kind.
+    hipEvent_t land_ev[2] = {nullptr, nullptr};
+    bool land_valid[2] = {false, false};
+    uint64_t fwd_seq = 0, slot_fwd_seq[2] = {0, 0};   // order of the forwards that recorded done_ev[s]
+    bool adaptive_waits = true;
+    bool hidden_kind[3] = {false, false, false};
 
     // emulated collectives + pause/resume (Sec. 3.2)
     hipStream_t comm_stream = nullptr;

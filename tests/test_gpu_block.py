@@ -281,3 +281,44 @@ def test_single_block_model_and_odd_block_counts():
                 assert rel_l2(y, ref) <= REL_L2_TOL and max_abs(y, ref) <= MAX_ABS_TOL
         finally:
             run.close()
+
+
+def _steps_with_stats(cfg, adaptive, n_steps=4):
+    run = BlockRunner(cfg, n_blocks=cfg.n_blocks)
+    try:
+        run.ctx.cf_set_adaptive_waits(adaptive)
+        run.ctx.set_resident_fraction(0.0)
+        ios = []
+        for blk in range(cfg.n_blocks):
+            run.register_params(blk, wl.gen_block_params(cfg.with_(n_total=512), blk))     # weights do not depend on N
+            gen = torch.Generator(device="cpu").manual_seed(1000 + blk)
+            x = torch.randn((cfg.n_local, cfg.d), generator=gen).to(torch.bfloat16).float().to(run.device)
+            temb = torch.randn((cfg.d,), generator=gen).to(torch.bfloat16).float().to(run.device)
+            ios.append({"x": x, "temb": temb, "y": torch.empty_like(x)})
+        structs = [run.io_struct(t) for t in ios]
+        run.ctx.cf_stats_reset()
+        run.begin(0)
+        for _ in range(n_steps):
+            run.step(structs)
+        run.fwd(0, structs[0])
+        run.ctx.cf_sync()
+        return [t["y"].clone() for t in ios], run.ctx.cf_stats()
+    finally:
+        run.close()
+
+
+def test_one_wait_per_block_once_the_prefetch_is_hidden():
+    """A toy-width block over 16384 tokens computes for about a millisecond while its 7.9 MB of weights
+    take a third of that to arrive: after the first blocks have shown that their weights were in place
+    before they started, a block waits once instead of once per chunk; results are the same bit for bit,
+    and the link-bound toy configuration never leaves the per-chunk mode."""
+    big = wl.CONFIGS["toy"].with_(n_total=16384, n_blocks=3)
+    y_adaptive, st_a = _steps_with_stats(big, True)
+    y_per_chunk, st_p = _steps_with_stats(big, False)
+    assert st_p["blocks_one_wait"] == 0
+    assert st_a["blocks_one_wait"] >= 6, st_a            # 13 forwards, the first few still observe
+    assert st_a["h2d_bytes"] == st_p["h2d_bytes"]
+    for a, b in zip(y_adaptive, y_per_chunk):
+        assert torch.equal(a, b)
+    _, st_small = _steps_with_stats(wl.CONFIGS["toy"].with_(n_blocks=3), True)
+    assert st_small["blocks_one_wait"] == 0, st_small
