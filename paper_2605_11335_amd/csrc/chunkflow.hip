@@ -924,6 +924,7 @@ int set_resident_fraction(cf_ctx* c, double r, double* actual) {
     CF_HIP(c, hipDeviceSynchronize());
     free_weights(c);
     for (int k = 0; k < 3; ++k) { c->plan[k].n_res_chunks = n_res[k]; c->plan[k].res_bytes = res_bytes[k]; }
+    for (bool& h : c->hidden_kind) h = false;                 // what was observed belonged to the old split
     if (slot_bytes) {
         for (int s = 0; s < 2; ++s)
             if (hipMalloc((void**)&c->slot[s], slot_bytes) != hipSuccess) {
