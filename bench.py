@@ -345,6 +345,8 @@ def main():
         "eta_comp_measured": (total_flops / (res_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS) if do_res else None,
         "h2d_gbs": h2d_gbs, "h2d_frac_link_peak": h2d_gbs / PEAK_LINK_GBS,
         "h2d_bytes_per_step": h2d_per_step,
+        # block forwards of the offloaded arm that waited once for all their chunks (prefetch observed hidden)
+        "blocks_one_wait": st["blocks_one_wait"] if st else None,
         "exposed_prefetch_ms": (off_ms - res_ms) if (do_res and do_off) else None,
         "weight_memory_bytes": st["weight_memory_bytes"] if st else blob_total,
         "roofline": {"bound": "mfma", "kernel": dom["name"], "arm": arm_name,
