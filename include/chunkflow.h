@@ -295,6 +295,13 @@ int cf_op_ln_modulate(const float* x, const float* shift, const float* scale, ui
 /* m = W t + b over a blob holding W [n,K] and b [n]. */
 int cf_op_modvec(const void* blob, uint64_t w_off, uint64_t b_off, const float* t, float* m,
                  int32_t n, int32_t K, void* stream);
+/* Diagnostic, not part of the block path: 256 workgroups of 4 waves issue `iters` x 16 bf16 MFMAs
+ * (32x32x16) each on registers alone; a launch is 256 * 4 * iters * 16 * 32768 FLOPs.  Timed by the
+ * caller, it gives the matrix-core rate the chip sustains under load (Sec. 3.1's eta_c * P_peak has
+ * this as its ceiling, not the published peak).  The clock the chip settles to depends on the data:
+ * random_operands = 0 repeats one pair of small-valued fragments, 1 cycles through sixteen pairs of
+ * unit-variance pseudo-random fragments.  `out`: 65536 floats of device memory. */
+int cf_op_mfma_rate(int32_t iters, int32_t random_operands, float* out, void* stream);
 /* checksum of a device byte range (definition above); host_out[1]; blocks the host. */
 int cf_op_checksum(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* host_out, void* stream);
 

@@ -74,7 +74,7 @@ EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_ch
            "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
            "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling", "cf_set_adaptive_waits",
            "cf_kernel_times", "cf_kernel_times_reset", "cf_sync", "cf_op_linear", "cf_op_linear_residual",
-           "cf_op_attention", "cf_op_ln_modulate", "cf_op_modvec", "cf_op_checksum"]
+           "cf_op_attention", "cf_op_ln_modulate", "cf_op_modvec", "cf_op_mfma_rate", "cf_op_checksum"]
 
 _lib = None
 
@@ -131,6 +131,7 @@ def lib() -> C.CDLL:
                                          C.c_int32, C.c_int32, C.c_int32, C.c_void_p]
         _lib.cf_op_ln_modulate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib.cf_op_modvec.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        _lib.cf_op_mfma_rate.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         _lib.cf_op_checksum.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p]
     return _lib
 
@@ -352,6 +353,10 @@ def cf_op_linear(A, blob, w_off, bias_off, M, N, K, out0, out1=None, n_split=Non
     _check(lib().cf_op_linear(_ptr(A), K if lda is None else lda, _ptr(blob), w_off, bias_off, M, N, K, n0, n1, n_split,
                               _ptr(out0), (n_split if ld0 is None else ld0), _ptr(out1),
                               ((N - n_split) if ld1 is None else ld1), int(gelu_erf), _stream_handle(stream)))
+
+
+def cf_op_mfma_rate(iters: int, random_operands: bool, out, stream=None) -> None:
+    _check(lib().cf_op_mfma_rate(iters, int(random_operands), _ptr(out), _stream_handle(stream)))
 
 
 def cf_op_linear_residual(A, blob, w_off, bias_off, M, N, K, resid, gate, y, lda=None, stream=None):

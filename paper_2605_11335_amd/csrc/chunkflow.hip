@@ -1260,6 +1260,12 @@ int cf_op_modvec(const void* blob, uint64_t w_off, uint64_t b_off, const float* 
     return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "modvec: %s", hipGetErrorString(e));
 }
 
+int cf_op_mfma_rate(int32_t iters, int32_t random_operands, float* out, void* stream) {
+    if (iters <= 0 || iters > (1 << 24) || !out) return cf_fail(nullptr, CF_ERR_ARG, "mfma_rate: bad arguments");
+    hipError_t e = mfma_rate_launch(iters, random_operands != 0, out, (hipStream_t)stream);
+    return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "mfma_rate: %s", hipGetErrorString(e));
+}
+
 int cf_op_checksum(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* host_out, void* stream) {
     if (!data || !host_out) return cf_fail(nullptr, CF_ERR_ARG, "null operand");
     uint64_t* dev = nullptr;

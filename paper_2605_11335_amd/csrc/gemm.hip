@@ -434,6 +434,51 @@ double gemm_fill(int M, int n) {
     return work / std::min(c256, c128);
 }
 
+// Diagnostic: nothing but 32x32x16 bf16 MFMAs on registers, one wave per SIMD on every CU, four
+// independent accumulators per wave.  Its rate is what the matrix cores sustain at the clock the
+// chip settles to under this load (the published peak assumes the maximum clock).  The clock depends
+// on what the operands look like: `random_operands` = 0 feeds the same small values to every MFMA,
+// 1 feeds sixteen different pairs of pseudo-random fragments spread like N(0,1) data, as a GEMM does.
+namespace {
+__global__ __launch_bounds__(256) void mfma_rate_kernel(int iters, int random_operands, float* out) {
+    bf16x8 a[4], b[4];
+    uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            h = h * 1664525u + 1013904223u;
+            const float u = (float)(h >> 8) * (1.0f / 16777216.0f);          // [0, 1)
+            h = h * 1664525u + 1013904223u;
+            const float w = (float)(h >> 8) * (1.0f / 16777216.0f);
+            a[i][e] = random_operands ? (bf16)(3.46f * (u - 0.5f)) : (bf16)(0.001f * (threadIdx.x + e));   // unit variance
+            b[i][e] = random_operands ? (bf16)(3.46f * (w - 0.5f)) : (bf16)(0.002f * (e + 1));
+        }
+    floatx16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    for (int it = 0; it < iters; ++it)
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            acc[q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[random_operands ? (q & 3) : 0], b[random_operands ? (q >> 2) : 0],
+                                                                 acc[q & 3], 0, 0, 0);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+}  // namespace
+
+// `out` holds 256 * 256 floats; FLOPs of a launch = 256 workgroups x 4 waves x iters x 16 MFMAs x 32768
+hipError_t mfma_rate_launch(int iters, int random_operands, float* out, hipStream_t s) {
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(256), dim3(256), 0, s, iters, random_operands, out);
+    return hipGetLastError();
+}
+
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     const int t = gemm_tile(g);
     // the erf form of the activation costs some forty VALU operations per element: it gets kernels

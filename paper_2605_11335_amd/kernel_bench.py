@@ -5,6 +5,7 @@ device-to-device copy of known size, used to calibrate hardware byte counters.
     python -m paper_2605_11335_amd.kernel_bench linear_residual 2304x3072x15360 [iters]
     python -m paper_2605_11335_amd.kernel_bench attention 12x4608x128 [iters]
     python -m paper_2605_11335_amd.kernel_bench copy 536870912 [iters]      # bytes
+    python -m paper_2605_11335_amd.kernel_bench mfma_rate 20000 [iters]     # MFMAs on registers only
 
 Timing uses events on the current stream; inputs are seeded N(0,1) activations and N(0,0.02)
 weights in bf16.  The GEMM benchmarks rotate over enough operand sets that consecutive launches
@@ -75,6 +76,14 @@ def main(argv):
         dst = torch.empty_like(src)
         ms = timeit(lambda: dst.copy_(src), iters)
         print(f"copy {n} bytes: {ms:.4f} ms  {2 * n / ms / 1e6:.1f} GB/s (read + write)")
+    elif which == "mfma_rate":
+        n = int(shape)
+        out = torch.empty(256 * 256, dtype=torch.float32, device=DEV)
+        flops = 256 * 4 * n * 16 * 32768.0
+        for rnd, what in ((False, "one pair of small-valued fragments repeated"), (True, "16 pairs of unit-variance random fragments")):
+            ms = timeit(lambda: B.cf_op_mfma_rate(n, rnd, out), iters)
+            print(f"mfma_rate {n} x 16 MFMAs per wave, 1024 waves, {what}: {ms:.4f} ms  {flops / ms / 1e9:.1f} TFLOP/s "
+                  f"({flops / ms / 1e9 / 2500 * 100:.1f} % of the published 2500; implied clock {flops / ms / 1e9 / 2500 * 2.4:.2f} GHz)")
     else:
         raise SystemExit(__doc__)
 
