@@ -242,3 +242,16 @@ def test_linear_gelu_forms_are_told_apart():
     for form in (False, True):
         assert (np.abs(outs[form] - refs[form]) <= tol(refs[form])).all(), form
         assert (np.abs(outs[form] - refs[not form]) > tol(refs[not form])).sum() > 100, form
+
+
+def test_mfma_rate_diagnostic_runs_and_is_deterministic():
+    out = torch.zeros(256 * 256, dtype=torch.float32, device=DEV)
+    res = []
+    for rnd in (False, True, True):
+        B.cf_op_mfma_rate(50, rnd, out)
+        torch.cuda.synchronize()
+        res.append(out.cpu().numpy().copy())
+        assert np.isfinite(res[-1]).all() and np.abs(res[-1]).max() > 0
+    assert np.array_equal(res[1], res[2]) and not np.array_equal(res[0], res[1])
+    with pytest.raises(B.ChunkflowError):
+        B.cf_op_mfma_rate(0, False, out)
