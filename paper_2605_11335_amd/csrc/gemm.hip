@@ -79,7 +79,9 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, uint32_t bid, 
     const int tiles_m = (g.M + BM - 1) / BM;
     const int tiles_n = (g.n1 - g.n0 + BN - 1) / BN;
     const uint32_t lid = xcd_contiguous_id(bid, nblk);
-    constexpr int GM = 8;
+    // row-tile groups of about 8, all of one size: a short last group would walk every weight tile once more
+    const int n_groups = max(1, (tiles_m + 4) / 8);
+    const int GM = (tiles_m + n_groups - 1) / n_groups;
     const int group = lid / (GM * tiles_n);
     const int first_m = group * GM;
     const int gsz = min(tiles_m - first_m, GM);
