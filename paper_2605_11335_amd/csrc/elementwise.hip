@@ -13,6 +13,12 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+__device__ __forceinline__ void unpack8(const uint32x4& u, float* f) {
+    f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
+    f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
+    f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xffff0000u);
+    f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
+}
 __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
     f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
     f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
@@ -36,6 +42,11 @@ __device__ __forceinline__ int remote_pos(const TokenMap& m, int i) {
 // once per MV_ROWS weight vectors and that many 16-byte loads are in flight per lane.  A row's sum
 // is accumulated in the same lane order whatever rows share its wave.
 constexpr int MV_ROWS = 4;
+// U steps of the walk over K are fetched together (U * (MV_ROWS + 2) loads in flight per lane): with one
+// step per round trip to memory the kernel ran at the latency of K / 512 + MV_ROWS dependent loads, not
+// at the bandwidth of the weight matrix.  A lane whose step lies past the end re-reads the row's last
+// chunk and adds nothing.
+template <int U>
 __global__ __launch_bounds__(256) void modvec_kernel(WView W, uint64_t w_off, uint64_t b_off, const float* __restrict__ t,
                                                      float* __restrict__ m, int n0, int n1, int K, long m_bs) {
     t += (size_t)blockIdx.y * K;                 // one sample of the batch per grid row
@@ -46,26 +57,42 @@ __global__ __launch_bounds__(256) void modvec_kernel(WView W, uint64_t w_off, ui
     float acc[MV_ROWS];
 #pragma unroll
     for (int r = 0; r < MV_ROWS; ++r) acc[r] = 0.f;
-    for (int c = lane; c < K / 8; c += 64) {
-        uint4 u[MV_ROWS];
+    const int nc = K / 8;                        // 16-byte chunks per row
+    for (int c0 = lane; c0 < nc; c0 += 64 * U) {
+        uint32x4 u[U][MV_ROWS];
+        floatx4 t0[U], t1[U];
 #pragma unroll
-        for (int r = 0; r < MV_ROWS; ++r) {
-            const int nr = min(n + r, n1 - 1);
-            u[r] = *(const uint4*)wv_ptr(W, w_off + ((uint64_t)nr * K + (uint64_t)c * 8) * 2);
+        for (int q = 0; q < U; ++q) {
+            const int c = min(c0 + 64 * q, nc - 1);
+#pragma unroll
+            for (int r = 0; r < MV_ROWS; ++r) {
+                const int nr = min(n + r, n1 - 1);
+                u[q][r] = *(const uint32x4*)wv_ptr(W, w_off + ((uint64_t)nr * K + (uint64_t)c * 8) * 2);
+            }
+            t0[q] = *(const floatx4*)(t + c * 8);
+            t1[q] = *(const floatx4*)(t + c * 8 + 4);
         }
-        const float4 t0 = *(const float4*)(t + c * 8), t1 = *(const float4*)(t + c * 8 + 4);
 #pragma unroll
-        for (int r = 0; r < MV_ROWS; ++r) {
-            float w[8];
-            unpack8(u[r], w);
-            acc[r] += w[0] * t0.x + w[1] * t0.y + w[2] * t0.z + w[3] * t0.w + w[4] * t1.x + w[5] * t1.y + w[6] * t1.z + w[7] * t1.w;
+        for (int q = 0; q < U; ++q) {
+            if (c0 + 64 * q < nc) {
+#pragma unroll
+                for (int r = 0; r < MV_ROWS; ++r) {
+                    float w[8];
+                    unpack8(u[q][r], w);
+                    acc[r] += w[0] * t0[q].x + w[1] * t0[q].y + w[2] * t0[q].z + w[3] * t0[q].w + w[4] * t1[q].x + w[5] * t1[q].y +
+                              w[6] * t1[q].z + w[7] * t1[q].w;
+                }
+            }
         }
     }
+    // lane r adds the bias of row r and writes it: the MV_ROWS bias loads go out side by side
+    float mine = 0.f;
 #pragma unroll
     for (int r = 0; r < MV_ROWS; ++r) {
         const float v = wave_sum(acc[r]);
-        if (lane == 0 && n + r < n1) m[n + r] = v + wv_bf16(W, b_off, n + r);
+        if (lane == r) mine = v;
     }
+    if (lane < MV_ROWS && n + lane < n1) m[n + lane] = mine + wv_bf16(W, b_off, n + lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -90,6 +117,23 @@ __global__ __launch_bounds__(256) void ln_kernel(const float* __restrict__ x, co
         v[j] = *(const float4*)(xr + (lane + 64 * j) * 4);
         s += v[j].x + v[j].y + v[j].z + v[j].w;
     }
+    // the row-independent operands of the last step are requested now, so that they arrive while the
+    // statistics are reduced instead of costing a round trip of their own afterwards
+    floatx4 ma[NJ], mb[NJ];                      // modulate: scale, shift;  affine: weight | bias as bf16 pairs
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const int c = (lane + 64 * j) * 4;
+        if (AFFINE) {
+            const uint32x2 wa = *(const uint32x2*)wv_ptr(W, w_off + 2ull * c), wb = *(const uint32x2*)wv_ptr(W, b_off + 2ull * c);
+            ma[j] = floatx4{__uint_as_float(wa.x << 16), __uint_as_float(wa.x & 0xffff0000u), __uint_as_float(wa.y << 16),
+                            __uint_as_float(wa.y & 0xffff0000u)};
+            mb[j] = floatx4{__uint_as_float(wb.x << 16), __uint_as_float(wb.x & 0xffff0000u), __uint_as_float(wb.y << 16),
+                            __uint_as_float(wb.y & 0xffff0000u)};
+        } else {
+            ma[j] = *(const floatx4*)(scale + c);
+            mb[j] = *(const floatx4*)(shift + c);
+        }
+    }
     const float mean = wave_sum(s) / d;
     float q = 0.f;
 #pragma unroll
@@ -102,16 +146,10 @@ __global__ __launch_bounds__(256) void ln_kernel(const float* __restrict__ x, co
     for (int j = 0; j < NJ; ++j) {
         const int c = (lane + 64 * j) * 4;
         float a[4], b[4];
-        if (AFFINE) {
-            const uint2 wa = *(const uint2*)wv_ptr(W, w_off + 2ull * c), wb = *(const uint2*)wv_ptr(W, b_off + 2ull * c);
-            a[0] = __uint_as_float(wa.x << 16); a[1] = __uint_as_float(wa.x & 0xffff0000u);
-            a[2] = __uint_as_float(wa.y << 16); a[3] = __uint_as_float(wa.y & 0xffff0000u);
-            b[0] = __uint_as_float(wb.x << 16); b[1] = __uint_as_float(wb.x & 0xffff0000u);
-            b[2] = __uint_as_float(wb.y << 16); b[3] = __uint_as_float(wb.y & 0xffff0000u);
-        } else {
-            const float4 sc = *(const float4*)(scale + c), sh = *(const float4*)(shift + c);
-            a[0] = 1.f + sc.x; a[1] = 1.f + sc.y; a[2] = 1.f + sc.z; a[3] = 1.f + sc.w;
-            b[0] = sh.x; b[1] = sh.y; b[2] = sh.z; b[3] = sh.w;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a[e] = AFFINE ? ma[j][e] : 1.f + ma[j][e];
+            b[e] = mb[j][e];
         }
         bf16x4 o;
         o[0] = (bf16)(v[j].x * rstd * a[0] + b[0]);
@@ -390,8 +428,14 @@ hipError_t modvec_launch(const WView& W, uint64_t w_off, uint64_t b_off, const f
                          int K, int batch, long m_bs, hipStream_t s) {
     if (n1 <= n0) return hipSuccess;
     if (K % 8 || batch < 1 || batch > 65535) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(modvec_kernel, dim3((n1 - n0 + 4 * MV_ROWS - 1) / (4 * MV_ROWS), batch), dim3(256), 0, s, W, w_off, b_off, t, m, n0,
-                       n1, K, m_bs);
+    const dim3 grid((n1 - n0 + 4 * MV_ROWS - 1) / (4 * MV_ROWS), batch);
+    const int steps = (K / 8 + 63) / 64;         // steps of a lane's walk over K; taken 3 or 4 at a time
+#define CF_MV_CASE(U) hipLaunchKernelGGL(modvec_kernel<U>, grid, dim3(256), 0, s, W, w_off, b_off, t, m, n0, n1, K, m_bs)
+    if (steps == 1) CF_MV_CASE(1);
+    else if (steps == 2) CF_MV_CASE(2);
+    else if (steps % 3 == 0) CF_MV_CASE(3);
+    else CF_MV_CASE(4);
+#undef CF_MV_CASE
     return hipGetLastError();
 }
 
