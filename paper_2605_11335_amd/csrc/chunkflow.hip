@@ -1037,7 +1037,10 @@ int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute
     }
     if (rc != CF_OK) return rc;
     if (streamed) {
-        CF_TRY(chunked_prefetch_wait(c, block, -1, compute_stream));   // no-op unless a tail chunk fed nothing
+        // the slot's release below must follow every chunk: a tail chunk that fed no layer is waited for
+        // here (nothing to do when the layers' own waits reached the last chunk -- a wait on an event
+        // that fired long ago still costs the stream tens of microseconds)
+        if (c->waited_upto < p.n_chunks - 1) CF_TRY(chunked_prefetch_wait(c, block, -1, compute_stream));
         CF_HIP(c, hipEventRecord(c->done_ev[s], (hipStream_t)compute_stream));
         c->slot_fwd_seq[s] = ++c->fwd_seq;
         c->done_valid[s] = true;
