@@ -242,131 +242,131 @@ __device__ __forceinline__ void gemm_tile_body(const GemmArgs& g, uint32_t bid, 
     constexpr int PITCH = RB + (OUT_BF16 ? 16 : 32);       // padded: conflict-free quad writes
     constexpr int CPR = RB / 16, RPI = 64 / CPR;           // 16-byte chunks per row, rows per store
     static_assert(4 * WM * PITCH <= 160 * 1024, "staging exceeds LDS");
-    {   // (a scope of its own: the names below shadow the main loop's)
-    // lane coordinates are derived afresh (lane from the wave's bit count, wave from its scalar copy)
-    // rather than kept in vector registers across the main loop
-    const int lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)), wave = uw;
-    const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
-    const int li = lane & 31, lg = lane >> 5;
-    // Bias of the wave's features, in accumulator order: 4 consecutive features per (feature tile, register
-    // quad).  Fetched in one go: taken one by one in the epilogue, each would cost a memory round trip.
-    uint32x2 bias_raw[NT][4];
-#pragma unroll
-    for (int i = 0; i < NT; ++i)
-#pragma unroll
-        for (int vb = 0; vb < 4; ++vb) bias_raw[i][vb] = uint32x2{0u, 0u};
-    if (g.has_bias) {
+    {   // the epilogue is a scope of its own: its lane coordinates shadow the main loop's
+        // lane coordinates are derived afresh (lane from the wave's bit count, wave from its scalar copy)
+        // rather than kept in vector registers across the main loop
+        const int lane = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)), wave = uw;
+        const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+        const int li = lane & 31, lg = lane >> 5;
+        // Bias of the wave's features, in accumulator order: 4 consecutive features per (feature tile, register
+        // quad).  Fetched in one go: taken one by one in the epilogue, each would cost a memory round trip.
+        uint32x2 bias_raw[NT][4];
 #pragma unroll
         for (int i = 0; i < NT; ++i)
 #pragma unroll
-            for (int vb = 0; vb < 4; ++vb) {
-                const int n = min(n0 + wn0 + i * 32 + vb * 8 + lg * 4, g.N - 4);
-                bias_raw[i][vb] = *(const uint32x2*)wv_ptr(g.W, g.bias_off + 2ull * n);
-            }
-    }
-    slab_handover();                                       // every wave is done reading the slabs; the bias loads flew meanwhile
-    char* const stg = smem + wave * (WM * PITCH);
+            for (int vb = 0; vb < 4; ++vb) bias_raw[i][vb] = uint32x2{0u, 0u};
+        if (g.has_bias) {
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
+            for (int i = 0; i < NT; ++i)
 #pragma unroll
-        for (int ii = 0; ii < NTP; ++ii) {
-            const int i = p * NTP + ii;
-#pragma unroll
-            for (int vb = 0; vb < 4; ++vb) {
-                const int n = min(n0 + wn0 + i * 32 + vb * 8 + lg * 4, g.N - 4);
-                const uint32x2 bb = bias_raw[i][vb];
-                const float b[4] = {__uint_as_float(bb.x << 16), __uint_as_float(bb.x & 0xffff0000u),
-                                    __uint_as_float(bb.y << 16), __uint_as_float(bb.y & 0xffff0000u)};
-                const bool act = OUT_BF16 && n >= g.n_split;
-#pragma unroll
-                for (int j = 0; j < MT; ++j) {
-                    float v[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] = acc[i][j][vb * 4 + e] + b[e];
-                    char* dst = stg + (j * 32 + li) * PITCH + (ii * 32 + vb * 8 + lg * 4) * ELT;
-                    if (OUT_BF16) {
-                        if (act) {
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) v[e] = ACT_ERF ? gelu_erf_f32(v[e]) : gelu_tanh_f32(v[e]);
-                        }
-                        bf16x4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-                        *(bf16x4*)dst = o;
-                    } else {
-                        *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
-                    }
+                for (int vb = 0; vb < 4; ++vb) {
+                    const int n = min(n0 + wn0 + i * 32 + vb * 8 + lg * 4, g.N - 4);
+                    bias_raw[i][vb] = *(const uint32x2*)wv_ptr(g.W, g.bias_off + 2ull * n);
                 }
-            }
         }
-        // coalesced write-out of this pass
-        const int col = (lane % CPR) * (16 / ELT);                         // first column of the lane's chunk
-        const int n = n0 + wn0 + p * (NTP * 32) + col;
-        if constexpr (OUT_BF16) {
+        slab_handover();                       // every wave is done reading the slabs; the bias loads flew meanwhile
+        char* const stg = smem + wave * (WM * PITCH);
 #pragma unroll
-            for (int r = 0; r < WM / RPI; ++r) {
-                const int row = r * RPI + lane / CPR;
-                const int m = m0 + wm0 + row;
-                const uint4 val = *(const uint4*)(stg + row * PITCH + (lane % CPR) * 16);
-                if (m < g.M && n < g.n1) {
-                    bf16* dst = n < g.n_split ? g.out0 + (size_t)m * g.ld0 + n
-                                              : g.out1 + (size_t)m * g.ld1 + g.col1_off + (n - g.n_split);
-                    *(uint4*)dst = val;
-                }
-            }
-        } else {
-            // y = resid + gate * (...), the product rounded before the sum; the gate belongs to the row's
-            // sample.  The residual rows of UB stores are fetched together: taken one by one, each store
-            // would wait out a memory round trip of its own.  Lanes outside the problem read a valid
-            // address (row M-1, column 0) and store nothing.
-            constexpr int UB = 8;
-            static_assert((WM / RPI) % UB == 0, "write-out batches");
-            const bool n_ok = n < g.n1;
-            const int nc = n_ok ? n : 0;
-            const bool has_gate = g.gate != nullptr;
-            const float* const gate_p = has_gate ? g.gate : g.resid;       // a readable address either way
-            const long gate_bs = has_gate ? g.gate_bs : 0;
-            auto write_out = [&](auto per_sample) {
-                constexpr bool PS = decltype(per_sample)::value;
-                floatx4 gate_c = {1.f, 1.f, 1.f, 1.f};
-                if (!PS && has_gate) gate_c = *(const floatx4*)(gate_p + nc);
+        for (int p = 0; p < PASSES; ++p) {
 #pragma unroll
-                for (int r0 = 0; r0 < WM / RPI; r0 += UB) {
-                    floatx4 rr[UB], gt[UB];                // native vectors: arrays of them stay in registers
-                    size_t y_off[UB];
-                    bool ok[UB];
+            for (int ii = 0; ii < NTP; ++ii) {
+                const int i = p * NTP + ii;
 #pragma unroll
-                    for (int u = 0; u < UB; ++u) {
-                        const int row = (r0 + u) * RPI + lane / CPR;
-                        const int m = m0 + wm0 + row;
-                        ok[u] = n_ok && m < g.M;
-                        const int mm = min(m, g.M - 1);
-                        int b = 0, i = mm;
-                        if (PS) { b = mm / g.rows_per_sample; i = mm - b * g.rows_per_sample; }
-                        rr[u] = *(const floatx4*)(g.resid + (size_t)b * g.resid_bs + (size_t)i * g.ldy + nc);
-                        if (PS) {
-                            const floatx4 t = *(const floatx4*)(gate_p + (size_t)b * gate_bs + nc);
-                            gt[u] = has_gate ? t : gate_c;
+                for (int vb = 0; vb < 4; ++vb) {
+                    const int n = min(n0 + wn0 + i * 32 + vb * 8 + lg * 4, g.N - 4);
+                    const uint32x2 bb = bias_raw[i][vb];
+                    const float b[4] = {__uint_as_float(bb.x << 16), __uint_as_float(bb.x & 0xffff0000u),
+                                        __uint_as_float(bb.y << 16), __uint_as_float(bb.y & 0xffff0000u)};
+                    const bool act = OUT_BF16 && n >= g.n_split;
+#pragma unroll
+                    for (int j = 0; j < MT; ++j) {
+                        float v[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][vb * 4 + e] + b[e];
+                        char* dst = stg + (j * 32 + li) * PITCH + (ii * 32 + vb * 8 + lg * 4) * ELT;
+                        if (OUT_BF16) {
+                            if (act) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) v[e] = ACT_ERF ? gelu_erf_f32(v[e]) : gelu_tanh_f32(v[e]);
+                            }
+                            bf16x4 o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+                            *(bf16x4*)dst = o;
                         } else {
-                            gt[u] = gate_c;
+                            *(float4*)dst = make_float4(v[0], v[1], v[2], v[3]);
                         }
-                        y_off[u] = (size_t)b * g.y_bs + (size_t)i * g.ldy + nc;
-                    }
-#pragma unroll
-                    for (int u = 0; u < UB; ++u) {
-                        const int row = (r0 + u) * RPI + lane / CPR;
-                        const floatx4 val = *(const floatx4*)(stg + row * PITCH + (lane % CPR) * 16);
-                        floatx4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = __fadd_rn(rr[u][e], __fmul_rn(gt[u][e], val[e]));
-                        if (ok[u]) *(floatx4*)(g.y + y_off[u]) = o;
                     }
                 }
-            };
-            if (g.rows_per_sample) write_out(std::true_type{}); else write_out(std::false_type{});
+            }
+            // coalesced write-out of this pass
+            const int col = (lane % CPR) * (16 / ELT);                         // first column of the lane's chunk
+            const int n = n0 + wn0 + p * (NTP * 32) + col;
+            if constexpr (OUT_BF16) {
+#pragma unroll
+                for (int r = 0; r < WM / RPI; ++r) {
+                    const int row = r * RPI + lane / CPR;
+                    const int m = m0 + wm0 + row;
+                    const uint4 val = *(const uint4*)(stg + row * PITCH + (lane % CPR) * 16);
+                    if (m < g.M && n < g.n1) {
+                        bf16* dst = n < g.n_split ? g.out0 + (size_t)m * g.ld0 + n
+                                                  : g.out1 + (size_t)m * g.ld1 + g.col1_off + (n - g.n_split);
+                        *(uint4*)dst = val;
+                    }
+                }
+            } else {
+                // y = resid + gate * (...), the product rounded before the sum; the gate belongs to the row's
+                // sample.  The residual rows of UB stores are fetched together: taken one by one, each store
+                // would wait out a memory round trip of its own.  Lanes outside the problem read a valid
+                // address (row M-1, column 0) and store nothing.
+                constexpr int UB = 8;
+                static_assert((WM / RPI) % UB == 0, "write-out batches");
+                const bool n_ok = n < g.n1;
+                const int nc = n_ok ? n : 0;
+                const bool has_gate = g.gate != nullptr;
+                const float* const gate_p = has_gate ? g.gate : g.resid;       // a readable address either way
+                const long gate_bs = has_gate ? g.gate_bs : 0;
+                auto write_out = [&](auto per_sample) {
+                    constexpr bool PS = decltype(per_sample)::value;
+                    floatx4 gate_c = {1.f, 1.f, 1.f, 1.f};
+                    if (!PS && has_gate) gate_c = *(const floatx4*)(gate_p + nc);
+#pragma unroll
+                    for (int r0 = 0; r0 < WM / RPI; r0 += UB) {
+                        floatx4 rr[UB], gt[UB];                // native vectors: arrays of them stay in registers
+                        size_t y_off[UB];
+                        bool ok[UB];
+#pragma unroll
+                        for (int u = 0; u < UB; ++u) {
+                            const int row = (r0 + u) * RPI + lane / CPR;
+                            const int m = m0 + wm0 + row;
+                            ok[u] = n_ok && m < g.M;
+                            const int mm = min(m, g.M - 1);
+                            int b = 0, i = mm;
+                            if (PS) { b = mm / g.rows_per_sample; i = mm - b * g.rows_per_sample; }
+                            rr[u] = *(const floatx4*)(g.resid + (size_t)b * g.resid_bs + (size_t)i * g.ldy + nc);
+                            if (PS) {
+                                const floatx4 t = *(const floatx4*)(gate_p + (size_t)b * gate_bs + nc);
+                                gt[u] = has_gate ? t : gate_c;
+                            } else {
+                                gt[u] = gate_c;
+                            }
+                            y_off[u] = (size_t)b * g.y_bs + (size_t)i * g.ldy + nc;
+                        }
+#pragma unroll
+                        for (int u = 0; u < UB; ++u) {
+                            const int row = (r0 + u) * RPI + lane / CPR;
+                            const floatx4 val = *(const floatx4*)(stg + row * PITCH + (lane % CPR) * 16);
+                            floatx4 o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = __fadd_rn(rr[u][e], __fmul_rn(gt[u][e], val[e]));
+                            if (ok[u]) *(floatx4*)(g.y + y_off[u]) = o;
+                        }
+                    }
+                };
+                if (g.rows_per_sample) write_out(std::true_type{}); else write_out(std::false_type{});
+            }
         }
     }
-    }   // epilogue scope
 }
 
 template <int BM, int BN, int EPI>
