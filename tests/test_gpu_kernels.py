@@ -127,8 +127,10 @@ def test_attention_uniform_values_and_dominant_key():
     assert np.abs(got[0, 3] - bf16_round(v2[0, 150])[0]).max() < 1e-2
 
 
-@pytest.mark.parametrize("rows,d", [(100, 512), (37, 3072), (5, 256)])
+@pytest.mark.parametrize("rows,d", [(100, 512), (37, 3072), (5, 256), (9, 768), (6, 1024), (7, 1536), (3, 2048), (2, 4096)])
 def test_ln_modulate(rows, d):
+    """Every row width the kernel is built for (d / 256 in 1, 2, 3, 4, 6, 8, 12, 16), row counts that leave
+    the last workgroup partly empty."""
     rng = np.random.default_rng(rows + d)
     x = (rng.normal(size=(rows, d)) * 2 + 0.5).astype(np.float32)
     shift, scale = rng.normal(size=d).astype(np.float32), rng.normal(size=d).astype(np.float32)
@@ -140,9 +142,11 @@ def test_ln_modulate(rows, d):
     assert_bf16_close(host_bits(out), ref, extra_abs=1e-5)
 
 
-def test_modvec():
-    n, K = 1536, 512
-    rng = np.random.default_rng(3)
+@pytest.mark.parametrize("n,K", [(1536, 512), (70, 1024), (264, 2560), (96, 4096), (50, 768), (33, 3072)])
+def test_modvec(n, K):
+    """One, two, three and four steps of the walk over K per trip (K = 2560 ends on a trip whose last steps
+    lie past the row, K = 768 on a step only half the lanes take part in); row counts that are not whole waves."""
+    rng = np.random.default_rng(3 + n + K)
     buf, w, b, w_off, b_off = make_blob(rng, n, K)
     t = rng.normal(size=K).astype(np.float32)
     m = torch.zeros(n, dtype=torch.float32, device=DEV)
