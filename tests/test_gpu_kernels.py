@@ -222,6 +222,32 @@ def test_linear_under_one_round_of_tiles():
     assert max_abs(y.cpu().numpy(), resid + g.astype(np.float64) * z) < 1e-3
 
 
+@pytest.mark.parametrize("M,N", [(2304, 4096), (2100, 2056)])
+def test_linear_every_epilogue_on_both_tiles(M, N):
+    """The first shape fills the chip better with 256 x 256 tiles, the second (ragged in both directions)
+    with 128 x 128 ones; each runs the split epilogue with either activation and the gated residual one."""
+    K, n_split = 192, 1024
+    rng = np.random.default_rng(M + N)
+    a, ab = bf16_round(rng.normal(size=(M, K)))
+    buf, w, b, w_off, b_off = make_blob(rng, N, K)
+    A, blob = dev_bits(ab), torch.from_numpy(buf).to(DEV)
+    z = a.astype(np.float64) @ w.T + b
+    for erf_form in (False, True):
+        out0 = torch.zeros((M, n_split), dtype=torch.int16, device=DEV)
+        out1 = torch.zeros((M, N - n_split), dtype=torch.int16, device=DEV)
+        B.cf_op_linear(A, blob, w_off, b_off, M, N, K, out0, out1, n_split=n_split, gelu_erf=erf_form)
+        torch.cuda.synchronize()
+        act = ob.gelu_erf if erf_form else ob.gelu_tanh
+        assert_bf16_close(host_bits(out0), z[:, :n_split], extra_abs=1e-4)
+        assert_bf16_close(host_bits(out1), act(z[:, n_split:]), extra_abs=2e-4)
+    resid = rng.normal(size=(M, N)).astype(np.float32)
+    g = rng.normal(size=N).astype(np.float32)
+    y = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    B.cf_op_linear_residual(A, blob, w_off, b_off, M, N, K, torch.from_numpy(resid).to(DEV), torch.from_numpy(g).to(DEV), y)
+    torch.cuda.synchronize()
+    assert max_abs(y.cpu().numpy(), resid + g.astype(np.float64) * z) < 1e-3
+
+
 def test_linear_gelu_forms_are_told_apart():
     """The epilogue's two activations (tanh form, erf form) against the oracle's: pre-activations
     are spread over +-6 so that the region where the forms differ by several bf16 ulps (around
