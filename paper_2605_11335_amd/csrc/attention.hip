@@ -33,8 +33,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 constexpr int BKV = 64;    // keys per tile
 
-// NW waves of 32 queries each per workgroup.  NW = 4 runs two workgroups per CU; NW = 5..8 run one,
-// which lets the launcher pick the query-tile height whose grid fills the last round best.
+// NW waves of 32 queries each per workgroup: 4 (two workgroups per CU), 7 or 8 (one per CU).
 template <int HD, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
     constexpr int BQ = 32 * NW;
@@ -279,8 +278,6 @@ hipError_t launch(const AttnArgs& a, hipStream_t s) {
 template <int HD>
 hipError_t launch_nw(int nw, const AttnArgs& a, hipStream_t s) {
     switch (nw) {
-        case 5: return launch<HD, 5>(a, s);
-        case 6: return launch<HD, 6>(a, s);
         case 7: return launch<HD, 7>(a, s);
         case 8: return launch<HD, 8>(a, s);
         default: return launch<HD, 4>(a, s);
@@ -302,20 +299,33 @@ const char* attn_check(const AttnArgs& a) {
     return nullptr;
 }
 
-// Waves per workgroup: a CU holds 8 waves of this kernel (two 4-wave workgroups or one of 5..8), so
-// a round of workgroups costs (waves resident per CU) / 8 of a full round; pick the height with the
-// cheapest total, preferring fewer, taller workgroups (fewer K/V tile copies) on ties.
+// Waves per workgroup.  A CU holds 8 waves of this kernel, as one workgroup of 7 or 8 or as two of 4, and
+// runs its workgroups generation after generation; a generation takes about as long whether the chip is
+// full of workgroups or holds a handful.  Estimated time, in units of one K/V tile of an 8-wave workgroup
+// (fitted to sweeps of 8 to 1861 tiles on 12 to 24 heads):
+//   8 waves: generations x (tiles + 2.5)           the fixed part is the prologue and epilogue nothing overlaps
+//   7 waves: generations x (0.96 tiles + 9)        a little faster per tile (one SIMD holds a single wave), its
+//                                                  tile copies dealt unevenly; never fewer generations than 8
+//   4 waves: generations x (1.08 tiles + 0.5)      twice the tile copies per query, but one workgroup's fixed
+//                                                  part hides behind the other's tiles, and a last generation
+//                                                  of at most one workgroup per CU takes 0.55 of a full one
+// Short sweeps (cross-attention to a few hundred keys) and grids that end on a half-empty generation go to
+// 4; very long sweeps whose 7- and 8-wave grids need the same number of generations to 7; the rest to 8.
+// Heights 5 and 6 were built once and never won: three SIMDs share the work of four.
 int attn_waves(const AttnArgs& a) {
     // a grid that cannot even give every CU one 4-wave workgroup is spread as widely as possible
     if ((long)((a.nq + 127) / 128) * a.H <= 256) return 4;
-    int best = 4;
-    double best_cost = 1e300;
-    for (int nw = 8; nw >= 4; --nw) {
-        const long items = (long)((a.nq + 32 * nw - 1) / (32 * nw)) * a.H;
-        const long slots = nw == 4 ? 512 : 256;
-        const double cost = (double)((items + slots - 1) / slots) * (nw == 4 ? 1.0 : nw / 8.0);
-        if (cost < best_cost - 1e-9) { best_cost = cost; best = nw; }
-    }
+    const double tiles = (double)((a.nk + BKV - 1) / BKV);
+    auto items = [&](int nw) { return (long)((a.nq + 32 * nw - 1) / (32 * nw)) * a.H; };
+    auto generations = [](long n, long slots) { return (double)((n + slots - 1) / slots); };
+    const double c8 = generations(items(8), 256) * (tiles + 2.5);
+    const double c7 = generations(items(7), 256) * (0.96 * tiles + 9.0);
+    const long full4 = items(4) / 512, rest4 = items(4) % 512;
+    const double c4 = ((double)full4 + (rest4 == 0 ? 0.0 : (rest4 <= 256 ? 0.55 : 1.0))) * (1.08 * tiles + 0.5);
+    int best = 8;
+    double best_cost = c8;
+    if (c7 < best_cost - 1e-9) { best = 7; best_cost = c7; }
+    if (c4 < best_cost - 1e-9) { best = 4; best_cost = c4; }
     return best;
 }
 
