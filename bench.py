@@ -29,9 +29,9 @@ PEAK_LINK_GBS = 64.0           # PCIe Gen5 x16, one direction
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # scaled by a copy kernel of known size (see profiles/); None until measured for a workload.
-TRAFFIC = {("flux", "gemm_lin1/256x256"): 607760349,      # profiles/hbm_traffic_flux_kernels.md
-           ("flux", "gemm_lin2/128x128"): 528729856,
-           ("flux", "attention"): 73297702}
+TRAFFIC = {("flux", "gemm_lin1/256x256"): 607860396,      # profiles/hbm_traffic_flux_kernels.md
+           ("flux", "gemm_lin2/128x128"): 528712950,
+           ("flux", "attention"): 66201452}
 
 
 def parse():
