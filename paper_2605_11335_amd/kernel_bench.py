@@ -5,6 +5,7 @@ device-to-device copy of known size, used to calibrate hardware byte counters.
     python -m paper_2605_11335_amd.kernel_bench linear_residual 2304x3072x15360 [iters]
     python -m paper_2605_11335_amd.kernel_bench attention 12x4608x128 [iters]
     python -m paper_2605_11335_amd.kernel_bench copy 536870912 [iters]      # bytes
+    python -m paper_2605_11335_amd.kernel_bench checksum 283183616 [iters]  # bytes (a C2 blob)
     python -m paper_2605_11335_amd.kernel_bench mfma_rate 20000 [iters]     # MFMAs on registers only
 
 Timing uses events on the current stream; inputs are seeded N(0,1) activations and N(0,0.02)
@@ -76,6 +77,11 @@ def main(argv):
         dst = torch.empty_like(src)
         ms = timeit(lambda: dst.copy_(src), iters)
         print(f"copy {n} bytes: {ms:.4f} ms  {2 * n / ms / 1e6:.1f} GB/s (read + write)")
+    elif which == "checksum":
+        n = int(shape) // 8 * 8
+        data = torch.empty(n, dtype=torch.uint8, device=DEV).random_(0, 255)
+        ms = timeit(lambda: B.cf_op_checksum(data, n, 0), iters)       # reads the result back: a host sync per call
+        print(f"checksum {n} bytes: {ms:.4f} ms  {n / ms / 1e6:.1f} GB/s (read)")
     elif which == "mfma_rate":
         n = int(shape)
         out = torch.empty(256 * 256, dtype=torch.float32, device=DEV)
