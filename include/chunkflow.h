@@ -191,6 +191,14 @@ int cf_blob_layout_of(const cf_ctx* ctx, int32_t block, cf_tensor_slot* out, int
 int cf_plan_panels(const cf_ctx* ctx, const char* tensor, int32_t m_rows, int32_t n_resident_chunks,
                    int32_t* row0, int32_t* row1, int32_t* wait_chunk, int32_t* n);
 
+/* Host-only view of how an attention launch over H heads, nq queries and nk keys of width head_dim is
+ * shaped (Sec. 2.1: each rank attends over the whole sequence for its heads; App. B: the 4*B*S^2*d
+ * term): *waves_per_workgroup receives 4 (two workgroups per CU), 7 or 8 (one), each wave owning 32
+ * queries.  The choice minimises an estimate of the launch's time: generations of workgroups times the
+ * time of one generation, fitted to measurements.  No GPU is touched.  CF_ERR_ARG: non-positive
+ * sizes, head_dim other than 64 or 128, NULL result. */
+int cf_plan_attention(int32_t H, int32_t nq, int32_t nk, int32_t head_dim, int32_t* waves_per_workgroup);
+
 /* ---- overlap model at chunk granularity and the memory-latency dial (Sec. 3.1-3.3; host only).
  * cf_simulate walks the copy stream and the compute stream of the scheduler chunk by chunk for the
  * context's model, chunk size and block kinds: chunks of block i+1 are copied back to back while

@@ -70,7 +70,7 @@ class cf_tune_choice(C.Structure):
 #: every symbol include/chunkflow.h declares
 EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_chunks", "cf_blob_layout",
            "cf_set_block_kinds", "cf_block_kind_of", "cf_blob_bytes_of", "cf_n_chunks_of", "cf_blob_layout_of",
-           "cf_workspace_bytes", "cf_plan_panels", "cf_simulate", "cf_tune", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
+           "cf_workspace_bytes", "cf_plan_panels", "cf_plan_attention", "cf_simulate", "cf_tune", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
            "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
            "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling", "cf_set_adaptive_waits",
            "cf_kernel_times", "cf_kernel_times_reset", "cf_sync", "cf_op_linear", "cf_op_linear_residual",
@@ -106,6 +106,7 @@ def lib() -> C.CDLL:
         _lib.cf_set_adaptive_waits.argtypes = [C.c_void_p, C.c_int32]
         _lib.cf_plan_panels.argtypes = [C.c_void_p, C.c_char_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(C.c_int32)]
+        _lib.cf_plan_attention.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         _lib.cf_register_block.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64]
         _lib.cf_set_block_kinds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         _lib.cf_simulate.argtypes = [C.c_void_p, C.c_double, C.POINTER(cf_machine_t), C.POINTER(cf_sim_result)]
@@ -353,6 +354,13 @@ def cf_op_linear(A, blob, w_off, bias_off, M, N, K, out0, out1=None, n_split=Non
     _check(lib().cf_op_linear(_ptr(A), K if lda is None else lda, _ptr(blob), w_off, bias_off, M, N, K, n0, n1, n_split,
                               _ptr(out0), (n_split if ld0 is None else ld0), _ptr(out1),
                               ((N - n_split) if ld1 is None else ld1), int(gelu_erf), _stream_handle(stream)))
+
+
+def cf_plan_attention(H: int, nq: int, nk: int, head_dim: int) -> int:
+    """Waves per workgroup an attention launch of this shape takes (host arithmetic only)."""
+    out = C.c_int32()
+    _check(lib().cf_plan_attention(H, nq, nk, head_dim, C.byref(out)))
+    return out.value
 
 
 def cf_op_mfma_rate(iters: int, random_operands: bool, out, stream=None) -> None:

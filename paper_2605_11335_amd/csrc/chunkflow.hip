@@ -878,6 +878,15 @@ int cf_plan_panels(const cf_ctx* c, const char* tensor, int32_t m_rows, int32_t 
     return CF_OK;
 }
 
+int cf_plan_attention(int32_t H, int32_t nq, int32_t nk, int32_t head_dim, int32_t* waves_per_workgroup) {
+    if (!waves_per_workgroup || H <= 0 || nq <= 0 || nk <= 0 || (head_dim != 64 && head_dim != 128))
+        return cf_fail(nullptr, CF_ERR_ARG, "cf_plan_attention: positive sizes, head_dim 64 or 128 and a result pointer are required");
+    AttnArgs a{};
+    a.H = H; a.nq = nq; a.nk = nk; a.hd = head_dim;
+    *waves_per_workgroup = attn_waves(a);
+    return CF_OK;
+}
+
 int cf_workspace_bytes(const cf_ctx* c, uint64_t* out) {
     if (!c || !out) return CF_ERR_ARG;
     *out = c->ws_bytes;

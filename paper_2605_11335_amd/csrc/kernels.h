@@ -55,6 +55,7 @@ struct AttnArgs {
 };
 const char* attn_check(const AttnArgs& a);
 hipError_t attn_launch(const AttnArgs& a, hipStream_t s);
+int attn_waves(const AttnArgs& a);      // waves per workgroup attn_launch takes (host arithmetic only)
 
 // m[b][n] = sum_k W[n,k] t[b][k] + bias[n]  (fp32 out), rows [n0, n1), for `batch` vectors t + b*K -> m + b*m_bs
 hipError_t modvec_launch(const WView& W, uint64_t w_off, uint64_t b_off, const float* t, float* m,

@@ -189,3 +189,28 @@ def test_mixed_block_kinds_are_planned_per_block():
             no_txt.cf_set_block_kinds([wl.KIND_DOUBLE, 0])      # double-stream needs text rows
     finally:
         no_txt.close()
+
+
+def test_attention_launch_shapes():
+    """The launch planner's choices for the shapes they were measured on (one MI355X): 8 waves per
+    workgroup for the Flux-like and the Hunyuan-like self-attention, 7 for the Wan-like one (7- and 8-wave
+    grids take six generations either way, and a 7-wave generation of such a long sweep is shorter), 4 for
+    the cross-attention to 512 context tokens (short sweeps: one workgroup's fixed part hides behind the
+    other's tiles) and for grids that end on a half-empty generation; tiny grids are spread over 4-wave
+    workgroups.  Growing the key count alone never moves a choice from 8 towards 4."""
+    assert B.cf_plan_attention(12, 4608, 4608, 128) == 8
+    assert B.cf_plan_attention(12, 119056, 119056, 128) == 8
+    assert B.cf_plan_attention(12, 59528, 59528, 128) == 8
+    assert B.cf_plan_attention(12, 27280, 27280, 128) == 7
+    assert B.cf_plan_attention(24, 13640, 512, 128) == 4
+    assert B.cf_plan_attention(12, 8192, 8192, 128) == 4
+    assert B.cf_plan_attention(24, 4096, 4096, 128) == 4
+    assert B.cf_plan_attention(8, 512, 512, 64) == 4
+    for nq, H in ((4608, 12), (13640, 24), (5120, 8)):
+        picks = [B.cf_plan_attention(H, nq, nk, 128) for nk in (128, 512, 2048, 8192, 32768)]
+        assert all(p in (4, 7, 8) for p in picks)
+        first_tall = next((i for i, p in enumerate(picks) if p != 4), len(picks))
+        assert all(p != 4 for p in picks[first_tall:]), picks
+    for bad in ((0, 10, 10, 128), (1, 0, 10, 128), (1, 10, 0, 128), (1, 10, 10, 96)):
+        with pytest.raises(B.ChunkflowError):
+            B.cf_plan_attention(*bad)
