@@ -199,6 +199,13 @@ int cf_plan_panels(const cf_ctx* ctx, const char* tensor, int32_t m_rows, int32_
  * sizes, head_dim other than 64 or 128, NULL result. */
 int cf_plan_attention(int32_t H, int32_t nq, int32_t nk, int32_t head_dim, int32_t* waves_per_workgroup);
 
+/* Host-only view of the tile a linear layer over m_rows tokens and n_features output features is
+ * launched with (the GEMMs of App. B): *tile_rows receives 256 (256 x 256 tiles, one workgroup per CU)
+ * or 128 (128 x 128 tiles, two per CU).  The big tile has the better arithmetic intensity; the small
+ * one is taken where the big one would leave most CUs without a tile.  No GPU is touched.
+ * CF_ERR_ARG: non-positive sizes, NULL result. */
+int cf_plan_linear(int32_t m_rows, int32_t n_features, int32_t* tile_rows);
+
 /* ---- overlap model at chunk granularity and the memory-latency dial (Sec. 3.1-3.3; host only).
  * cf_simulate walks the copy stream and the compute stream of the scheduler chunk by chunk for the
  * context's model, chunk size and block kinds: chunks of block i+1 are copied back to back while

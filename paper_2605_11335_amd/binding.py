@@ -70,7 +70,7 @@ class cf_tune_choice(C.Structure):
 #: every symbol include/chunkflow.h declares
 EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_chunks", "cf_blob_layout",
            "cf_set_block_kinds", "cf_block_kind_of", "cf_blob_bytes_of", "cf_n_chunks_of", "cf_blob_layout_of",
-           "cf_workspace_bytes", "cf_plan_panels", "cf_plan_attention", "cf_simulate", "cf_tune", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
+           "cf_workspace_bytes", "cf_plan_panels", "cf_plan_attention", "cf_plan_linear", "cf_simulate", "cf_tune", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
            "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
            "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling", "cf_set_adaptive_waits",
            "cf_kernel_times", "cf_kernel_times_reset", "cf_sync", "cf_op_linear", "cf_op_linear_residual",
@@ -107,6 +107,7 @@ def lib() -> C.CDLL:
         _lib.cf_plan_panels.argtypes = [C.c_void_p, C.c_char_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                         C.POINTER(C.c_int32)]
         _lib.cf_plan_attention.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
+        _lib.cf_plan_linear.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         _lib.cf_register_block.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_uint64]
         _lib.cf_set_block_kinds.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
         _lib.cf_simulate.argtypes = [C.c_void_p, C.c_double, C.POINTER(cf_machine_t), C.POINTER(cf_sim_result)]
@@ -360,6 +361,13 @@ def cf_plan_attention(H: int, nq: int, nk: int, head_dim: int) -> int:
     """Waves per workgroup an attention launch of this shape takes (host arithmetic only)."""
     out = C.c_int32()
     _check(lib().cf_plan_attention(H, nq, nk, head_dim, C.byref(out)))
+    return out.value
+
+
+def cf_plan_linear(m_rows: int, n_features: int) -> int:
+    """Tile height (256 or 128) a linear layer of this shape is launched with (host arithmetic only)."""
+    out = C.c_int32()
+    _check(lib().cf_plan_linear(m_rows, n_features, C.byref(out)))
     return out.value
 
 

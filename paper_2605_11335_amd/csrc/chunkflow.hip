@@ -887,6 +887,15 @@ int cf_plan_attention(int32_t H, int32_t nq, int32_t nk, int32_t head_dim, int32
     return CF_OK;
 }
 
+int cf_plan_linear(int32_t m_rows, int32_t n_features, int32_t* tile_rows) {
+    if (!tile_rows || m_rows <= 0 || n_features <= 0)
+        return cf_fail(nullptr, CF_ERR_ARG, "cf_plan_linear: positive sizes and a result pointer are required");
+    GemmArgs g{};
+    g.M = m_rows; g.n0 = 0; g.n1 = n_features; g.N = n_features;
+    *tile_rows = gemm_tile(g) == 0 ? 256 : 128;
+    return CF_OK;
+}
+
 int cf_workspace_bytes(const cf_ctx* c, uint64_t* out) {
     if (!c || !out) return CF_ERR_ARG;
     *out = c->ws_bytes;

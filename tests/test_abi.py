@@ -214,3 +214,15 @@ def test_attention_launch_shapes():
     for bad in ((0, 10, 10, 128), (1, 0, 10, 128), (1, 10, 0, 128), (1, 10, 10, 96)):
         with pytest.raises(B.ChunkflowError):
             B.cf_plan_attention(*bad)
+
+
+def test_linear_tile_shapes():
+    """The tile choice for layer shapes on which both tiles were timed (one MI355X, operands read cold): the
+    listed choice was the faster one by 5-45 % (the Flux-like and Wan-like shares' layers, the context
+    projection of the Wan-like cross-attention, the image stream of the mixed stack's double-stream blocks)."""
+    for m, n, want in ((2304, 21504, 256), (2304, 3072, 128), (13640, 3072, 256), (13640, 9216, 256), (2048, 3072, 128),
+                       (512, 6144, 128), (4608, 3072, 256), (4608, 9216, 256), (1024, 21504, 256)):
+        assert B.cf_plan_linear(m, n) == want, (m, n)
+    assert B.cf_plan_linear(64, 64) == 128                       # one tile either way: the small one
+    with pytest.raises(B.ChunkflowError):
+        B.cf_plan_linear(0, 64)
