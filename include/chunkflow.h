@@ -319,6 +319,16 @@ int cf_op_modvec(const void* blob, uint64_t w_off, uint64_t b_off, const float* 
 int cf_op_mfma_rate(int32_t iters, int32_t random_operands, float* out, void* stream);
 /* checksum of a device byte range (definition above); host_out[1]; blocks the host. */
 int cf_op_checksum(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* host_out, void* stream);
+/* The same checksum for callers that cannot allocate device memory or block: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  `data` (device, 8-byte aligned,
+ * `bytes` a multiple of 8) is reduced into *dev_out (DEVICE memory, one uint64_t, caller-owned); the call
+ * only enqueues two kernels on `stream` and returns.  No hipMalloc/hipFree, no host synchronisation.
+ * The per-workgroup partial sums live in a fixed 256 KiB array inside the library image (one copy per
+ * GPU, held until the process ends), which bounds a call to 1 GiB (2^30 bytes): larger `bytes` is
+ * CF_ERR_ARG, as are NULL or misaligned pointers; nothing is launched then.  bytes = 0 stores 0.
+ * All calls on one GPU share that array: two calls whose kernels may overlap (different streams
+ * without an ordering between them) race; calls on one stream, or ordered by events, are safe. */
+int cf_op_checksum_noalloc(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* dev_out, void* stream);
 
 #ifdef __cplusplus
 }

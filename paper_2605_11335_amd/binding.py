@@ -74,7 +74,7 @@ EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_ch
            "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
            "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling", "cf_set_adaptive_waits",
            "cf_kernel_times", "cf_kernel_times_reset", "cf_sync", "cf_op_linear", "cf_op_linear_residual",
-           "cf_op_attention", "cf_op_ln_modulate", "cf_op_modvec", "cf_op_mfma_rate", "cf_op_checksum"]
+           "cf_op_attention", "cf_op_ln_modulate", "cf_op_modvec", "cf_op_mfma_rate", "cf_op_checksum", "cf_op_checksum_noalloc"]
 
 _lib = None
 
@@ -135,6 +135,7 @@ def lib() -> C.CDLL:
         _lib.cf_op_modvec.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib.cf_op_mfma_rate.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         _lib.cf_op_checksum.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p]
+        _lib.cf_op_checksum_noalloc.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p]
     return _lib
 
 
@@ -396,3 +397,9 @@ def cf_op_checksum(data, nbytes, first_word, stream=None) -> int:
     out = C.c_uint64()
     _check(lib().cf_op_checksum(_ptr(data), nbytes, first_word, C.byref(out), _stream_handle(stream)))
     return out.value
+
+
+def cf_op_checksum_noalloc(data, nbytes, first_word, dev_out, stream=None) -> None:
+    """Checksum of a device byte range into a device uint64 (torch int64 tensor of one element);
+    enqueues only: the caller synchronises before reading dev_out."""
+    _check(lib().cf_op_checksum_noalloc(_ptr(data), nbytes, first_word, _ptr(dev_out), _stream_handle(stream)))

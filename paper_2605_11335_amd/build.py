@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libchunkflow.so")
-SOURCES = ["chunkflow.hip", "simulate.hip", "gemm.hip", "attention.hip", "elementwise.hip"]
+SOURCES = ["chunkflow.hip", "simulate.hip", "gemm.hip", "attention.hip", "elementwise.hip", "checksum_noalloc.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-pthread",
          # packed-fp32 VALU forms are kept out of every kernel
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -58,3 +58,11 @@ __device__ __forceinline__ float gelu_erf_f32(float x) {
     const float e = 1.0f - poly * exp2f(-1.4426950408889634f * z * z);       // erf(|x| / sqrt 2)
     return 0.5f * x + 0.5f * fabsf(x) * e;                                    // 0.5 x (1 + sign(x) e)
 }
+
+// splitmix64's output function: the per-word mixer of the streamed-bytes checksum.
+__device__ __forceinline__ uint64_t cf_mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+constexpr uint64_t CF_GOLDEN64 = 0x9E3779B97F4A7C15ull;

@@ -391,12 +391,6 @@ __global__ __launch_bounds__(256) void attn_gather_kernel(const bf16* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t mix64(uint64_t z) {
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
 __global__ __launch_bounds__(256) void zero_u64_kernel(uint64_t* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0; }
 
 // sum over 64-bit words of mix(word ^ (index+1)*GOLDEN), index counted from the blob start
@@ -404,7 +398,7 @@ __global__ __launch_bounds__(256) void checksum_kernel(const uint64_t* __restric
                                                        unsigned long long* __restrict__ out) {
     uint64_t acc = 0;
     for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (uint64_t)gridDim.x * 256)
-        acc += mix64(w[i] ^ ((first_word + i + 1) * 0x9E3779B97F4A7C15ull));
+        acc += cf_mix64(w[i] ^ ((first_word + i + 1) * CF_GOLDEN64));
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         const uint32_t lo = __shfl_xor((uint32_t)acc, o), hi = __shfl_xor((uint32_t)(acc >> 32), o);

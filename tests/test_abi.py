@@ -226,3 +226,15 @@ def test_linear_tile_shapes():
     assert B.cf_plan_linear(64, 64) == 128                       # one tile either way: the small one
     with pytest.raises(B.ChunkflowError):
         B.cf_plan_linear(0, 64)
+
+
+def test_no_alloc_checksum_rejects_oversize_and_misaligned_requests_before_touching_a_gpu():
+    """The argument checks of cf_op_checksum_noalloc come before any HIP call: a request beyond what
+    its fixed partial-sum array covers (1 GiB) is an argument error with a message that says so."""
+    lib = B.lib()
+    fake = C.c_void_p(4096)             # never dereferenced: the call must fail on its arguments
+    assert lib.cf_op_checksum_noalloc(fake, (1 << 30) + 8, 0, fake, None) == B.CF_ERR_ARG
+    assert b"exceed" in lib.cf_last_error(None)
+    assert lib.cf_op_checksum_noalloc(fake, 12, 0, fake, None) == B.CF_ERR_ARG
+    assert lib.cf_op_checksum_noalloc(fake, 8, 0, None, None) == B.CF_ERR_ARG
+    assert lib.cf_op_checksum_noalloc(C.c_void_p(4097), 8, 0, fake, None) == B.CF_ERR_ARG
