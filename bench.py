@@ -7,6 +7,11 @@ blocks of the configuration, in steady state (the prefetch of block 0 for the ne
 during the last block).  Two arms are timed with the same kernels: fully resident (r = 1) and
 chunked offload (r = --resident, default 0 = every weight byte streamed from pinned host memory).
 
+Headline workload (no --config): the HunyuanVideo-like large-workload share, all 20 double-stream
+blocks with distinct seeded weights -- the regime in which the prefetch has to hide (Sec. 4.2).  The
+Flux-like small-workload share (8 blocks) and the Wan-like share (30 DiT blocks) are measured in
+the same run and carried as `other_workloads` of the same JSON line.
+
 Prints ONE JSON line: the offloaded step time as `value`, the resident step time beside it, the
 roofline of the dominant kernel (measured with HIP events on the compute stream, per launch) and
 the CPU oracle timed on this host's cores.
@@ -32,6 +37,7 @@ PEAK_LINK_GBS = 64.0           # PCIe Gen5 x16, one direction
 TRAFFIC = {("flux", "gemm_lin1/256x256"): 607860396,      # profiles/hbm_traffic_flux_kernels.md
            ("flux", "gemm_lin2/128x128"): 528712950,
            ("flux", "attention"): 66201452}
+HEADLINE = "hunyuan"
 
 
 def parse():
@@ -39,7 +45,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", default="flux", choices=["toy", "flux", "wan", "hunyuan", "flux_mm", "hunyuan_mm", "toy_mm"])
+    ap.add_argument("--config", default=None, help="one workload only (default: the headline workload plus the others as sub-records)", choices=["toy", "flux", "wan", "hunyuan", "flux_mm", "hunyuan_mm", "toy_mm"])
     ap.add_argument("--blocks", type=int, default=0, help="override the number of blocks (0 = the config's)")
     ap.add_argument("--shared-weights", action="store_true",
                     help="one seeded host blob per block kind, registered for every block of that kind: lets the full "
@@ -56,6 +62,9 @@ def parse():
                     help="vary the sequence length of the config (frames for wan, image tokens for flux) and locate "
                          "the workload at which the prefetch becomes hidden (Eq. 3-4); prints its own JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="headline workload only, no sub-records")
+    ap.add_argument("--profile-steps", type=int, default=0,
+                    help="steps of the pass that times every kernel with an event pair (0: --steps, at most 3 on the video shares)")
     ap.add_argument("--only", choices=["both", "resident", "offload"], default="both")
     return ap.parse_args()
 
@@ -190,40 +199,59 @@ def scale_sweep(args):
     print(json.dumps(out))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    if args.scale_sweep:
-        return scale_sweep(args)
+def gen_params_parallel(cfg, blocks, wl, workers=8):
+    """Seeded weights of several blocks, drawn tensor by tensor on a few host threads (NumPy's
+    generators fill large arrays without holding the interpreter lock).  Same values as
+    workload.gen_block_params: each tensor has its own counter-based stream."""
+    from concurrent.futures import ThreadPoolExecutor
+    jobs = [(b, spec) for b in blocks for spec in wl.param_specs(cfg.block_cfg(b))]
+    def draw(job):
+        b, (name, shape, std, mean) = job
+        return b, name, wl.normal_bf16(cfg.name, b, name, shape, std, mean)
+    out = {b: {} for b in blocks}
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        for b, name, arr in ex.map(draw, jobs):
+            out[b][name] = arr
+    return out
+
+
+def measure(args, name, steps, warmup, *, blocks=0, shared_weights=False, shared_inputs=False, prof_steps=0,
+            cpu_baseline=True, sweeps=False, streams=None):
+    """Both arms of one workload; returns the fields of the JSON line that describe it."""
     import numpy as np
     import torch
     import workload as wl
     from paper_2605_11335_amd.runner import BlockRunner, chunk_bytes_for
 
-    cfg = wl.CONFIGS[args.config].with_(batch=max(1, args.batch))
-    if cfg.n_double and cfg.n_blocks > 12 and not args.blocks and not args.shared_weights:
-        args.blocks = 6          # the full MMDiT stack holds 24 GB of distinct seeded weights; keep its 1:2 mix
-    if args.blocks:
+    cfg = wl.CONFIGS[name].with_(batch=max(1, args.batch))
+    if cfg.n_double and cfg.n_blocks > 12 and not blocks and not shared_weights:
+        blocks = 6               # the full MMDiT stack holds 24 GB of distinct seeded weights; keep its 1:2 mix
+    if blocks:
         # a mixed stack keeps its proportion of double-stream blocks
-        cfg = cfg.with_(n_blocks=args.blocks,
-                        n_double=(max(1, round(args.blocks * cfg.n_double / cfg.n_blocks)) if cfg.n_double else 0))
+        cfg = cfg.with_(n_blocks=blocks,
+                        n_double=(max(1, round(blocks * cfg.n_double / cfg.n_blocks)) if cfg.n_double else 0))
     L = cfg.n_blocks
     chunk_bytes = int(args.chunk_mib * (1 << 20)) if args.chunk_mib else chunk_bytes_for(cfg)
+    video = cfg.n_total > 8192
+    prof_steps = prof_steps or (min(steps, 3) if video else steps)
+    prof_warmup = min(warmup, 1) if video else warmup
 
     t_setup = time.perf_counter()
-    run = BlockRunner(cfg, chunk_bytes=chunk_bytes)
+    run = BlockRunner(cfg, chunk_bytes=chunk_bytes, streams=streams)
     first_of_kind = {}
     for b in range(L):
-        k = cfg.kind_of(b)
-        if args.shared_weights and k in first_of_kind:
-            run.register_blob(b, run.blobs[first_of_kind[k]])
-        else:
-            run.register_params(b, wl.gen_block_params(cfg.block_cfg(b), b))
-            first_of_kind.setdefault(k, b)
-    if args.shared_weights:
-        # activations too: one seeded set of inputs per kind (peer tensors of a video share are 0.5 GB each)
+        first_of_kind.setdefault(cfg.kind_of(b), b)
+    own = [b for b in range(L) if not shared_weights or first_of_kind[cfg.kind_of(b)] == b]
+    # distinct seeded weights, a few blocks at a time so that the unpacked tensors never pile up
+    for i in range(0, len(own), 4):
+        for b, params in gen_params_parallel(cfg, own[i:i + 4], wl).items():
+            run.register_params(b, params)
+    for b in range(L):
+        if b not in own:
+            run.register_blob(b, run.blobs[first_of_kind[cfg.kind_of(b)]])
+    if shared_weights or shared_inputs:
+        # one seeded set of inputs per kind (peer tensors of a video share are 0.2-0.5 GB each); the
+        # residual stream is chained through the blocks either way
         per_kind = {k: run.make_io(wl.gen_block_inputs(cfg.block_cfg(b), b)) for k, b in first_of_kind.items()}
         tens = [dict(per_kind[cfg.kind_of(b)]) for b in range(L)]
     else:
@@ -233,7 +261,7 @@ def main():
     blob_total = run.total_blob_bytes                      # weight bytes of the whole stack
     print(f"[bench] {cfg.name}: {L} blocks, blobs {blob_total/1e6:.1f} MB in all, chunks of "
           f"{chunk_bytes/1e6:.2f} MB ({[run.ctx.cf_n_chunks(b) for b in range(L)]} per block), "
-          f"setup {time.perf_counter()-t_setup:.1f}s", file=sys.stderr)
+          f"setup {time.perf_counter()-t_setup:.1f}s", file=sys.stderr, flush=True)
 
     comm_host = None
     def set_contention(mode):
@@ -247,11 +275,11 @@ def main():
             comm_host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
         run.ctx.cf_set_contention(run.comm, comm_host, nbytes, mode == "pause")
 
-    def arm(r, steps, warmup):
+    def arm(r, n_steps, n_warmup):
         actual = run.ctx.set_resident_fraction(r)
         run.ctx.cf_stats_reset()
         run.begin(0)
-        ms = time_steps(run, ios, steps, warmup, torch)
+        ms = time_steps(run, ios, n_steps, n_warmup, torch)
         st = run.ctx.cf_stats()
         run.fwd(0, ios[0])                         # consume the pending prefetch
         run.ctx.cf_sync()
@@ -288,24 +316,26 @@ def main():
                 "other_ms": step_ms - comp - waits["prefetch_stall"] - waits["collective_wait"]}
 
     set_contention(args.contention)
-    total_steps = args.steps + args.warmup
+    total_steps = steps + warmup
+    prof_total = prof_steps + prof_warmup
     do_res, do_off = args.only in ("both", "resident"), args.only in ("both", "offload")
     res_ms = off_ms = None
     kt_res, kt_off, st, actual_r = [], [], None, None
     if do_res:
         # resident arm: timed without event pairs, then once more with a hipEvent pair around
         # every kernel launch on the compute stream (the per-kernel table and the roofline)
-        res_ms, _, _ = arm(1.0, args.steps, args.warmup)
+        res_ms, _, _ = arm(1.0, steps, warmup)
         run.ctx.cf_kernel_times_reset()
         run.ctx.cf_set_profiling(True)
-        res_prof_ms, _, _ = arm(1.0, args.steps, args.warmup)
+        res_prof_ms, _, _ = arm(1.0, prof_steps, prof_warmup)
         kt_res = run.ctx.cf_kernel_times()
         run.ctx.cf_set_profiling(False)
+        print(f"[bench] {cfg.name}: resident {res_ms:.3f} ms/step", file=sys.stderr, flush=True)
     if do_off:
-        off_ms, actual_r, st = arm(args.resident, args.steps, args.warmup)
+        off_ms, actual_r, st = arm(args.resident, steps, warmup)
         run.ctx.cf_kernel_times_reset()
         run.ctx.cf_set_profiling(True)
-        off_prof_ms, _, _ = arm(args.resident, args.steps, args.warmup)
+        off_prof_ms, _, _ = arm(args.resident, prof_steps, prof_warmup)
         kt_off = run.ctx.cf_kernel_times()
         run.ctx.cf_set_profiling(False)
         h2d_per_step = st["model_blob_bytes"] - st["model_resident_bytes"]
@@ -314,30 +344,33 @@ def main():
         first = run.blob_bytes_of[0] - min(run.blob_bytes_of[0], n_res0 * chunk_bytes)
         assert st["h2d_bytes"] == total_steps * h2d_per_step + first, "I/O volume changed"
         h2d_gbs = h2d_per_step / (off_ms * 1e-3) / 1e9
+        print(f"[bench] {cfg.name}: chunked offload {off_ms:.3f} ms/step", file=sys.stderr, flush=True)
     else:
         h2d_per_step, h2d_gbs = 0, 0.0
 
     is_mfma = lambda k: k["flops"] > 0 and not k["name"].startswith("modvec")
     kt_main = kt_res if do_res else kt_off
     arm_name = "resident" if do_res else "offload"
-    # each arm ran total_steps steps plus one drain block: FLOPs per step from the counters
-    total_flops = sum(k["flops"] for k in kt_main if is_mfma(k)) * L / (total_steps * L + 1)
+    # the profiled arm ran prof_total steps plus one drain block: FLOPs per step from the counters
+    total_flops = sum(k["flops"] for k in kt_main if is_mfma(k)) * L / (prof_total * L + 1)
     dom = max([k for k in kt_main if is_mfma(k)], key=lambda k: k["total_ms"])
     dom_ms = dom["total_ms"] / dom["launches"]
     dom_flops = dom["flops"] / dom["launches"]
     value = off_ms if do_off else res_ms
 
+    weights_note = ("one seeded blob per block kind, registered for every block of that kind" if shared_weights
+                    else "distinct seeded weights per block")
+    inputs_note = ("one seeded set of activations and peer tensors per block kind, residual stream chained"
+                   if (shared_weights or shared_inputs) else "distinct seeded inputs per block, residual stream chained")
     result = {
-        "metric": "denoise step ms (chunked offload vs resident)",
-        "value": value, "unit": "ms", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": value, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "value": value, "unit": "ms", "steps": steps, "warmup": warmup, "ms_per_step": value,
         "config": {"workload": f"{cfg.name}: {L} blocks" + (f" ({cfg.n_double} double-stream + {L - cfg.n_double} single-stream)" if cfg.n_double else "") + f", d={cfg.d}, H={cfg.n_heads}x{cfg.head_dim}, f={cfg.f}, "
                                f"N={cfg.n_total}, Ulysses P={cfg.sp_degree} share (GEMMs on {cfg.n_local} tokens, "
                                f"attention {cfg.h_local} heads over {cfg.n_total})" + (f", batch {cfg.batch}" if cfg.batch > 1 else ""),
                    "arm": "chunked offload" if do_off else "resident",
                    "chunk_bytes": chunk_bytes, "chunks_per_block": run.n_chunks, "blob_bytes": run.blob_bytes,
-                   "blob_bytes_all_blocks": blob_total, "shared_weights": bool(args.shared_weights),
+                   "blob_bytes_all_blocks": blob_total, "shared_weights": bool(shared_weights),
+                   "weights": weights_note, "inputs": inputs_note,
                    "resident_fraction": actual_r if do_off else 1.0, "contention": args.contention},
         "offload_ms": off_ms, "resident_ms": res_ms,
         "offload_over_resident": (off_ms / res_ms) if (do_res and do_off) else None,
@@ -354,21 +387,23 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": dom_flops / dom_ms / 1e9 / PEAK_BF16_TFLOPS,
                      "avg_launch_ms": dom_ms, "flops_per_launch": dom_flops, "launches": dom["launches"],
                      "traffic": TRAFFIC.get((cfg.name, dom["name"]))},
-        "kernels_resident_arm": table(kt_res, total_steps), "kernels_offload_arm": table(kt_off, total_steps),
-        "breakdown_resident_arm": breakdown(kt_res, total_steps, res_prof_ms) if do_res else None,
-        "breakdown_offload_arm": breakdown(kt_off, total_steps, off_prof_ms) if do_off else None,
+        "profiled_steps": prof_steps,
+        "kernels_resident_arm": table(kt_res, prof_total), "kernels_offload_arm": table(kt_off, prof_total),
+        "breakdown_resident_arm": breakdown(kt_res, prof_total, res_prof_ms) if do_res else None,
+        "breakdown_offload_arm": breakdown(kt_off, prof_total, off_prof_ms) if do_off else None,
     }
 
     # ---- overlap-model view of this machine (Eq. 1-4 with the measured eta's)
     blob = blob_total / L                 # per block, averaged over the stack (App. B, block-averaged)
     t_comp_blk = (res_ms if do_res else off_ms) / L
     t_pref_blk = (blob / (h2d_gbs * 1e9) * 1e3) if h2d_gbs > 0 else None
-    result["model"] = {"t_comp_block_ms": t_comp_blk, "t_pref_block_ms": t_pref_blk,
-                       "hidden": (t_pref_blk is not None and t_comp_blk >= t_pref_blk),
+    result["model"] = {"t_comp_block_ms": t_comp_blk, "t_pref_block_ms_at_measured_rate": t_pref_blk,
+                       "t_pref_block_ms_at_link_peak": blob / (PEAK_LINK_GBS * 1e9) * 1e3,
+                       "hidden": bool(do_res and do_off and off_ms <= 1.05 * res_ms),
                        "i_block_flop_per_byte": total_flops / L / blob,
                        "i_star_flop_per_byte": (total_flops / L / (t_comp_blk * 1e-3)) / (h2d_gbs * 1e9) if h2d_gbs else None}
 
-    if args.sweep:
+    if sweeps:
         grid = []
         link = None                       # H2D rate of the fully offloaded, uncontended point
         # per-kind block compute time for the chunk-level model
@@ -379,7 +414,7 @@ def main():
             base_ms = None                # r = 1 step time of this contention mode
             pts = []
             for r in (1.0, 0.75, 0.5, 0.25, 0.0):
-                ms, act, s2 = arm(r, args.steps, max(2, args.warmup))
+                ms, act, s2 = arm(r, steps, max(2, warmup))
                 pts.append((r, ms, act, s2))
                 if r == 1.0:
                     base_ms = ms
@@ -401,7 +436,7 @@ def main():
         # the dial (Sec. 3.3): fastest resident fraction under a weight-memory budget, then measured
         budget = int(args.tune_budget_frac * blob_total)
         choice = run.ctx.cf_tune(t_comp, link / 1e9, [chunk_bytes], 16, memory_budget_bytes=budget)
-        ms, act, s2 = arm(choice["r"], args.steps, max(2, args.warmup))
+        ms, act, s2 = arm(choice["r"], steps, max(2, warmup))
         result["tune"] = {"budget_bytes": budget, "t_comp_ms_per_block": t_comp, "link_gbs": link / 1e9,
                           "chosen_r": choice["r"], "feasible": choice["feasible"],
                           "predicted_step_ms": choice["step_ms"], "measured_step_ms": ms,
@@ -409,30 +444,75 @@ def main():
                           "measured_weight_memory_bytes": s2["weight_memory_bytes"]}
         print("[tune] " + json.dumps(result["tune"]), file=sys.stderr)
 
-    # ---- CPU oracle on this host, bounded sample: one full-size block
-    if not args.no_cpu_baseline:
+    streams_used = (run.compute, run.copy, run.comm)
+    run.close()
+    del run, tens, bufs, ios
+    torch.cuda.empty_cache()
+
+    # ---- CPU oracle on this host, bounded sample (the GPU is idle meanwhile)
+    if cpu_baseline:
         from oracle import block as ob
         import threadpoolctl
         rows = None
         sample = "1 full block of each kind"
-        if cfg.n_total > 8192:                    # exact row sample: attention would take hours
+        n_rows = 0
+        if video:                                 # exact row sample: full attention would take hours
+            # a few hundred rows keep the sample to some tens of seconds: K and V of all tokens are always built
+            n_rows = 256
             rng = np.random.default_rng(1)
-            rows = np.sort(rng.choice(cfg.n_local, 256, replace=False))
-            sample = "256 of %d local rows of 1 block (all keys), scaled by rows" % cfg.n_local
-        scale = 1.0 if rows is None else cfg.n_local / 256.0
+            rows = np.sort(rng.choice(cfg.n_local, n_rows, replace=False))
+            sample = "%d of %d local rows of 1 block (keys and values of all %d tokens)" % (n_rows, cfg.n_local, cfg.n_total)
         total = 0.0
+        measured = 0.0
         for b in sorted({cfg.kinds.index(k) for k in set(cfg.kinds)}):      # first block of each kind
             cb = cfg.block_cfg(b).with_(batch=1)          # one sample; a batch is that many independent samples
             params, inputs = wl.gen_block_params(cb, b), wl.gen_block_inputs(cb, b)
             t0 = time.perf_counter()
             ob.block_forward(cb, params, inputs, rows=rows, send_rows=(None if rows is None else np.arange(0)))
-            total += (time.perf_counter() - t0) * cfg.kinds.count(cb.kind) * cfg.batch
+            dt = time.perf_counter() - t0
+            measured += dt
+            total += dt * cfg.kinds.count(cb.kind) * cfg.batch
         threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+        scale = 1.0 if rows is None else cfg.n_local / float(n_rows)
         result["cpu_baseline"] = {"value": total * 1e3 * scale, "unit": "ms", "cores": threads, "kind": "oracle",
+                                  "measured_s": measured,
                                   "sample": f"{sample}, float64 NumPy, times the number of blocks of that kind per step"
-                                            + ("" if rows is None else " (linear extrapolation)")}
-    run.close()
-    print(json.dumps(result))
+                                            + ("" if rows is None else
+                                               f"; row-sample extrapolation: measured time x {cfg.n_local}/{n_rows} rows, which "
+                                               "overstates the share of the key/value projections that every row shares")}
+    return result, streams_used
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding): use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if args.scale_sweep:
+        args.config = args.config or "flux"
+        return scale_sweep(args)
+    contract = {"metric": "denoise step ms (chunked offload vs resident)", "n_gpus": 1, "higher_is_better": False,
+                "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+    if args.config:
+        res, _ = measure(args, args.config, args.steps, args.warmup, blocks=args.blocks, shared_weights=args.shared_weights,
+                         prof_steps=args.profile_steps, cpu_baseline=not args.no_cpu_baseline, sweeps=args.sweep)
+        print(json.dumps({**contract, **res}))
+        return
+    # Headline: the large-workload share with all its blocks; K timed steps per arm as asked.
+    res, streams = measure(args, HEADLINE, args.steps, args.warmup, blocks=args.blocks, shared_weights=args.shared_weights,
+                           shared_inputs=True, prof_steps=args.profile_steps, cpu_baseline=not args.no_cpu_baseline)
+    out = {**contract, **res}
+    if not args.no_others:
+        others = {}
+        # the small-workload regime (link-bound by construction: the memory-latency curve lives here) and
+        # the Wan-like share; the same three streams serve every runner (hardware queues are few)
+        r2, _ = measure(args, "flux", args.steps, args.warmup, cpu_baseline=False, streams=streams)
+        others["flux"] = r2
+        r3, _ = measure(args, "wan", min(args.steps, 8), min(args.warmup, 2), shared_weights=True, cpu_baseline=False,
+                        streams=streams)
+        others["wan"] = r3
+        out["other_workloads"] = others
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":
