@@ -67,14 +67,18 @@ class cf_tune_choice(C.Structure):
     _fields_ = [("chunk_bytes", C.c_uint64), ("r", C.c_double), ("feasible", C.c_int32), ("sim", cf_sim_result)]
 
 
-#: every symbol include/chunkflow.h declares
-EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_chunks", "cf_blob_layout",
-           "cf_set_block_kinds", "cf_block_kind_of", "cf_blob_bytes_of", "cf_n_chunks_of", "cf_blob_layout_of",
-           "cf_workspace_bytes", "cf_plan_panels", "cf_plan_attention", "cf_plan_linear", "cf_simulate", "cf_tune", "cf_register_block", "set_resident_fraction", "chunked_prefetch_begin",
-           "chunked_prefetch_wait", "dit_block_fwd", "cf_set_contention", "cf_comm_begin", "cf_comm_end",
-           "cf_checksum_block", "cf_read_block", "cf_stats", "cf_stats_reset", "cf_set_profiling", "cf_set_adaptive_waits",
-           "cf_kernel_times", "cf_kernel_times_reset", "cf_sync", "cf_op_linear", "cf_op_linear_residual",
-           "cf_op_attention", "cf_op_ln_modulate", "cf_op_modvec", "cf_op_mfma_rate", "cf_op_checksum", "cf_op_checksum_noalloc"]
+#: what include/chunkflow.h declares: the block path's contract
+CORE_EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf_n_chunks", "cf_blob_layout",
+                "cf_set_block_kinds", "cf_block_kind_of", "cf_blob_bytes_of", "cf_n_chunks_of", "cf_blob_layout_of",
+                "cf_workspace_bytes", "cf_plan_panels", "cf_simulate", "cf_tune", "cf_register_block",
+                "set_resident_fraction", "chunked_prefetch_begin", "chunked_prefetch_wait", "dit_block_fwd",
+                "cf_set_contention", "cf_comm_begin", "cf_comm_end", "cf_checksum_block", "cf_read_block", "cf_stats",
+                "cf_stats_reset", "cf_set_profiling", "cf_set_adaptive_waits", "cf_kernel_times", "cf_kernel_times_reset",
+                "cf_sync", "cf_op_checksum", "cf_op_checksum_noalloc"]
+#: what include/chunkflow_diag.h declares: single-kernel hooks, planner views, the matrix-core rate probe
+DIAG_EXPORTS = ["cf_plan_attention", "cf_plan_linear", "cf_op_linear", "cf_op_linear_residual", "cf_op_attention",
+                "cf_op_ln_modulate", "cf_op_modvec", "cf_op_mfma_rate"]
+EXPORTS = CORE_EXPORTS + DIAG_EXPORTS
 
 _lib = None
 

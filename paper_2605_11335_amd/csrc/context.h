@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/chunkflow.h"
+#include "../../include/chunkflow_diag.h"
 #include "kernels.h"
 
 struct TensorDesc {
@@ -28,6 +29,14 @@ struct ProfEntry {
 };
 
 enum { SLOT_EMPTY = 0, SLOT_FILLED = 1, SLOT_CONSUMED = 2 };
+
+// A collective announced by cf_comm_begin that the prefetch worker has not yet seen finished (Sec. 3.2):
+// `ready` fires when the compute stream reaches the collective, `done` when the collective has finished.
+struct PendingComm {
+    hipEvent_t ready, done;
+    bool done_recorded;     // cf_comm_end has recorded `done` on the collective's stream
+    bool handled;           // the copy stream has already been parked on `done`
+};
 
 struct PrefetchJob {
     int block;
@@ -71,13 +80,13 @@ struct cf_ctx {
     int slot_state[2] = {SLOT_EMPTY, SLOT_EMPTY};
     std::vector<hipEvent_t> chunk_ev[2];
     hipEvent_t done_ev[2] = {nullptr, nullptr};
-    bool done_valid[2] = {false, false};
+    std::atomic<bool> done_valid[2] = {{false}, {false}};     // read by the prefetch worker
     int waited_upto = -1;               // highest chunk the current forward already waited for
     // One wait per block when the prefetch is hidden anyway: land_ev[s] follows the last chunk copy into
     // slot s; comparing it with the end of the block that ran before the slot's tenant tells whether that
     // tenant's weights had landed before it started (Sec. 3.1: T_pref <= T_comp), per block kind.
     hipEvent_t land_ev[2] = {nullptr, nullptr};
-    bool land_valid[2] = {false, false};
+    std::atomic<bool> land_valid[2] = {{false}, {false}};     // written by the prefetch worker
     uint64_t fwd_seq = 0, slot_fwd_seq[2] = {0, 0};   // order of the forwards that recorded done_ev[s]
     bool adaptive_waits = true;
     bool hidden_kind[3] = {false, false, false};
@@ -88,14 +97,20 @@ struct cf_ctx {
     uint8_t* comm_dev = nullptr;
     uint64_t comm_bytes = 0;
     bool pause_resume = false;
-    hipEvent_t comm_ready_ev = nullptr, comm_done_ev = nullptr;
+    int pause_depth = 1;                // chunk copies the worker keeps enqueued ahead of the link in pause/resume mode
+    hipEvent_t comm_ready_ev = nullptr, comm_done_ev = nullptr;   // the one pair used without pause/resume
+    hipEvent_t cur_ready = nullptr, cur_done = nullptr;           // the pair of the collective being issued
+    std::deque<PendingComm> comm_pending;      // guarded by mu; oldest first
+    std::vector<hipEvent_t> comm_ev_pool;      // guarded by mu; events of retired collectives
+    // Host run-ahead bound while collectives are emulated: forward n is enqueued once forward n-2 has finished.
+    hipEvent_t fwd_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    uint64_t fwd_count = 0;
 
     std::thread worker;
     std::mutex mu;
     std::condition_variable cv;
     std::deque<PrefetchJob> jobs;
     bool worker_stop = false, worker_busy = false;
-    bool pause_flag = false;            // guarded by mu: a collective was issued, done event recorded
     int enq_count[2] = {0, 0};          // chunks of the slot's tenant whose copy has been enqueued
     std::string worker_err;
 

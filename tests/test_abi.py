@@ -18,10 +18,15 @@ from paper_2605_11335_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def header_functions():
-    text = open(os.path.join(ROOT, "include", "chunkflow.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return re.findall(r"^\s*(?:int|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+def header_functions(name=None):
+    """Functions declared by include/<name> (every header of include/ when no name is given)."""
+    inc = os.path.join(ROOT, "include")
+    names = []
+    for h in sorted(os.listdir(inc)) if name is None else [name]:
+        text = open(os.path.join(inc, h)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"^\s*(?:int|const char\*)\s+(\w+)\s*\(", text, flags=re.M)
+    return names
 
 
 def test_library_exports_every_declared_symbol():
@@ -31,6 +36,11 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(names) == sorted(B.EXPORTS)
+    # the block path's contract and the diagnostics are separate headers
+    core, diag = header_functions("chunkflow.h"), header_functions("chunkflow_diag.h")
+    assert sorted(core) == sorted(B.CORE_EXPORTS) and sorted(diag) == sorted(B.DIAG_EXPORTS)
+    assert not any(n.startswith("cf_op_") or n in ("cf_plan_attention", "cf_plan_linear") for n in core
+                   if not n.startswith("cf_op_checksum"))
 
 
 def ctx_for(cfg, chunk):
