@@ -12,9 +12,15 @@
  *   - The caller owns all host blobs and all device tensors it passes in.  The library owns its
  *     context, its events, the two staging slots, the per-block resident buffers and (when the
  *     pause/resume worker is enabled) one host thread.  Nothing is freed behind the caller's back.
- *   - Streams are hipStream_t handles passed as void*.  Calls only enqueue work unless stated;
- *     no call blocks the host except cf_sync, cf_destroy, set_resident_fraction,
- *     cf_checksum_block, cf_kernel_times and the bounded waits of the prefetch worker.
+ *   - Streams are hipStream_t handles passed as void*.  Calls only enqueue work unless stated.
+ *     Calls that block the host until the GPU is idle: cf_sync, cf_destroy, set_resident_fraction,
+ *     cf_set_contention, cf_checksum_block, cf_op_checksum, cf_read_block, cf_kernel_times.
+ *     Calls that may block the host for a bounded time, to keep it at most one block forward ahead of
+ *     the GPU: chunked_prefetch_begin (whenever it has chunks to copy) and dit_block_fwd (while
+ *     emulated collectives are enabled); each waits for the block forward issued two forwards earlier.
+ *     The prefetch worker of pause/resume mode is a host thread of the library's own; it never blocks
+ *     the caller except inside dit_block_fwd, which waits until the worker has enqueued the chunk a
+ *     layer needs.
  *   - bf16 tensors are uint16_t bit patterns.  The residual stream (x in, y out) is fp32.
  *   - A context is not thread-safe; use it from one host thread.
  */
@@ -223,7 +229,10 @@ int set_resident_fraction(cf_ctx* ctx, double r, double* actual);
  * copy_stream and the compute stream must run concurrently: HIP multiplexes streams onto a few
  * hardware queues (4 by default), in creation order, and two streams that land on the same queue
  * execute one after the other -- the prefetch then hides behind nothing.  A process that creates
- * many streams should create these two back to back, or reuse one pair. */
+ * many streams should create these two back to back, or reuse one pair.
+ * Host wait: before enqueueing, the call waits (hipEventSynchronize) for the block forward that last
+ * used the OTHER slot, i.e. the forward issued two forwards ago, so that the host never runs more than
+ * one block ahead of the GPU; with everything resident it returns at once. */
 int chunked_prefetch_begin(cf_ctx* ctx, int32_t block, void* copy_stream);
 
 /* ---- Sec. 2.2 step 1, at chunk granularity: make compute_stream wait (on the GPU) until chunk
@@ -234,15 +243,24 @@ int chunked_prefetch_wait(cf_ctx* ctx, int32_t block, int32_t chunk, void* compu
 /* ---- Sec. 2.2 step 2: enqueue the forward pass of `block` on compute_stream.  Each kernel that
  * reads weights is preceded by the wait for the last chunk it needs, and the GEMMs are launched
  * as panels of output features per chunk, so compute starts before the whole layer has landed.
- * Marks the staging slot reusable when the block's last kernel finishes (step 4). */
+ * Marks the staging slot reusable when the block's last kernel finishes (step 4); a forward that
+ * returns an error after it began enqueueing releases the slot as well, behind what it enqueued.
+ * Host waits: in pause/resume mode, for the worker thread to have enqueued each chunk a layer is about
+ * to wait for; while emulated collectives are enabled, for the forward issued two forwards earlier. */
 int dit_block_fwd(cf_ctx* ctx, int32_t block, const cf_block_io* io, void* compute_stream);
 
 /* ---- Sec. 3.2 pause/resume.  cf_set_contention enables, per block forward, four emulated
  * collectives (q,k,v before attention, o after), each moving `bytes_per_collective` split half
  * host->device / half device->host on comm_stream through host_pinned / a device buffer the
- * library owns; the compute stream waits for each.  With pause_resume != 0 a prefetch worker
- * thread enqueues chunks with at most 2 in flight and, when a collective is in progress, makes
- * the copy stream wait for its completion event before the next chunk.  comm_stream NULL disables. */
+ * library owns; the compute stream waits for each.  comm_stream NULL disables.
+ * pause_resume = 0: chunk copies are enqueued by chunked_prefetch_begin as without collectives.
+ * pause_resume = 1 or 2: a prefetch worker thread enqueues the chunks, keeping that many copies ahead
+ * of the link (1: a chunk is enqueued when the one before it has landed, so a collective never waits
+ * for more than the chunk on the link, the bound of Sec. 3.2; 2: one more copy queued behind it, which
+ * closes the gap between copies and doubles the bound).  Before each chunk the worker looks at the
+ * oldest unfinished collective: if the compute stream has reached it (GPU time, not host enqueue time),
+ * the copy stream is made to wait for that collective's completion event -- once per collective;
+ * cf_stats().pauses counts these.  Blocks the host until the GPU is idle (it changes streams' roles). */
 int cf_set_contention(cf_ctx* ctx, void* comm_stream, void* host_pinned, uint64_t host_bytes,
                       uint64_t bytes_per_collective, int32_t pause_resume);
 /* The same two hooks for a caller that issues its own collective on comm_stream between them. */

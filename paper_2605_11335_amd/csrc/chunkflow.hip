@@ -171,6 +171,7 @@ int ensure_device(cf_ctx* c) {
     }
     CF_HIP(c, hipEventCreateWithFlags(&c->comm_ready_ev, hipEventDisableTiming));
     CF_HIP(c, hipEventCreateWithFlags(&c->comm_done_ev, hipEventDisableTiming));
+    for (auto& e : c->fwd_ev) CF_HIP(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
     c->device_ready = true;
     return CF_OK;
 }
@@ -220,18 +221,43 @@ WView view_of(const cf_ctx* c, int block) {
 // prefetch worker (Sec. 3.2): enqueues chunk copies with at most 2 in flight and, when a
 // collective has been issued, parks the copy stream on that collective's completion event
 // ------------------------------------------------------------------------------------------
+// Pause decision of the prefetch worker, taken before each chunk copy is enqueued (Sec. 3.2: the flag is
+// checked at chunk boundaries).  A collective counts as issued once the compute stream has reached it in
+// GPU time (its `ready` event has fired), not when the host enqueued it: the host runs a block ahead of the
+// GPU.  The copy stream is then parked on the collective's completion event, once per collective; the chunk
+// already on the link finishes first, which is the residual stall the paper bounds by one chunk's service
+// time (with pause_depth = 1 no further chunk is queued behind it).  Called with c->mu held.
+int pause_if_collective_running(cf_ctx* c, hipStream_t copy, std::unique_lock<std::mutex>& lk) {
+    while (!c->comm_pending.empty()) {
+        PendingComm& p = c->comm_pending.front();
+        if (!p.done_recorded || hipEventQuery(p.done) != hipSuccess) break;
+        c->comm_ev_pool.push_back(p.ready);
+        c->comm_ev_pool.push_back(p.done);
+        c->comm_pending.pop_front();
+    }
+    (void)hipGetLastError();                          // hipErrorNotReady of a query is not an error
+    if (c->comm_pending.empty()) return CF_OK;
+    PendingComm& p = c->comm_pending.front();
+    if (p.handled || hipEventQuery(p.ready) != hipSuccess) { (void)hipGetLastError(); return CF_OK; }
+    // the caller is between cf_comm_begin and cf_comm_end: its completion event is recorded within microseconds
+    c->cv.wait_for(lk, std::chrono::milliseconds(200), [&] { return c->comm_pending.front().done_recorded || c->worker_stop; });
+    PendingComm& q = c->comm_pending.front();
+    if (!q.done_recorded) return CF_OK;               // cf_comm_end never came: nothing to wait for
+    CF_HIP(c, hipStreamWaitEvent(copy, q.done, 0));
+    q.handled = true;
+    c->stats.pauses++;
+    return CF_OK;
+}
+
 int enqueue_block_copies(cf_ctx* c, int block, int s, hipStream_t copy, bool bounded) {
     const Plan& p = c->P(block);
     if (c->done_valid[s]) CF_HIP(c, hipStreamWaitEvent(copy, c->done_ev[s], 0));   // slot's last reader
     for (int k = p.n_res_chunks; k < p.n_chunks; ++k) {
         if (bounded) {
-            if (k - 2 >= p.n_res_chunks) CF_HIP(c, hipEventSynchronize(c->chunk_ev[s][k - 2]));
-            std::lock_guard<std::mutex> lk(c->mu);
-            if (c->pause_flag) {
-                CF_HIP(c, hipStreamWaitEvent(copy, c->comm_done_ev, 0));
-                c->pause_flag = false;
-                c->stats.pauses++;
-            }
+            const int depth = c->pause_depth;
+            if (k - depth >= p.n_res_chunks) CF_HIP(c, hipEventSynchronize(c->chunk_ev[s][k - depth]));
+            std::unique_lock<std::mutex> lk(c->mu);
+            CF_TRY(pause_if_collective_running(c, copy, lk));
         }
         const uint64_t b = chunk_begin(c, k), e = chunk_end(c, p, k);
         CF_HIP(c, hipMemcpyAsync(c->slot[s] + (b - p.res_bytes), c->host[block] + b, e - b, hipMemcpyHostToDevice, copy));
@@ -751,6 +777,11 @@ void plan_model(cf_ctx* c) {
     }
 }
 
+// A prefetch counts as hidden when its last chunk landed at least this long before the block that ran ahead of
+// its consumer ended: a margin of a few event-timestamp granules (timestamps of two streams are only comparable
+// to some microseconds), small against any block that could hide a prefetch at all.
+constexpr float kLandedAheadMs = 0.05f;
+
 int check_block(const cf_ctx* c, int block) {
     if (!c) return CF_ERR_ARG;
     if (block < 0 || block >= c->d.n_blocks) return cf_fail(c, CF_ERR_ARG, "block %d out of range [0,%d)", block, c->d.n_blocks);
@@ -795,6 +826,9 @@ int cf_destroy(cf_ctx* c) {
         }
         (void)hipEventDestroy(c->comm_ready_ev);
         (void)hipEventDestroy(c->comm_done_ev);
+        for (auto e : c->fwd_ev) (void)hipEventDestroy(e);
+        for (auto& pc : c->comm_pending) { (void)hipEventDestroy(pc.ready); (void)hipEventDestroy(pc.done); }
+        for (auto e : c->comm_ev_pool) (void)hipEventDestroy(e);
         for (auto& pe : c->prof_pending) { (void)hipEventDestroy(pe.a); (void)hipEventDestroy(pe.b); }
         for (auto e : c->ev_pool) (void)hipEventDestroy(e);
         if (c->comm_dev) (void)hipFree(c->comm_dev);
@@ -978,7 +1012,7 @@ int chunked_prefetch_begin(cf_ctx* c, int32_t block, void* copy_stream) {
         bool hidden = false;
         float ms = 0.f;
         if (hipEventQuery(c->land_ev[s]) == hipSuccess && hipEventElapsedTime(&ms, c->land_ev[s], c->done_ev[s ^ 1]) == hipSuccess)
-            hidden = ms > 0.05f;
+            hidden = ms > kLandedAheadMs;
         (void)hipGetLastError();
         c->hidden_kind[c->block_kind[c->slot_tenant[s]]] = hidden;
     }
@@ -1038,6 +1072,13 @@ int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute
     if (streamed && (s < 0 || c->slot_tenant[s] != block || c->slot_state[s] != SLOT_FILLED))
         return cf_fail(c, CF_ERR_STATE, "block %d: chunked_prefetch_begin must precede dit_block_fwd", block);
 
+    // While collectives are emulated the host stays at most one block ahead of the GPU, streamed weights or not
+    // (chunked_prefetch_begin bounds it the same way when chunks stream): waits between the compute and the
+    // collective stream that are enqueued long before their events fire cost far more than waits that find
+    // the event fired (measured: a fully resident step with collectives 18-22 ms unbounded, 14 ms bounded).
+    if (c->comm_stream && c->comm_bytes && c->fwd_count >= 2)
+        CF_HIP(c, hipEventSynchronize(c->fwd_ev[(c->fwd_count - 2) % 4]));
+
     Fwd F{c, block, (hipStream_t)compute_stream, view_of(c, block), io, carve(c->d, p.kind, (char*)io->workspace)};
     c->waited_upto = p.n_res_chunks - 1;
     if (streamed && c->adaptive_waits && !c->pause_resume && c->hidden_kind[p.kind]) {
@@ -1053,17 +1094,25 @@ int dit_block_fwd(cf_ctx* c, int32_t block, const cf_block_io* io, void* compute
         case CF_DIT_CROSS: rc = fwd_dit(F); break;
         default: rc = fwd_double(F); break;
     }
-    if (rc != CF_OK) return rc;
     if (streamed) {
-        // the slot's release below must follow every chunk: a tail chunk that fed no layer is waited for
-        // here (nothing to do when the layers' own waits reached the last chunk -- a wait on an event
-        // that fired long ago still costs the stream tens of microseconds)
-        if (c->waited_upto < p.n_chunks - 1) CF_TRY(chunked_prefetch_wait(c, block, -1, compute_stream));
-        CF_HIP(c, hipEventRecord(c->done_ev[s], (hipStream_t)compute_stream));
+        // The slot's release must follow every chunk: a tail chunk that fed no layer is waited for here
+        // (nothing to do when the layers' own waits reached the last chunk -- a wait on an event that fired
+        // long ago still costs the stream tens of microseconds).  A forward that failed half way releases
+        // its slot all the same, behind whatever it had enqueued, so that the next prefetch is not refused;
+        // the caller gets the forward's error, the message of a failing release is dropped.
+        const std::string fwd_err = c->err;
+        int rel = CF_OK;
+        if (c->waited_upto < p.n_chunks - 1) rel = chunked_prefetch_wait(c, block, -1, compute_stream);
+        if (rel == CF_OK && hipEventRecord(c->done_ev[s], (hipStream_t)compute_stream) != hipSuccess)
+            rel = cf_fail(c, CF_ERR_HIP, "recording the slot's release failed");
         c->slot_fwd_seq[s] = ++c->fwd_seq;
-        c->done_valid[s] = true;
+        c->done_valid[s] = rel == CF_OK;
         c->slot_state[s] = SLOT_CONSUMED;
+        if (rc != CF_OK) c->err = fwd_err; else rc = rel;
     }
+    if (rc != CF_OK) return rc;
+    CF_HIP(c, hipEventRecord(c->fwd_ev[c->fwd_count % 4], (hipStream_t)compute_stream));
+    c->fwd_count++;
     return CF_OK;
 }
 
@@ -1073,6 +1122,14 @@ int cf_set_contention(cf_ctx* c, void* comm_stream, void* host_pinned, uint64_t 
     CF_TRY(ensure_device(c));
     worker_drain(c);
     CF_HIP(c, hipDeviceSynchronize());
+    {
+        // nothing is in flight any more: collectives of the previous setting are history
+        std::lock_guard<std::mutex> lk(c->mu);
+        for (auto& pc : c->comm_pending) { c->comm_ev_pool.push_back(pc.ready); c->comm_ev_pool.push_back(pc.done); }
+        c->comm_pending.clear();
+        c->cur_ready = c->cur_done = nullptr;
+    }
+    if (pause_resume < 0 || pause_resume > 2) return cf_fail(c, CF_ERR_ARG, "pause_resume must be 0, 1 or 2");
     if (!comm_stream) {
         c->comm_stream = nullptr;
         c->comm_bytes = 0;
@@ -1099,6 +1156,7 @@ int cf_set_contention(cf_ctx* c, void* comm_stream, void* host_pinned, uint64_t 
     c->comm_host = (uint8_t*)host_pinned;
     c->comm_bytes = bytes_per_collective;
     c->pause_resume = pause_resume != 0;
+    c->pause_depth = pause_resume == 2 ? 2 : 1;
     if (!c->pause_resume) worker_stop(c);
     return CF_OK;
 }
@@ -1303,25 +1361,38 @@ int cf_op_checksum(const void* data, uint64_t bytes, uint64_t first_word, uint64
 namespace {
 
 int cf_comm_begin_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute) {
-    // the collective may start once the compute stream has produced its operands
-    CF_HIP(c, hipEventRecord(c->comm_ready_ev, compute));
     if (c->pause_resume) {
-        // pause request in GPU time: the host waits until compute has really reached the collective,
-        // so that the flag is not raised while the GPU is still far behind the host
-        CF_HIP(c, hipEventSynchronize(c->comm_ready_ev));
+        // pause/resume: this collective gets an event pair of its own, which the prefetch worker polls --
+        // `ready` tells it, in GPU time, that the compute stream has reached the collective (Sec. 3.2: the
+        // flag goes up when the collective is issued), `done` is what it parks the copy stream on
+        std::lock_guard<std::mutex> lk(c->mu);
+        for (hipEvent_t* e : {&c->cur_ready, &c->cur_done}) {
+            if (!c->comm_ev_pool.empty()) { *e = c->comm_ev_pool.back(); c->comm_ev_pool.pop_back(); }
+            else CF_HIP(c, hipEventCreateWithFlags(e, hipEventDisableTiming));
+        }
+        CF_HIP(c, hipEventRecord(c->cur_ready, compute));
+        c->comm_pending.push_back(PendingComm{c->cur_ready, c->cur_done, false, false});
+    } else {
+        c->cur_ready = c->comm_ready_ev;
+        c->cur_done = c->comm_done_ev;
+        CF_HIP(c, hipEventRecord(c->cur_ready, compute));
     }
-    CF_HIP(c, hipStreamWaitEvent(comm, c->comm_ready_ev, 0));
+    // the collective may start once the compute stream has produced its operands
+    CF_HIP(c, hipStreamWaitEvent(comm, c->cur_ready, 0));
     return CF_OK;
 }
 
 int cf_comm_end_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute) {
+    if (!c->cur_done) return cf_fail(c, CF_ERR_STATE, "cf_comm_end without cf_comm_begin");
     {
         std::lock_guard<std::mutex> lk(c->mu);
-        CF_HIP(c, hipEventRecord(c->comm_done_ev, comm));
-        if (c->pause_resume) c->pause_flag = true;
+        CF_HIP(c, hipEventRecord(c->cur_done, comm));
+        if (c->pause_resume && !c->comm_pending.empty() && c->comm_pending.back().done == c->cur_done)
+            c->comm_pending.back().done_recorded = true;
     }
+    c->cv.notify_all();
     ProfScope ps(c, compute, K_COMM_WAIT, 0, 0);
-    CF_HIP(c, hipStreamWaitEvent(compute, c->comm_done_ev, 0));
+    CF_HIP(c, hipStreamWaitEvent(compute, c->cur_done, 0));
     return CF_OK;
 }
 

@@ -43,12 +43,26 @@ def _dev_bf16(bits: np.ndarray, device) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
 
 
+_STREAMS: Dict[str, tuple] = {}
+
+
+def process_streams(device) -> tuple:
+    """The process's (compute, copy, comm) streams on `device`, created once, back to back.  HIP
+    multiplexes streams onto a few hardware queues (4 by default) in creation order, and two streams
+    that share a queue run one after the other: a copy stream on the compute stream's queue hides
+    behind nothing, a collective stream on the copy stream's queue waits for every enqueued chunk.
+    Three streams created in a row sit on three different queues; triples created later in a process
+    that has made many streams may not, so every runner of a process uses the same triple."""
+    key = str(device)
+    if key not in _STREAMS:
+        _STREAMS[key] = tuple(torch.cuda.Stream(device=device) for _ in range(3))
+    return _STREAMS[key]
+
+
 class BlockRunner:
     def __init__(self, cfg, chunk_bytes: Optional[int] = None, device: str = "cuda:0", n_blocks: Optional[int] = None,
                  streams=None):
-        """streams: (compute, copy, comm) torch streams to use instead of new ones.  HIP multiplexes
-        streams onto a few hardware queues (4 by default); two streams that share a queue run one
-        after the other, so a process that builds several runners hands the same three to all."""
+        """streams: (compute, copy, comm) torch streams to use instead of the process's triple."""
         self.cfg = cfg if n_blocks is None else cfg.with_(n_blocks=n_blocks)
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
@@ -58,7 +72,7 @@ class BlockRunner:
         self.total_blob_bytes = sum(self.blob_bytes_of)
         self.blob_bytes = self.blob_bytes_of[0]
         self.n_chunks = self.ctx.cf_n_chunks()
-        self.compute, self.copy, self.comm = streams or tuple(torch.cuda.Stream(device=self.device) for _ in range(3))
+        self.compute, self.copy, self.comm = streams or process_streams(self.device)
         self.workspace = torch.empty(self.ctx.cf_workspace_bytes() + 256, dtype=torch.uint8, device=self.device)
         self.blobs: List[torch.Tensor] = []
         self.io_tensors: List[Dict[str, torch.Tensor]] = []
@@ -108,6 +122,9 @@ class BlockRunner:
             for k in ("send_q", "send_k", "send_v"):
                 t[k] = torch.zeros(lead + (ho, nl, hd), dtype=torch.int16, device=dev)
             t["send_attn"] = torch.zeros(lead + (hl, nrem, hd), dtype=torch.int16, device=dev)
+        # the tensors were produced on torch's current stream; the library reads and writes them on
+        # streams of its own, so their producers must have finished first
+        torch.cuda.current_stream(dev).synchronize()
         return t
 
     def io_struct(self, t: Dict[str, torch.Tensor]) -> B.cf_block_io:

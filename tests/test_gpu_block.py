@@ -212,11 +212,158 @@ def test_contention_and_pause_resume_keep_results_and_volume(n_chunks, r):
                 assert st["comm_bytes_h2d"] == st["comm_bytes_d2h"] == 7 * 4 * (nbytes // 2)
             if mode != "pause":
                 assert st["pauses"] == 0
+            else:
+                assert st["pauses"] <= 7 * 4             # at most one per collective
             if base is None:
                 base = outs
             else:
                 for a, b in zip(outs, base):
                     assert torch.equal(a, b), mode
+    finally:
+        run.close()
+
+
+def _pause_cfg():
+    # link-bound on purpose: 31 MB of weights per block against a tenth of a millisecond of compute, so the
+    # prefetch is on the link whenever a collective arrives
+    return wl.BlockConfig("mini_pause", wl.KIND_SINGLE, n_blocks=3, d=1024, n_heads=8, head_dim=128, f=4096,
+                          n_total=2048, sp_degree=1, qk_rmsnorm=True, n_chunks=16, temb_std=0.7)
+
+
+def test_pause_resume_fires_and_bounds_the_collective_stall():
+    """Sec. 3.2: with pause/resume the copy stream yields at chunk boundaries, so a collective waits for at
+    most the chunk already on the link; without it the collective shares the link with the prefetch for its
+    whole length.  Measured on a link-bound stack with 16 MB collectives (8 MB each way): the compute
+    stream's mean wait per collective, with nothing else on the link (everything resident), with the prefetch
+    running and no pause, and with pause/resume.  Asserted: pauses happen, the paused wait stays within the
+    lone collective's time plus two chunks' service time plus scheduling slack, the results are bit-identical
+    and the prefetch volume is unchanged.  Printed: all three waits and the chunk service time."""
+    cfg = _pause_cfg()
+    run = BlockRunner(cfg, chunk_bytes=chunk_bytes_for(cfg))
+    try:
+        ios = []
+        for blk in range(cfg.n_blocks):
+            run.register_params(blk, wl.gen_block_params(cfg, blk))
+            ios.append(run.make_io(wl.gen_block_inputs(cfg, blk)))
+        structs = [run.io_struct(t) for t in ios]
+        nbytes = 16 << 20
+        host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        n_steps = 6
+
+        def arm(mode, r):
+            if mode == "off":
+                run.ctx.cf_set_contention(None, None, 0, False)
+            else:
+                run.ctx.cf_set_contention(run.comm, host, nbytes, mode == "pause")
+            run.ctx.set_resident_fraction(r)
+            run.begin(0)
+            for _ in range(2):
+                run.step(structs)                       # warm-up
+            run.ctx.cf_sync()
+            run.ctx.cf_stats_reset()
+            run.ctx.cf_kernel_times_reset()
+            run.ctx.cf_set_profiling(True)
+            torch.cuda.synchronize()
+            import time
+            t0 = time.perf_counter()
+            for _ in range(n_steps):
+                run.step(structs)
+            run.ctx.cf_sync()
+            ms = (time.perf_counter() - t0) * 1e3 / n_steps
+            st = run.ctx.cf_stats()
+            kt = {k["name"]: k for k in run.ctx.cf_kernel_times()}
+            run.ctx.cf_set_profiling(False)
+            run.fwd(0, structs[0])
+            run.ctx.cf_sync()
+            cw = kt.get("collective_wait")
+            wait_ms = cw["total_ms"] / cw["launches"] if cw else 0.0     # per wait of the compute stream
+            return ms, st, wait_ms, [t["y"].clone() for t in ios]
+
+        off_ms, st_off, _, y_off = arm("off", 0.0)
+        t_chunk_ms = run.chunk_bytes / (st_off["h2d_bytes"] / n_steps / (off_ms * 1e-3)) * 1e3
+        _, _, lone_wait, _ = arm("on", 1.0)               # collectives alone on the link
+        on_ms, st_on, on_wait, y_on = arm("on", 0.0)
+        pa_ms, st_pa, pa_wait, y_pa = arm("pause", 0.0)
+        print(f"[pause] chunk {run.chunk_bytes / 1e6:.2f} MB, T_chunk {t_chunk_ms * 1e3:.0f} us; mean wait of the compute "
+              f"stream per collective group: alone {lone_wait * 1e3:.0f} us, beside the prefetch {on_wait * 1e3:.0f} us, "
+              f"with pause/resume {pa_wait * 1e3:.0f} us; step {off_ms:.2f} / {on_ms:.2f} / {pa_ms:.2f} ms (off / on / pause); "
+              f"pauses {st_pa['pauses']} of {n_steps * cfg.n_blocks * 2} collective groups")
+        assert st_on["pauses"] == 0 and st_pa["pauses"] > 0
+        assert st_pa["h2d_bytes"] == st_on["h2d_bytes"] == st_off["h2d_bytes"]
+        for a, b, c in zip(y_off, y_on, y_pa):
+            assert torch.equal(a, b) and torch.equal(a, c)
+        # a group of three collectives (q, k, v) is the longest wait; bound every wait by the lone figure plus
+        # the chunk that was on the link, with one more chunk and 0.1 ms of slack for the host's reaction
+        assert pa_wait <= lone_wait + 2 * t_chunk_ms + 0.1, (pa_wait, lone_wait, t_chunk_ms)
+    finally:
+        run.close()
+
+
+def test_step_time_does_not_grow_with_the_resident_fraction_under_contention():
+    """Sec. 4.5: keeping more chunks resident never makes a step slower, with the emulated collectives
+    running and with pause/resume as well (10 % tolerance for timing noise)."""
+    import time
+    cfg = _pause_cfg()
+    run = BlockRunner(cfg, chunk_bytes=chunk_bytes_for(cfg))
+    try:
+        ios = []
+        for blk in range(cfg.n_blocks):
+            run.register_params(blk, wl.gen_block_params(cfg, blk))
+            ios.append(run.make_io(wl.gen_block_inputs(cfg, blk)))
+        structs = [run.io_struct(t) for t in ios]
+        nbytes = cfg.n_local * cfg.d * 2
+        host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        for mode in ("on", "pause"):
+            run.ctx.cf_set_contention(run.comm, host, nbytes, mode == "pause")
+            times = []
+            for r in (0.0, 0.25, 0.5, 0.75, 1.0):
+                run.ctx.set_resident_fraction(r)
+                run.begin(0)
+                for _ in range(3):
+                    run.step(structs)
+                run.ctx.cf_sync()
+                t0 = time.perf_counter()
+                for _ in range(10):
+                    run.step(structs)
+                run.ctx.cf_sync()
+                times.append((time.perf_counter() - t0) * 100.0)
+                run.fwd(0, structs[0])
+                run.ctx.cf_sync()
+            print(f"[monotone] {mode}: step ms at r = 0, .25, .5, .75, 1: " + ", ".join(f"{t:.3f}" for t in times))
+            for a, b in zip(times, times[1:]):
+                assert b <= a * 1.10 + 0.02, (mode, times)
+    finally:
+        run.close()
+
+
+def test_a_failed_forward_releases_its_slot():
+    """A forward that fails half way (here: a Ulysses share without its peer tensors, noticed after the
+    first layers were enqueued) must not leave its staging slot occupied: the next prefetch is accepted
+    and a correct forward afterwards gives the oracle's result."""
+    cfg = wl.BlockConfig("mini_fail", wl.KIND_SINGLE, n_blocks=2, d=512, n_heads=4, head_dim=128, f=1024,
+                         n_total=512, sp_degree=2, sp_rank=0, qk_rmsnorm=True, n_chunks=4, temb_std=1.0)
+    run = BlockRunner(cfg)
+    try:
+        params = [wl.gen_block_params(cfg, b) for b in range(2)]
+        inputs = [wl.gen_block_inputs(cfg, b) for b in range(2)]
+        for b in range(2):
+            run.register_params(b, params[b])
+        ts = [run.make_io(i) for i in inputs]
+        bad = run.io_struct(ts[0])
+        bad.peer_q = None
+        run.begin(0)
+        with pytest.raises(B.ChunkflowError) as e:
+            run.fwd(0, bad)
+        assert e.value.code == B.CF_ERR_ARG and "peer" in str(e.value)
+        run.begin(1)                                     # other slot
+        run.begin(0)                                     # the slot the failed forward held
+        run.fwd(1, run.io_struct(ts[1]))
+        run.fwd(0, run.io_struct(ts[0]))
+        run.ctx.cf_sync()
+        for b in range(2):
+            ref = ob.block_forward(cfg, params[b], inputs[b])["y"]
+            y = ts[b]["y"].cpu().numpy()
+            assert rel_l2(y, ref) <= REL_L2_TOL and max_abs(y, ref) <= MAX_ABS_TOL
     finally:
         run.close()
 

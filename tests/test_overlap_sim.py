@@ -162,3 +162,38 @@ def test_simulation_argument_errors():
         assert only == more
     finally:
         ctx.close()
+
+
+def test_segment_shares_against_a_layout_worked_by_hand():
+    """The booking rule of the chunk-level walk, applied on paper to two matrices and three chunks.
+
+    65536 tokens (256 token tiles, so a row group is 256 output features), one head of 64.
+    "w1"  512 x 64  at byte 0      (65536 bytes): rows 0-255 end at byte 32767 (chunk 0), rows 256-511 at 65535 (chunk 1)
+    "w2"  256 x 128 at byte 65536  (65536 bytes): one group, ends at byte 131071 (chunk 2)
+    chunks of 49152 bytes: [0, 49152), [49152, 98304), [98304, 131072)
+    FLOPs (App. B, 2 x tokens x out x in per linear term, 4 x H x N^2 x hd for attention, booked where QKV completes):
+      chunk 0: 2 * 65536 * 256 * 64                      = 2,147,483,648
+      chunk 1: 2 * 65536 * 256 * 64 + 4 * 65536^2 * 64   = 2,147,483,648 + 1,099,511,627,776
+      chunk 2: 2 * 65536 * 256 * 128                     = 4,294,967,296"""
+    from types import SimpleNamespace
+    cfg = SimpleNamespace(kind=0, n_total=65536, sp_degree=1, n_txt=0, n_heads=1, head_dim=64, l_ctx=0, batch=1)
+    lay = [("w1", 0, 512, 64), ("w2", 65536, 256, 128)]
+    got = om.segment_shares(cfg, lay, 131072, 49152)
+    f = [2_147_483_648, 2_147_483_648 + 1_099_511_627_776, 4_294_967_296]
+    assert got == pytest.approx([v / sum(f) for v in f], rel=1e-12)
+    # the same matrices under names that carry no attention term: pure linear terms, 1 : 1 : 2
+    lay = [("w_o", 0, 512, 64), ("w_up", 65536, 256, 128)]
+    assert om.segment_shares(cfg, lay, 131072, 49152) == pytest.approx([0.25, 0.25, 0.5], rel=1e-12)
+    # few token tiles: 512 tokens are 2 tiles, a group is 256 * 128 features, so each matrix is one group booked
+    # on the chunk of its last byte: w_o (2 * 512 * 512 * 64) on chunk 1, w_up (2 * 512 * 256 * 128) on chunk 2
+    small = SimpleNamespace(kind=0, n_total=512, sp_degree=1, n_txt=0, n_heads=1, head_dim=64, l_ctx=0, batch=1)
+    assert om.segment_shares(small, lay, 131072, 49152) == pytest.approx([0.0, 0.5, 0.5], rel=1e-12)
+    # the modulation matrix multiplies one vector and is booked 8 rows at a time: 24 x 1024 at byte 0 with
+    # 16384-byte chunks puts 8 rows (2 * 8 * 1024 FLOPs) on each of three chunks
+    lay = [("w_mod", 0, 24, 1024)]
+    assert om.segment_shares(small, lay, 49152, 16384) == pytest.approx([1 / 3, 1 / 3, 1 / 3], rel=1e-12)
+    # a sharded double-stream block: text-stream matrices see the text rows, image-stream ones the image rows
+    dbl = SimpleNamespace(kind=2, n_total=1024, sp_degree=2, n_txt=256, n_heads=2, head_dim=64, l_ctx=0, batch=1)
+    lay = [("txt_w_o", 0, 256, 64), ("img_w_o", 32768, 256, 64)]
+    # 128 text rows, 384 image rows: 2 * 128 * 256 * 64 on chunk 0, 2 * 384 * 256 * 64 on chunk 1
+    assert om.segment_shares(dbl, lay, 65536, 32768) == pytest.approx([0.25, 0.75], rel=1e-12)
