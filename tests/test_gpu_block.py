@@ -74,6 +74,31 @@ def test_flux_share_parity_full_size():
     run_and_check(wl.CONFIGS["flux"], 1)
 
 
+def test_flux_share_with_unit_variance_timestep_embedding_is_on_record():
+    """The benchmark shapes draw the timestep embedding with standard deviation sqrt(512/d) so that the
+    modulation keeps the toy configuration's spread.  This case runs the Flux-like share with the embedding
+    at N(0,1) instead (gates reach |g| ~ 4) and puts the error on record: relative L2 must still hold, the
+    largest absolute error is printed and held to the bf16 rounding of the operands it scales with."""
+    cfg = wl.CONFIGS["flux"].with_(temb_std=1.0, n_blocks=1)
+    params, inputs = wl.gen_block_params(cfg, 0), wl.gen_block_inputs(cfg, 0)
+    run = BlockRunner(cfg, n_blocks=1)
+    try:
+        run.register_params(0, params)
+        t = run.make_io(inputs)
+        run.run_block(0, t)
+        ref = ob.block_forward(cfg, params, inputs)
+        y, x = t["y"].cpu().numpy(), t["x"].cpu().numpy()
+        r, m, rb = rel_l2(y, ref["y"]), max_abs(y, ref["y"]), rel_l2(y - x, ref["y"] - x)
+        print(f"[flux, temb ~ N(0,1)] y rel_l2={r:.3e} max_abs={m:.3e} branch rel_l2={rb:.3e} "
+              f"max |y - x| = {np.abs(ref['y'] - x).max():.2f}")
+        assert r <= REL_L2_TOL and rb <= 2e-2
+        # every output is gate x (a 15360-term dot product of bf16-rounded operands): the absolute error scales
+        # with the branch's magnitude, 2^-8 relative per operand rounding
+        assert m <= 2.0 ** -7 * np.abs(ref["y"] - x).max()
+    finally:
+        run.close()
+
+
 def _outputs(run, t):
     keys = ["y"] + [k for k in ("send_q", "send_k", "send_v", "send_attn") if k in t]
     return {k: t[k].clone() for k in keys}

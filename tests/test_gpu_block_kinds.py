@@ -54,8 +54,11 @@ def run_case(cfg, r=0.0, n_rows=None, seed=0):
             if send_rows is not None:
                 sa = sa[:, send_rows]
             assert rel_l2(sa, ref["send_attn"]) <= REL_L2_TOL and max_abs(sa, ref["send_attn"]) <= MAX_ABS_TOL
-            for k in ("send_k", "send_v"):
+            for k in ("send_q", "send_k", "send_v"):
                 g = bits_to_f64(bits_of(t[k]))
+                if k == "send_q" and rows is not None:
+                    g = g[:, rows]                         # the oracle computes queries of the sampled rows only
+                assert g.shape == ref[k].shape, (k, g.shape, ref[k].shape)
                 assert rel_l2(g, ref[k]) <= REL_L2_TOL and max_abs(g, ref[k]) <= MAX_ABS_TOL, k
     finally:
         run.close()
