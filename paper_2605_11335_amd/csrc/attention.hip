@@ -33,6 +33,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 
 constexpr int BKV = 64;    // keys per tile
 
+__device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
+
 // NW waves of 32 queries each per workgroup: 4 (two workgroups per CU), 7 or 8 (one per CU).
 template <int HD, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
@@ -182,11 +184,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
                     if (key >= a.nk) s[mt][v] = -INFINITY;
                 }
         }
-        float mx = s[0][0];
+        // maximum of the lane's 32 scores as a tree of three-input maxima (11 + 4 + 1 instructions, depth 4)
+        float mx;
+        {
+            float m3[11];
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[mt][v]);
+            for (int i = 0; i < 10; ++i) m3[i] = max3f(s[(3 * i) >> 4][(3 * i) & 15], s[(3 * i + 1) >> 4][(3 * i + 1) & 15], s[(3 * i + 2) >> 4][(3 * i + 2) & 15]);
+            m3[10] = fmaxf(s[1][14], s[1][15]);
+            const float a0 = max3f(m3[0], m3[1], m3[2]), a1 = max3f(m3[3], m3[4], m3[5]), a2 = max3f(m3[6], m3[7], m3[8]);
+            mx = max3f(max3f(a0, a1, a2), m3[9], m3[10]);
+        }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         // Rescale lazily: the reference maximum only moves when some query of this wave exceeds it by
         // more than 2^8 (softmax is invariant to the reference as long as numerator and denominator
@@ -202,16 +209,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
             m_run = m_new;
         }
         const float mc = m_run * c2;
-        float psum = 0.f;
+        float psum[4] = {0.f, 0.f, 0.f, 0.f};             // four chains: a row sum is not one long dependency
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const float p = __builtin_amdgcn_exp2f(fmaf(s[mt][v], c2, -mc));
                 s[mt][v] = p;
-                psum += p;
+                psum[v & 3] += p;
             }
-        l_run += psum;
+        l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
 
         // ---- O^T += V^T . P^T: MFMA i handles k-step (i / DT) of 16 keys and d-tile (i % DT);
         // V^T fragments keep running 4 reads ahead
