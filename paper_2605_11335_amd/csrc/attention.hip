@@ -254,7 +254,24 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
     const int q = q0 + lj;
     if (q < a.nq) {
         const int hps = a.hps ? a.hps : a.H;            // heads per sample of a batch
-        bf16* op = a.O + (size_t)(h / hps) * a.o_bs + (size_t)(h % hps) * a.o_hs + (size_t)q * a.o_qs;
+        const int b = h / hps, hh = h % hps;
+        bf16* op;
+        if (a.scatter) {
+            // the second exchange by the stores themselves: this rank's positions go to the projection operand,
+            // the others to the send buffer (in ascending position order, as the receiver expects them)
+            const TokenMap& m = a.map;
+            if (q >= m.pos0 && q < m.pos0 + m.len0) {
+                op = a.dst0 + (size_t)b * a.bs0 + (size_t)(q - m.pos0) * a.ld + (a.h0 + hh) * HD;
+            } else if (q >= m.pos1 && q < m.pos1 + m.len1) {
+                op = a.dst1 + (size_t)b * a.bs1 + (size_t)(q - m.pos1) * a.ld + (a.h0 + hh) * HD;
+            } else {
+                const int ri = q - (q >= m.pos0 + m.len0 ? m.len0 : 0) - (q >= m.pos1 + m.len1 ? m.len1 : 0);
+                op = a.send ? a.send + (size_t)b * a.send_bs + ((size_t)hh * (m.n_total - m.n_local) + ri) * HD : nullptr;
+            }
+        } else {
+            op = a.O + (size_t)b * a.o_bs + (size_t)hh * a.o_hs + (size_t)q * a.o_qs;
+        }
+        if (op) {
 #pragma unroll
         for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -264,6 +281,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
                 for (int e = 0; e < 4; ++e) w[e] = (bf16)(o[d][vb * 4 + e] * inv);
                 *(bf16x4*)(op + d * 32 + vb * 8 + lg * 4) = w;
             }
+        }
     }
 }
 
@@ -298,9 +316,21 @@ const char* attn_check(const AttnArgs& a) {
     if (a.H <= 0 || a.nq <= 0 || a.nk <= 0) return "attention: empty shape";
     if (a.nk_pad % 64 || a.nk_pad < a.nk) return "attention: nk_pad must be a multiple of 64 covering nk";
     if ((uint64_t)a.nk_pad * a.hd * 2 >= (1ull << 32)) return "attention: a head's keys exceed the 4 GiB buffer range";
-    if (!a.Q || !a.K || !a.Vt || !a.O) return "attention: null operand";
+    if (!a.Q || !a.K || !a.Vt) return "attention: null operand";
     if (((uintptr_t)a.Q | (uintptr_t)a.K | (uintptr_t)a.Vt) % 16) return "attention: operands must be 16-byte aligned";
-    if (((uintptr_t)a.O % 8) || (a.o_hs % 4) || (a.o_qs % 4) || (a.o_bs % 4)) return "attention: output must be 8-byte aligned";
+    if (a.scatter) {
+        const TokenMap& m = a.map;
+        if (!a.dst0 || (m.len1 > 0 && !a.dst1)) return "attention: scatter mode needs the projection operand";
+        if (m.n_total != a.nq || m.len0 + m.len1 != m.n_local || m.pos0 < 0 || m.len0 < 0 || m.len1 < 0 ||
+            m.pos0 + m.len0 > m.pos1 || m.pos1 + m.len1 > m.n_total)
+            return "attention: scatter map must hold two ordered position ranges inside the query sequence";
+        if ((((uintptr_t)a.dst0 | (uintptr_t)a.dst1 | (uintptr_t)a.send) % 8) || (a.ld % 4) || (a.bs0 % 4) || (a.bs1 % 4) || (a.send_bs % 4))
+            return "attention: scatter targets must be 8-byte aligned";
+        if (a.h0 < 0 || a.ld < (a.h0 + (a.hps ? a.hps : a.H)) * a.hd) return "attention: scatter columns exceed the operand's row";
+    } else {
+        if (!a.O) return "attention: null operand";
+        if (((uintptr_t)a.O % 8) || (a.o_hs % 4) || (a.o_qs % 4) || (a.o_bs % 4)) return "attention: output must be 8-byte aligned";
+    }
     if (a.hps < 0 || (a.hps && a.H % a.hps)) return "attention: H must be whole samples of hps heads";
     if ((long)((a.nq + 127) / 128) * a.H > 0x7fffffffL) return "attention: grid too large";
     return nullptr;

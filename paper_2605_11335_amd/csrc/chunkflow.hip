@@ -111,7 +111,7 @@ struct Ws {
     bf16* xn = nullptr;        // [n_local, d]
     bf16* qkv = nullptr;       // [n_local, 3d]
     bf16* c = nullptr;         // single: [n_local, d+f]; others: attention rows [n_local, d]
-    bf16 *Q = nullptr, *K = nullptr, *Vt = nullptr, *O = nullptr;
+    bf16 *Q = nullptr, *K = nullptr, *Vt = nullptr;
     float *x1 = nullptr, *x2 = nullptr;
     bf16* up = nullptr;        // [n_local, f]
     bf16 *ckv = nullptr, *cQ = nullptr, *cK = nullptr, *cVt = nullptr;
@@ -138,10 +138,6 @@ Ws carve(const cf_model_desc& m, int kind, char* base) {
     w.Q = (bf16*)take(2 * hl * N * hd);
     w.K = (bf16*)take(2 * hl * N * hd);
     w.Vt = (bf16*)take(2 * hl * hd * n_pad_of(N));
-    // attention output on the full sequence, when it cannot be written straight into the rows of the
-    // output projection's operand: other ranks' rows are among it, or the two streams' rows of a
-    // batched double-stream block lie in separate regions
-    if (m.sp_degree > 1 || (kind == CF_DOUBLE_STREAM && B > 1)) w.O = (bf16*)take(2 * hl * N * hd);
     if (kind != CF_SINGLE_STREAM) {
         w.x1 = (float*)take(4 * nl * d);
         w.up = (bf16*)take(2 * nl * f);
@@ -323,14 +319,14 @@ void worker_stop(cf_ctx* c) {
 // profiling: hipEvent pair around each kernel launch, resolved lazily
 // ------------------------------------------------------------------------------------------
 enum Kid {
-    K_MODVEC, K_LN, K_LIN1, K_QKV, K_RELAYOUT, K_ATTN, K_GATHER, K_LIN2, K_OUT, K_UP, K_DOWN,
+    K_MODVEC, K_LN, K_LIN1, K_QKV, K_RELAYOUT, K_ATTN, K_LIN2, K_OUT, K_UP, K_DOWN,
     K_CROSS_Q, K_CROSS_KV, K_CROSS_ATTN, K_CROSS_OUT,
     // not kernels: time the compute stream spends parked on a chunk's event (the exposed prefetch of
     // Sec. 4.3's breakdown) and on an emulated collective's completion
     K_CHUNK_WAIT, K_COMM_WAIT, K_COUNT
 };
 const char* kKidName[K_COUNT] = {"modvec", "ln_modulate", "gemm_lin1", "gemm_qkv", "pre_attention",
-                                 "attention", "attn_gather", "gemm_lin2", "gemm_out", "gemm_up", "gemm_down",
+                                 "attention", "gemm_lin2", "gemm_out", "gemm_up", "gemm_down",
                                  "gemm_cross_q", "gemm_cross_kv", "cross_attention", "gemm_cross_out",
                                  "prefetch_stall", "collective_wait"};
 
@@ -631,6 +627,8 @@ int run_joint_attention(Fwd& F, const RelayoutArgs* parts, int n_parts, const At
         return cf_fail(c, CF_ERR_ARG, "sp_degree > 1 needs peer_q, peer_k, peer_v and peer_attn");
     const size_t op_bs = (size_t)hl * m.n_total * hd, vt_bs = (size_t)hl * hd * npad;        // Q,K / Vt per sample
     const size_t peer_bs = (size_t)hl * n_rem * hd, send_bs = (size_t)(m.n_heads - hl) * map.n_local * hd;
+    const bool direct = P == 1 && !out.dst1;        // attention writes the projection operand row by row itself
+    const size_t pa_bs = (size_t)map.n_local * (m.n_heads - hl) * hd;
     for (int b = 0; b < B; ++b) {
         RelayoutArgs pb[2];
         double bytes = 0;
@@ -644,34 +642,43 @@ int run_joint_attention(Fwd& F, const RelayoutArgs* parts, int n_parts, const At
             if (r.send_v) r.send_v += b * send_bs;
             bytes += 2.0 * 2 * r.rows * 3.0 * m.d;
         }
-        if (P > 1) bytes += 2.0 * 2 * 3 * hl * (double)n_rem * hd;
+        // what the second exchange delivers (the other heads' attention rows of the local tokens) is an input
+        // of the block: it is put in place by the same launch, ahead of attention
+        PeerAttnArgs pa{};
+        if (P > 1) {
+            bytes += 2.0 * 2 * 3 * hl * (double)n_rem * hd + 2.0 * 2 * (double)pa_bs;
+            pa.peer_attn = (const bf16*)io->peer_attn + b * pa_bs;
+            pa.dst = out.dst + b * out.bs0;
+            pa.dst1 = out.dst1 ? out.dst1 + b * out.bs1 : nullptr;
+            pa.ld = out.ld; pa.n_heads = m.n_heads; pa.h0 = h0; pa.h_local = hl; pa.hd = hd; pa.map = map;
+        }
         ProfScope ps(c, F.s, K_RELAYOUT, 0, bytes);
         CF_HIP(c, pre_attention_launch(pb, n_parts, P > 1 ? (const bf16*)io->peer_q + b * peer_bs : nullptr,
                                        P > 1 ? (const bf16*)io->peer_k + b * peer_bs : nullptr,
-                                       P > 1 ? (const bf16*)io->peer_v + b * peer_bs : nullptr, F.s));
+                                       P > 1 ? (const bf16*)io->peer_v + b * peer_bs : nullptr, pa, F.s));
     }
     CF_TRY(emulate_collectives(F, 3));
-    const bool direct = P == 1 && !out.dst1;        // attention writes the projection operand itself
     AttnArgs a{};
     a.Q = F.ws.Q; a.K = F.ws.K; a.Vt = F.ws.Vt;
     a.H = B * hl; a.hps = hl; a.nq = m.n_total; a.nk = m.n_total; a.nk_pad = npad; a.hd = hd;
     a.scale = 1.0f / sqrtf((float)hd);
-    if (direct) { a.O = out.dst; a.o_hs = hd; a.o_qs = out.ld; a.o_bs = out.bs0; }
-    else { a.O = F.ws.O; a.o_hs = (long)m.n_total * hd; a.o_qs = hd; a.o_bs = (long)op_bs; }
+    if (direct) {
+        a.O = out.dst; a.o_hs = hd; a.o_qs = out.ld; a.o_bs = out.bs0;
+    } else {
+        // the attention kernel's stores do the second exchange: rows of this rank's positions go to the
+        // projection operand, the others to the send buffer
+        a.scatter = 1;
+        a.map = map;
+        a.dst0 = out.dst; a.bs0 = out.bs0;
+        a.dst1 = out.dst1 ? out.dst1 : out.dst + (size_t)map.len0 * out.ld;
+        a.bs1 = out.dst1 ? out.bs1 : out.bs0;
+        a.ld = out.ld; a.h0 = h0;
+        a.send = (bf16*)io->send_attn; a.send_bs = (long)peer_bs;
+    }
     if (const char* msg = attn_check(a)) return cf_fail(c, CF_ERR_ARG, "%s", msg);
     {
         ProfScope ps(c, F.s, K_ATTN, 4.0 * B * hl * (double)m.n_total * m.n_total * hd, 0);
         CF_HIP(c, attn_launch(a, F.s));
-    }
-    if (!direct) {
-        const size_t pa_bs = (size_t)map.n_local * (m.n_heads - hl) * hd;
-        for (int b = 0; b < B; ++b) {
-            ProfScope ps(c, F.s, K_GATHER, 0, 2.0 * 2 * ((double)hl * m.n_total + (double)map.n_local * (m.n_heads - hl)) * hd);
-            CF_HIP(c, attn_gather_launch(F.ws.O + b * op_bs, P > 1 ? (const bf16*)io->peer_attn + b * pa_bs : nullptr,
-                                         out.dst + b * out.bs0, out.dst1 ? out.dst1 + b * out.bs1 : nullptr, out.ld,
-                                         io->send_attn ? (bf16*)io->send_attn + b * peer_bs : nullptr, m.n_heads, h0, hl, hd,
-                                         map, F.s));
-        }
     }
     return emulate_collectives(F, 1);
 }

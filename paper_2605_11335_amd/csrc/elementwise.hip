@@ -1,6 +1,7 @@
 // HBM-bound kernels of the block: adaLN modulation vector, LayerNorm+modulate, q/k RMSNorm
-// with the Ulysses head-major relayout, the stand-ins for the two exchanges around attention
-// (Sec. 2.1), and the streamed-bytes checksum.  All accesses are 8- or 16-byte per lane and
+// with the Ulysses head-major relayout, the receiving side of the two exchanges around attention
+// (Sec. 2.1; the sending side of the second one is the attention kernel's own stores), and the
+// streamed-bytes checksum.  All accesses are 8- or 16-byte per lane and
 // consecutive lanes touch consecutive addresses.
 #include "common.h"
 #include "kernels.h"
@@ -310,6 +311,21 @@ __device__ __forceinline__ void peer_qk_part(int bid, int nblk, const bf16* __re
     }
 }
 
+// attention rows of the other ranks' heads for this rank's tokens -> their columns of the projection operand
+__device__ __forceinline__ void peer_attn_part(int bid, int nblk, const PeerAttnArgs& p) {
+    const int cpr = p.hd / 8, n_other = p.n_heads - p.h_local;
+    const long total = (long)p.map.n_local * n_other * cpr;
+    for (long q = (long)bid * 256 + threadIdx.x; q < total; q += (long)nblk * 256) {
+        const int c = q % cpr;
+        long rest = q / cpr;
+        const int ho = rest % n_other;
+        const int i = rest / n_other;
+        const int hh = ho < p.h0 ? ho : ho + p.h_local;
+        bf16* row = i < p.map.len0 ? p.dst + (size_t)i * p.ld : p.dst1 + (size_t)(i - p.map.len0) * p.ld;
+        *(uint4*)(row + hh * p.hd + c * 8) = *(const uint4*)(p.peer_attn + ((size_t)i * n_other + ho) * p.hd + c * 8);
+    }
+}
+
 // Everything between the QKV projection and attention in ONE launch: per part (one per stream)
 // the q/k RMSNorm + head-major relayout and the transposition of the own heads' v, then the peer
 // rows (q, k copied, v transposed).  Workgroups are dealt to the sub-tasks by index range.
@@ -317,7 +333,8 @@ struct PreAttnArgs {
     RelayoutArgs part[2];
     int n_parts;
     const bf16 *peer_q, *peer_k, *peer_v;      // may be NULL (sp_degree 1, or projection-only use)
-    int seg[7];                                // end of each segment: qk0, vt0, qk1, vt1, peer_qk, peer_vt (, total)
+    PeerAttnArgs pa;
+    int seg[7];                                // end of each segment: qk0, vt0, qk1, vt1, peer_qk, peer_vt, peer_attn
 };
 
 __global__ __launch_bounds__(256) void pre_attention_kernel(PreAttnArgs a) {
@@ -346,48 +363,10 @@ __global__ __launch_bounds__(256) void pre_attention_kernel(PreAttnArgs a) {
         const int nbx = (n_rem + 63) / 64, i = b - lo;
         v_transpose_part(tile, i % nbx, i / nbx, a.peer_v, (long)n_rem * r0.hd, (long)r0.hd, n_rem, 0, r0.Vt, r0.hd, r0.n_pad,
                          r0.map, 1);
+        return;
     }
-}
-
-// attention output on the full sequence -> projection operand rows + send buffer; peer heads in
-__global__ __launch_bounds__(256) void attn_gather_kernel(const bf16* __restrict__ O, const bf16* __restrict__ peer_attn,
-                                                          bf16* __restrict__ dst, bf16* __restrict__ dst1, int ld,
-                                                          bf16* __restrict__ send_attn, int n_heads, int h0, int h_local,
-                                                          int hd, TokenMap map) {
-    const int cpr = hd / 8;
-    // local row i of the first segment sits at dst + i*ld, of the second at dst1 + (i - len0)*ld
-    auto row_ptr = [&](int i) { return i < map.len0 ? dst + (size_t)i * ld : dst1 + (size_t)(i - map.len0) * ld; };
-    const int n_rem = map.n_total - map.n_local;
-    const long n_loc = (long)h_local * map.n_local * cpr;
-    const long n_snd = send_attn ? (long)h_local * n_rem * cpr : 0;
-    const long n_peer = (long)map.n_local * (n_heads - h_local) * cpr;
-    for (long q = (long)blockIdx.x * 256 + threadIdx.x; q < n_loc + n_snd + n_peer; q += (long)gridDim.x * 256) {
-        if (q < n_loc) {
-            const int c = q % cpr;
-            long rest = q / cpr;
-            const int h = rest % h_local;
-            const int i = rest / h_local;
-            const bf16* s = O + ((size_t)h * map.n_total + local_pos(map, i)) * hd + c * 8;
-            *(uint4*)(row_ptr(i) + (h0 + h) * hd + c * 8) = *(const uint4*)s;
-        } else if (q < n_loc + n_snd) {
-            const long qq = q - n_loc;
-            const int c = qq % cpr;
-            long rest = qq / cpr;
-            const int i = rest % n_rem;
-            const int h = rest / n_rem;
-            const bf16* s = O + ((size_t)h * map.n_total + remote_pos(map, i)) * hd + c * 8;
-            *(uint4*)(send_attn + ((size_t)h * n_rem + i) * hd + c * 8) = *(const uint4*)s;
-        } else {
-            const long qq = q - n_loc - n_snd;
-            const int c = qq % cpr;
-            long rest = qq / cpr;
-            const int ho = rest % (n_heads - h_local);
-            const int i = rest / (n_heads - h_local);
-            const int hh = ho < h0 ? ho : ho + h_local;
-            const bf16* s = peer_attn + ((size_t)i * (n_heads - h_local) + ho) * hd + c * 8;
-            *(uint4*)(row_ptr(i) + hh * hd + c * 8) = *(const uint4*)s;
-        }
-    }
+    lo = a.seg[5];
+    if (b < a.seg[6]) peer_attn_part(b - lo, a.seg[6] - lo, a.pa);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -445,11 +424,12 @@ hipError_t ln_affine_launch(const float* x, const WView& W, uint64_t w_off, uint
 }
 
 hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf16* peer_q, const bf16* peer_k,
-                                const bf16* peer_v, hipStream_t s) {
+                                const bf16* peer_v, const PeerAttnArgs& pa, hipStream_t s) {
     if (n_parts < 1 || n_parts > 2) return hipErrorInvalidValue;
     PreAttnArgs a{};
     a.n_parts = n_parts;
     a.peer_q = peer_q; a.peer_k = peer_k; a.peer_v = peer_v;
+    a.pa = pa;
     int end = 0;
     for (int p = 0; p < 2; ++p) {
         if (p < n_parts) {
@@ -474,22 +454,19 @@ hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf
     } else {
         a.seg[4] = a.seg[5] = end;
     }
+    if (pa.peer_attn && pa.n_heads > pa.h_local && pa.map.n_local > 0) {
+        if ((pa.hd != 64 && pa.hd != 128) || !pa.dst || (pa.ld % 8)) return hipErrorInvalidValue;
+        if (!a.pa.dst1) a.pa.dst1 = pa.dst + (size_t)pa.map.len0 * pa.ld;
+        end += grid_for((long)pa.map.n_local * (pa.n_heads - pa.h_local) * (pa.hd / 8), 256);
+    }
     a.seg[6] = end;
     if (end == 0) return hipSuccess;
     hipLaunchKernelGGL(pre_attention_kernel, dim3(end), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
-hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s) { return pre_attention_launch(&r, 1, nullptr, nullptr, nullptr, s); }
-
-hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, bf16* dst1, int ld, bf16* send_attn,
-                              int n_heads, int h0, int h_local, int hd, TokenMap map, hipStream_t s) {
-    const int cpr = hd / 8;
-    const long total = (long)h_local * map.n_total * cpr + (long)map.n_local * (n_heads - h_local) * cpr;
-    if (!dst1) dst1 = dst + (size_t)map.len0 * ld;
-    hipLaunchKernelGGL(attn_gather_kernel, dim3(grid_for(total, 256)), dim3(256), 0, s, O_full, peer_attn, dst, dst1, ld,
-                       send_attn, n_heads, h0, h_local, hd, map);
-    return hipGetLastError();
+hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s) {
+    return pre_attention_launch(&r, 1, nullptr, nullptr, nullptr, PeerAttnArgs{}, s);
 }
 
 hipError_t checksum_launch(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* out, hipStream_t s) {

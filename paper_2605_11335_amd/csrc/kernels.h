@@ -52,6 +52,16 @@ struct AttnArgs {
     int H, nq, nk, nk_pad, hd;
     int hps;            // heads per sample (a batch is H / hps samples of hps heads each); 0 = H
     float scale;        // 1/sqrt(hd)
+    // Scatter mode (the second Ulysses exchange, Sec. 2.1, done by the attention kernel's own stores; O unused):
+    // query position q of head h (sample b = h / hps, head hh = h % hps) is one of this rank's positions in `map`
+    // -> columns (h0 + hh)*hd of the output projection's operand, row i of the map's first segment at
+    // dst0 + b*bs0 + i*ld, of its second segment at dst1 + b*bs1 + i*ld; any other position -> row of the send
+    // buffer, send + b*send_bs + (hh*(n_total - n_local) + index among the remote positions)*hd (send NULL: dropped).
+    int scatter;
+    TokenMap map;
+    bf16 *dst0, *dst1, *send;
+    int ld, h0;
+    long bs0, bs1, send_bs;
 };
 const char* attn_check(const AttnArgs& a);
 hipError_t attn_launch(const AttnArgs& a, hipStream_t s);
@@ -87,18 +97,21 @@ struct RelayoutArgs {
 };
 hipError_t relayout_launch(const RelayoutArgs& r, hipStream_t s);
 
-// One launch for everything between the QKV projection and attention: the relayout of up to two
-// parts (one per stream) and, when given, the peer rows (what the exchange delivers) placed at the
-// remote positions of parts[0]'s operands (q, k copied; v transposed).
-hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf16* peer_q, const bf16* peer_k,
-                                const bf16* peer_v, hipStream_t s);
+// What this rank receives from the second exchange (Sec. 2.1): the attention output of the other ranks' heads for
+// its own tokens, peer_attn [n_local, n_heads - h_local, hd], copied into the columns of those heads in the
+// output projection's operand (rows of the map's first segment at dst, of its second at dst1; leading dimension ld).
+struct PeerAttnArgs {
+    const bf16* peer_attn;            // NULL: nothing to copy
+    bf16 *dst, *dst1;
+    int ld, n_heads, h0, h_local, hd;
+    TokenMap map;
+};
 
-// After attention on the full sequence: local rows of the local heads and peer_attn (other heads)
-// into the [n_local, ld] operand of the output projection; remote rows into send_attn.  Local
-// rows of the second segment of the map go to dst1 when given (NULL: they follow the first in dst).
-hipError_t attn_gather_launch(const bf16* O_full, const bf16* peer_attn, bf16* dst, bf16* dst1, int ld,
-                              bf16* send_attn, int n_heads, int h0, int h_local, int hd,
-                              TokenMap map, hipStream_t s);
+// One launch for everything that does not depend on attention itself: the relayout of up to two parts (one per
+// stream), when given the peer rows (what the first exchange delivers) placed at the remote positions of
+// parts[0]'s operands (q, k copied; v transposed), and the peer attention rows of the second exchange.
+hipError_t pre_attention_launch(const RelayoutArgs* parts, int n_parts, const bf16* peer_q, const bf16* peer_k,
+                                const bf16* peer_v, const PeerAttnArgs& pa, hipStream_t s);
 
 hipError_t checksum_launch(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* out, hipStream_t s);
 hipError_t f32_to_bf16_launch(const float* src, bf16* dst, size_t n, hipStream_t s);
