@@ -55,6 +55,17 @@ int cf_op_modvec(const void* blob, uint64_t w_off, uint64_t b_off, const float* 
  * random_operands = 0 repeats one pair of small-valued fragments, 1 cycles through sixteen pairs of
  * unit-variance pseudo-random fragments.  `out`: 65536 floats of device memory. */
 int cf_op_mfma_rate(int32_t iters, int32_t random_operands, float* out, void* stream);
+/* Diagnostic, not part of the block path: the same loop with the other work a kernel's waves have to issue
+ * beside their MFMAs -- per 16 MFMAs a wave makes `reads_per_16` LDS fragment reads (16 bytes per lane, through a
+ * ring of four fragments) and per MFMA `valu_per_mfma` fused multiply-adds and `exp_per_mfma` exp2's; `waves`
+ * (4 or 8) waves per workgroup, one workgroup per CU, no global memory traffic, no barriers.  Timed by the
+ * caller it gives the ceiling of an instruction mix: the attention kernel's is one read, about four VALU
+ * operations and one exp2 per MFMA on 8 waves, the GEMM's one read per two MFMAs on 4 waves.  A launch is
+ * 256 * waves * iters * 16 * 32768 FLOPs.  `out`: 256 * 64 * waves floats of device memory.  Built mixes:
+ * reads_per_16 in {0, 8, 16} x (valu, exp) in {(0,0)}, and (2,0), (4,0) without reads, (2,1), (4,1) with any
+ * reads; anything else is CF_ERR_ARG. */
+int cf_op_mix_rate(int32_t iters, int32_t waves, int32_t reads_per_16, int32_t valu_per_mfma, int32_t exp_per_mfma,
+                   float* out, void* stream);
 #ifdef __cplusplus
 }
 #endif

@@ -77,7 +77,7 @@ CORE_EXPORTS = ["cf_create", "cf_destroy", "cf_last_error", "cf_blob_bytes", "cf
                 "cf_sync", "cf_op_checksum", "cf_op_checksum_noalloc"]
 #: what include/chunkflow_diag.h declares: single-kernel hooks, planner views, the matrix-core rate probe
 DIAG_EXPORTS = ["cf_plan_attention", "cf_plan_linear", "cf_op_linear", "cf_op_linear_residual", "cf_op_attention",
-                "cf_op_ln_modulate", "cf_op_modvec", "cf_op_mfma_rate"]
+                "cf_op_ln_modulate", "cf_op_modvec", "cf_op_mfma_rate", "cf_op_mix_rate"]
 EXPORTS = CORE_EXPORTS + DIAG_EXPORTS
 
 _lib = None
@@ -138,6 +138,7 @@ def lib() -> C.CDLL:
         _lib.cf_op_ln_modulate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib.cf_op_modvec.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
         _lib.cf_op_mfma_rate.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        _lib.cf_op_mix_rate.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         _lib.cf_op_checksum.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p]
         _lib.cf_op_checksum_noalloc.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_void_p, C.c_void_p]
     return _lib
@@ -378,6 +379,10 @@ def cf_plan_linear(m_rows: int, n_features: int) -> int:
 
 def cf_op_mfma_rate(iters: int, random_operands: bool, out, stream=None) -> None:
     _check(lib().cf_op_mfma_rate(iters, int(random_operands), _ptr(out), _stream_handle(stream)))
+
+
+def cf_op_mix_rate(iters: int, waves: int, reads_per_16: int, valu_per_mfma: int, exp_per_mfma: int, out, stream=None) -> None:
+    _check(lib().cf_op_mix_rate(iters, waves, reads_per_16, valu_per_mfma, exp_per_mfma, _ptr(out), _stream_handle(stream)))
 
 
 def cf_op_linear_residual(A, blob, w_off, bias_off, M, N, K, resid, gate, y, lda=None, stream=None):

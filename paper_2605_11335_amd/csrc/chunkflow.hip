@@ -839,6 +839,7 @@ int cf_destroy(cf_ctx* c) {
         for (auto& pe : c->prof_pending) { (void)hipEventDestroy(pe.a); (void)hipEventDestroy(pe.b); }
         for (auto e : c->ev_pool) (void)hipEventDestroy(e);
         if (c->comm_dev) (void)hipFree(c->comm_dev);
+        if (c->checksum_dev) (void)hipFree(c->checksum_dev);
     }
     delete c;
     return CF_OK;
@@ -1187,8 +1188,12 @@ int cf_checksum_block(cf_ctx* c, int32_t block, uint64_t* host_out, void* stream
     hipStream_t s = (hipStream_t)stream;
     const Plan& p = c->P(block);
     if (p.n_res_chunks < p.n_chunks) CF_TRY(chunked_prefetch_wait(c, block, -1, stream));
-    uint64_t* dev = nullptr;
-    if (hipMalloc((void**)&dev, 8ull * p.n_chunks) != hipSuccess) { (void)hipGetLastError(); return cf_fail(c, CF_ERR_NOMEM, "hipMalloc failed"); }
+    if (!c->checksum_dev && hipMalloc((void**)&c->checksum_dev, 8ull * c->max_chunks) != hipSuccess) {
+        (void)hipGetLastError();
+        c->checksum_dev = nullptr;
+        return cf_fail(c, CF_ERR_NOMEM, "hipMalloc of the checksum words failed");
+    }
+    uint64_t* const dev = c->checksum_dev;
     const WView v = view_of(c, block);
     int rc = CF_OK;
     for (int k = 0; k < p.n_chunks && rc == CF_OK; ++k) {
@@ -1199,7 +1204,6 @@ int cf_checksum_block(cf_ctx* c, int32_t block, uint64_t* host_out, void* stream
     }
     if (rc == CF_OK && hipMemcpyAsync(host_out, dev, 8ull * p.n_chunks, hipMemcpyDeviceToHost, s) != hipSuccess) rc = cf_fail(c, CF_ERR_HIP, "checksum copy failed");
     if (hipStreamSynchronize(s) != hipSuccess && rc == CF_OK) rc = cf_fail(c, CF_ERR_HIP, "checksum sync failed");
-    (void)hipFree(dev);
     return rc;
 }
 
@@ -1350,6 +1354,14 @@ int cf_op_mfma_rate(int32_t iters, int32_t random_operands, float* out, void* st
     if (iters <= 0 || iters > (1 << 24) || !out) return cf_fail(nullptr, CF_ERR_ARG, "mfma_rate: bad arguments");
     hipError_t e = mfma_rate_launch(iters, random_operands != 0, out, (hipStream_t)stream);
     return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "mfma_rate: %s", hipGetErrorString(e));
+}
+
+int cf_op_mix_rate(int32_t iters, int32_t waves, int32_t reads_per_16, int32_t valu_per_mfma, int32_t exp_per_mfma, float* out,
+                   void* stream) {
+    if (iters <= 0 || iters > (1 << 24) || !out) return cf_fail(nullptr, CF_ERR_ARG, "mix_rate: bad arguments");
+    hipError_t e = mix_rate_launch(iters, waves, reads_per_16, valu_per_mfma, exp_per_mfma, out, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) { (void)hipGetLastError(); return cf_fail(nullptr, CF_ERR_ARG, "mix_rate: this instruction mix is not built"); }
+    return e == hipSuccess ? CF_OK : cf_fail(nullptr, CF_ERR_HIP, "mix_rate: %s", hipGetErrorString(e));
 }
 
 int cf_op_checksum(const void* data, uint64_t bytes, uint64_t first_word, uint64_t* host_out, void* stream) {

@@ -114,6 +114,8 @@ struct cf_ctx {
     int enq_count[2] = {0, 0};          // chunks of the slot's tenant whose copy has been enqueued
     std::string worker_err;
 
+    uint64_t* checksum_dev = nullptr;   // max_chunks words for cf_checksum_block, allocated at its first call
+
     // statistics / profiling
     cf_stats_t stats{};
     bool profiling = false;

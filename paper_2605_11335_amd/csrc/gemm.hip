@@ -536,6 +536,86 @@ hipError_t mfma_rate_launch(int iters, int random_operands, float* out, hipStrea
     return hipGetLastError();
 }
 
+// Diagnostic: what the matrix cores deliver when a wave's MFMAs share the SIMD with the other work a kernel
+// has to issue -- LDS fragment reads (ds_read_b128 through a ring of four fragments) and ordinary / transcendental
+// VALU instructions.  Per 16 MFMAs (four independent accumulators) a wave issues READS16 fragment reads,
+// 16 * VALU fused multiply-adds and 16 * EXPS exp2's; `waves` waves per workgroup, one workgroup per CU.
+// No global memory traffic, no barriers: the rate is the ceiling of an instruction mix, whatever the schedule.
+namespace {
+template <int READS16, int VALU, int EXPS>
+__global__ void mix_rate_kernel(int iters, float* out) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    typedef __attribute__((address_space(3))) const volatile bf16x8 lds_frag;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nthr = blockDim.x;
+    for (int i = threadIdx.x; i < 65536 / 4; i += nthr) {           // pairs of small bf16 values
+        const bf16 lo = (bf16)(0.01f * (i % 37 - 18)), hi = (bf16)(0.01f * (i % 41 - 20));
+        ((uint32_t*)smem)[i] = (uint32_t)__builtin_bit_cast(uint16_t, lo) | ((uint32_t)__builtin_bit_cast(uint16_t, hi) << 16);
+    }
+    __syncthreads();
+    bf16x8 a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            a[i][e] = (bf16)(0.01f * ((lane * 7 + e * 3 + i) % 97 - 48));
+            b[i][e] = (bf16)(0.02f * ((lane * 5 + e + i * 11) % 89 - 44));
+        }
+    floatx16 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    float vv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vv[i] = 0.5f + 0.01f * (lane + i);
+    const uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem + ((wave * 4096) & 0xffff) + lane * 16;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            acc[q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[q & 3], b[q >> 2], acc[q & 3], 0, 0, 0);
+            if (READS16 > 0 && (q % (16 / (READS16 > 0 ? READS16 : 1))) == 0)
+                a[q & 3] = *(lds_frag*)(uintptr_t)(base + ((q * 1024 + it * 64) & 0x3fff));     // the fragment four slots ahead
+#pragma unroll
+            for (int u = 0; u < VALU; ++u) vv[(q * VALU + u) & 7] = __builtin_fmaf(vv[(q * VALU + u) & 7], 0.9999f, 0.0001f);   // -> 1
+#pragma unroll
+            for (int u = 0; u < EXPS; ++u) vv[(q + 3) & 7] = __builtin_amdgcn_exp2f(-vv[(q + 3) & 7]);                       // stays in (0, 1]
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += vv[i];
+    out[blockIdx.x * nthr + threadIdx.x] = s;
+}
+
+template <int READS16, int VALU, int EXPS>
+hipError_t mix_rate_go(int iters, int waves, float* out, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)mix_rate_kernel<READS16, VALU, EXPS>, hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((mix_rate_kernel<READS16, VALU, EXPS>), dim3(256), dim3(64 * waves), 65536, s, iters, out);
+    return hipGetLastError();
+}
+}  // namespace
+
+// `out`: 256 * 64 * waves floats.  FLOPs of a launch = 256 * waves * iters * 16 * 32768.  Supported mixes:
+// reads16 in {0, 8, 16}, valu in {0, 2, 4}, exps in {0, 1}, waves in {4, 8}.
+hipError_t mix_rate_launch(int iters, int waves, int reads16, int valu, int exps, float* out, hipStream_t s) {
+    if (waves != 4 && waves != 8) return hipErrorInvalidValue;
+#define CF_MIX(R, V, E) if (reads16 == R && valu == V && exps == E) return mix_rate_go<R, V, E>(iters, waves, out, s);
+    CF_MIX(0, 0, 0) CF_MIX(8, 0, 0) CF_MIX(16, 0, 0)
+    CF_MIX(0, 2, 0) CF_MIX(0, 4, 0) CF_MIX(0, 2, 1) CF_MIX(0, 4, 1)
+    CF_MIX(8, 2, 1) CF_MIX(8, 4, 1) CF_MIX(16, 2, 1) CF_MIX(16, 4, 1)
+#undef CF_MIX
+    return hipErrorInvalidValue;
+}
+
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s) {
     const int t = gemm_tile(g);
     // the erf form of the activation costs some forty VALU operations per element: it gets kernels

@@ -32,6 +32,8 @@ int gemm_tile(const GemmArgs& g);      // tile gemm_launch will use: 0 = 256x256
 double gemm_fill(int M, int n);        // share of the launched rounds of workgroups that n features x M tokens fill
 hipError_t gemm_launch(const GemmArgs& g, hipStream_t s);
 hipError_t mfma_rate_launch(int iters, int random_operands, float* out, hipStream_t s);   // diagnostic: MFMAs on registers only
+// diagnostic: MFMAs sharing the SIMD with LDS fragment reads and VALU work (see gemm.hip for the supported mixes)
+hipError_t mix_rate_launch(int iters, int waves, int reads16, int valu, int exps, float* out, hipStream_t s);
 // two independent problems in one launch; gemm_pair_tile: the tile shape they share (as gemm_tile), -1 = cannot pair
 int gemm_pair_tile(const GemmArgs& g0, const GemmArgs& g1);
 hipError_t gemm_launch_pair(const GemmArgs& g0, const GemmArgs& g1, hipStream_t s);

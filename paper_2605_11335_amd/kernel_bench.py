@@ -7,6 +7,7 @@ device-to-device copy of known size, used to calibrate hardware byte counters.
     python -m paper_2605_11335_amd.kernel_bench copy 536870912 [iters]      # bytes
     python -m paper_2605_11335_amd.kernel_bench checksum 283183616 [iters]  # bytes (a C2 blob)
     python -m paper_2605_11335_amd.kernel_bench mfma_rate 20000 [iters]     # MFMAs on registers only
+    python -m paper_2605_11335_amd.kernel_bench mix_rate 20000 [iters]      # MFMAs beside LDS reads and VALU work
 
 Timing uses events on the current stream; inputs are seeded N(0,1) activations and N(0,0.02)
 weights in bf16.  The GEMM benchmarks rotate over enough operand sets that consecutive launches
@@ -90,6 +91,19 @@ def main(argv):
             ms = timeit(lambda: B.cf_op_mfma_rate(n, rnd, out), iters)
             print(f"mfma_rate {n} x 16 MFMAs per wave, 1024 waves, {what}: {ms:.4f} ms  {flops / ms / 1e9:.1f} TFLOP/s "
                   f"({flops / ms / 1e9 / 2500 * 100:.1f} % of the published 2500; implied clock {flops / ms / 1e9 / 2500 * 2.4:.2f} GHz)")
+    elif which == "mix_rate":
+        n = int(shape)
+        out = torch.empty(256 * 512, dtype=torch.float32, device=DEV)
+        mixes = [(4, 0, 0, 0), (8, 0, 0, 0), (4, 8, 0, 0), (8, 8, 0, 0), (8, 16, 0, 0), (8, 0, 2, 0), (8, 0, 4, 0), (8, 0, 2, 1),
+                 (8, 0, 4, 1), (8, 16, 4, 1), (8, 16, 2, 1), (8, 8, 4, 1), (8, 8, 2, 1), (4, 8, 4, 1), (4, 8, 2, 1), (4, 16, 4, 1)]
+        base = None
+        for waves, reads, valu, exps in mixes:
+            it = n * 8 // waves                                     # the same number of MFMAs per CU in every row
+            ms = timeit(lambda: B.cf_op_mix_rate(it, waves, reads, valu, exps, out), iters)
+            tf = 256 * waves * it * 16 * 32768.0 / ms / 1e9
+            base = base or tf
+            print(f"mix_rate waves/CU {waves}  LDS reads per 16 MFMAs {reads:2d}  VALU per MFMA {valu}  exp2 per MFMA {exps}: "
+                  f"{ms:8.3f} ms  {tf:7.1f} TFLOP/s  ({tf / base * 100:5.1f} % of MFMAs alone)")
     else:
         raise SystemExit(__doc__)
 

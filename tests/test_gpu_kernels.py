@@ -285,3 +285,22 @@ def test_mfma_rate_diagnostic_runs_and_is_deterministic():
     assert np.array_equal(res[1], res[2]) and not np.array_equal(res[0], res[1])
     with pytest.raises(B.ChunkflowError):
         B.cf_op_mfma_rate(0, False, out)
+
+
+def test_mix_rate_diagnostic_runs_for_every_built_mix_and_rejects_others():
+    out = torch.zeros(256 * 512, dtype=torch.float32, device=DEV)
+    ref = None
+    for waves, reads, valu, exps in [(4, 0, 0, 0), (8, 0, 0, 0), (8, 16, 0, 0), (8, 8, 0, 0), (8, 0, 4, 1), (8, 16, 4, 1), (4, 8, 2, 1)]:
+        out.zero_()
+        B.cf_op_mix_rate(20, waves, reads, valu, exps, out)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()[:256 * 64 * waves]
+        assert np.isfinite(got).all() and np.abs(got).max() > 0, (waves, reads, valu, exps)
+        if (waves, reads, valu, exps) == (8, 0, 0, 0):
+            ref = got.copy()
+    B.cf_op_mix_rate(20, 8, 0, 0, 0, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy()[:256 * 64 * 8], ref)         # deterministic
+    for bad in [(0, 8, 0, 0, 0), (20, 5, 0, 0, 0), (20, 8, 3, 0, 0), (20, 8, 16, 4, 0)]:
+        with pytest.raises(B.ChunkflowError):
+            B.cf_op_mix_rate(*bad, out)
