@@ -11,7 +11,10 @@ three critical configurations printed in App. C come out.
 The step-time closure `step_time` (sum over blocks of max(T_comp, T_pref)) and `weight_memory`
 are this build's own first-order extension of the hide-or-expose condition; the paper prints
 only the condition.  They are PARITY UNPINNED by the paper and are checked only through
-their limits (r=0, r=1) and monotonicity in r.
+their limits (r=0, r=1) and monotonicity in r.  The chunk-level walk (`segment_shares`,
+`simulate_step`) is this build's own as well: its booking rule is pinned on layouts worked by
+hand, its recurrence on the first-order limits and a two-block case worked by hand; what it
+predicts is judged against measurement.
 """
 from __future__ import annotations
 
