@@ -107,3 +107,35 @@ def test_chained_mixed_stack_matches_the_chained_oracle_and_offload_is_bit_ident
     for r in (0.0, 0.5):
         off, _ = chained(cfg, r)
         assert np.array_equal(off.view(np.uint32), got.view(np.uint32)), f"offloaded (r={r}) differs from resident"
+
+
+def test_flux_like_double_stream_block_at_full_size():
+    """The double-stream block of the Flux-like MMDiT share at its real shape (256 text + 2048 image rows of this
+    rank, joint attention of 12 heads over 4608 positions, 679 MB of weights streamed in chunks), against the
+    oracle's full computation: both streams' outputs and everything this rank would send."""
+    from paper_2605_11335_amd.runner import bits_of
+    from tests.util import bits_to_f64
+    cfg = wl.CONFIGS["flux_mm"].with_(n_blocks=1, n_double=1)
+    cb = cfg.block_cfg(0)
+    assert cb.kind == wl.KIND_DOUBLE
+    params, inputs = wl.gen_block_params(cb, 0), wl.gen_block_inputs(cb, 0)
+    run = BlockRunner(cfg)
+    try:
+        run.ctx.set_resident_fraction(0.0)
+        run.register_params(0, params)
+        t = run.make_io(inputs)
+        say("[flux_mm double-stream, full size] gpu forward")
+        run.run_block(0, t)
+        say("[flux_mm double-stream, full size] oracle")
+        ref = ob.block_forward(cb, params, inputs)
+        got = y_rows(cb, t)
+        x = np.concatenate([inputs["x_txt"], inputs["x"]])
+        r_, m_, rb = rel_l2(got, ref["y_rows"]), max_abs(got, ref["y_rows"]), rel_l2(got - x, ref["y_rows"] - x)
+        say(f"   y rel_l2={r_:.3e} max_abs={m_:.3e} branch rel_l2={rb:.3e}")
+        assert r_ <= REL_L2_TOL and m_ <= MAX_ABS_TOL and rb <= 2e-2
+        for k in ("send_q", "send_k", "send_v", "send_attn"):
+            g = bits_to_f64(bits_of(t[k]))
+            assert g.shape == ref[k].shape, k
+            assert rel_l2(g, ref[k]) <= REL_L2_TOL and max_abs(g, ref[k]) <= MAX_ABS_TOL, k
+    finally:
+        run.close()
