@@ -406,7 +406,6 @@ hipError_t modvec_launch(const WView& W, uint64_t w_off, uint64_t b_off, const f
 #define CF_MV_CASE(U) hipLaunchKernelGGL(modvec_kernel<U>, grid, dim3(256), 0, s, W, w_off, b_off, t, m, n0, n1, K, m_bs)
     if (steps == 1) CF_MV_CASE(1);
     else if (steps == 2) CF_MV_CASE(2);
-    else if (steps == 6) CF_MV_CASE(6);          // K = 3072: a lane's whole walk in flight at once
     else if (steps % 3 == 0) CF_MV_CASE(3);
     else CF_MV_CASE(4);
 #undef CF_MV_CASE
