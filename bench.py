@@ -55,8 +55,9 @@ def parse():
     ap.add_argument("--batch", type=int, default=1, help="samples per forward (B of App. B); the headline workload is 1")
     ap.add_argument("--resident", type=float, default=0.0, help="resident fraction of the offloaded arm")
     ap.add_argument("--chunk-mib", type=float, default=0.0, help="chunk size in MiB (0 = the config's chunk count)")
-    ap.add_argument("--contention", choices=["off", "on", "pause"], default="off",
-                    help="emulated all-to-all traffic on a third stream; 'pause' adds pause/resume")
+    ap.add_argument("--contention", choices=["off", "on", "pause", "pause2"], default="off",
+                    help="emulated all-to-all traffic on a third stream; 'pause' adds pause/resume with one chunk in flight, "
+                         "'pause2' with two")
     ap.add_argument("--sweep", action="store_true", help="memory-latency grid (r x chunk x contention) to stderr")
     ap.add_argument("--tune-budget-frac", type=float, default=0.5,
                     help="with --sweep: weight-memory budget, as a fraction of the stack's weights, handed to the tuner")
@@ -275,7 +276,7 @@ def measure(args, name, steps, warmup, *, blocks=0, shared_weights=False, shared
         nbytes = nbytes // 512 * 512
         if comm_host is None:
             comm_host = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
-        run.ctx.cf_set_contention(run.comm, comm_host, nbytes, mode == "pause")
+        run.ctx.cf_set_contention(run.comm, comm_host, nbytes, {"pause": 1, "pause2": 2}.get(mode, 0))
 
     def arm(r, n_steps, n_warmup):
         actual = run.ctx.set_resident_fraction(r)

@@ -286,7 +286,8 @@ class Context:
     def dit_block_fwd(self, block: int, io: cf_block_io, compute_stream) -> None:
         _check(lib().dit_block_fwd(self._h, block, C.byref(io), _stream_handle(compute_stream)), self._h)
 
-    def cf_set_contention(self, comm_stream, host_pinned, bytes_per_collective: int, pause_resume: bool) -> None:
+    def cf_set_contention(self, comm_stream, host_pinned, bytes_per_collective: int, pause_resume) -> None:
+        """pause_resume: 0 / False = off, 1 / True = one chunk in flight, 2 = two."""
         if host_pinned is not None:
             self._keep.append(host_pinned)
         _check(lib().cf_set_contention(self._h, _stream_handle(comm_stream), _ptr(host_pinned),

@@ -223,7 +223,8 @@ WView view_of(const cf_ctx* c, int block) {
 // GPU.  The copy stream is then parked on the collective's completion event, once per collective; the chunk
 // already on the link finishes first, which is the residual stall the paper bounds by one chunk's service
 // time (with pause_depth = 1 no further chunk is queued behind it).  Called with c->mu held.
-int pause_if_collective_running(cf_ctx* c, hipStream_t copy, std::unique_lock<std::mutex>& lk) {
+// Collectives that have finished leave the list and hand their events back.  Called with c->mu held.
+void retire_finished_collectives(cf_ctx* c) {
     while (!c->comm_pending.empty()) {
         PendingComm& p = c->comm_pending.front();
         if (!p.done_recorded || hipEventQuery(p.done) != hipSuccess) break;
@@ -232,6 +233,10 @@ int pause_if_collective_running(cf_ctx* c, hipStream_t copy, std::unique_lock<st
         c->comm_pending.pop_front();
     }
     (void)hipGetLastError();                          // hipErrorNotReady of a query is not an error
+}
+
+int pause_if_collective_running(cf_ctx* c, hipStream_t copy, std::unique_lock<std::mutex>& lk) {
+    retire_finished_collectives(c);
     if (c->comm_pending.empty()) return CF_OK;
     PendingComm& p = c->comm_pending.front();
     if (p.handled || hipEventQuery(p.ready) != hipSuccess) { (void)hipGetLastError(); return CF_OK; }
@@ -1385,6 +1390,7 @@ int cf_comm_begin_impl(cf_ctx* c, hipStream_t comm, hipStream_t compute) {
         // `ready` tells it, in GPU time, that the compute stream has reached the collective (Sec. 3.2: the
         // flag goes up when the collective is issued), `done` is what it parks the copy stream on
         std::lock_guard<std::mutex> lk(c->mu);
+        retire_finished_collectives(c);                // also when no chunk streams and the worker never looks
         for (hipEvent_t* e : {&c->cur_ready, &c->cur_done}) {
             if (!c->comm_ev_pool.empty()) { *e = c->comm_ev_pool.back(); c->comm_ev_pool.pop_back(); }
             else CF_HIP(c, hipEventCreateWithFlags(e, hipEventDisableTiming));
