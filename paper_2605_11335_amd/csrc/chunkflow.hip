@@ -214,15 +214,9 @@ WView view_of(const cf_ctx* c, int block) {
 }
 
 // ------------------------------------------------------------------------------------------
-// prefetch worker (Sec. 3.2): enqueues chunk copies with at most 2 in flight and, when a
-// collective has been issued, parks the copy stream on that collective's completion event
+// prefetch worker (Sec. 3.2): enqueues chunk copies with at most pause_depth (1 or 2) in flight and, when
+// the compute stream has reached a collective, parks the copy stream on that collective's completion event
 // ------------------------------------------------------------------------------------------
-// Pause decision of the prefetch worker, taken before each chunk copy is enqueued (Sec. 3.2: the flag is
-// checked at chunk boundaries).  A collective counts as issued once the compute stream has reached it in
-// GPU time (its `ready` event has fired), not when the host enqueued it: the host runs a block ahead of the
-// GPU.  The copy stream is then parked on the collective's completion event, once per collective; the chunk
-// already on the link finishes first, which is the residual stall the paper bounds by one chunk's service
-// time (with pause_depth = 1 no further chunk is queued behind it).  Called with c->mu held.
 // Collectives that have finished leave the list and hand their events back.  Called with c->mu held.
 void retire_finished_collectives(cf_ctx* c) {
     while (!c->comm_pending.empty()) {
@@ -235,6 +229,12 @@ void retire_finished_collectives(cf_ctx* c) {
     (void)hipGetLastError();                          // hipErrorNotReady of a query is not an error
 }
 
+// Pause decision of the prefetch worker, taken before each chunk copy is enqueued (Sec. 3.2: the flag is
+// checked at chunk boundaries).  A collective counts as issued once the compute stream has reached it in
+// GPU time (its `ready` event has fired), not when the host enqueued it: the host runs a block ahead of the
+// GPU.  The copy stream is then parked on the collective's completion event, once per collective; the chunk
+// already on the link finishes first, which is the residual stall the paper bounds by one chunk's service
+// time (with pause_depth = 1 no further chunk is queued behind it).  Called with c->mu held.
 int pause_if_collective_running(cf_ctx* c, hipStream_t copy, std::unique_lock<std::mutex>& lk) {
     retire_finished_collectives(c);
     if (c->comm_pending.empty()) return CF_OK;
