@@ -109,31 +109,39 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
     };
 
     floatx16 o[DT];
-#pragma unroll
-    for (int d = 0; d < DT; ++d)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[d][v] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float mc, l_run;                            // reference of the exponentials (base-2 units), row sum
     const float c2 = a.scale * 1.4426950408889634f;   // logits in base-2 units
 
     // key row fed to MFMA row i: swap bits 2 and 3 of i
     const int krow = (lj & 0x13) | ((lj & 4) << 1) | ((lj & 8) >> 1);
 
     const int NT = (a.nk + BKV - 1) / BKV;
-    issue_tile(0, 0);
-    __syncthreads();                            // (waits for the LDS-DMA, then the barrier)
+    int out_of_range = 0;                       // wave-uniform: a fast tile met scores it could not take
 
-    // one tile; the LDS buffer is a compile-time constant so that fragment addresses are a per-lane
-    // register plus an immediate (the loop below takes tiles in pairs)
-    auto tile = [&](int t, auto buf_c) __attribute__((always_inline)) {
+    // One tile.  The LDS buffer is a compile-time constant so that fragment addresses are a per-lane
+    // register plus an immediate.
+    //
+    // Softmax is invariant to the reference its exponentials are taken against, as long as numerator and
+    // denominator share it; magnitudes only have to stay inside the fp32 / bf16 range, whose relative
+    // precision does not depend on scale.  A tracking tile does what online softmax usually does: take
+    // the tile's maximum, move the reference there, rescale O^T and the row sum.  A fast tile takes no
+    // maximum: it forms P^T = exp2(s * c2 - mc) against the reference it inherits (one FMA, one exp2 and
+    // half a conversion per score) and looks at the row sums afterwards.  A query whose 64 values add
+    // up to 2^20 or more has its reference, O^T and row sum shifted by a whole power of two (exact); if
+    // they add up to 2^64 or more, or to no number (exp2 overflowed), the tile is declared out of range:
+    // nothing is repaired on the spot, the workgroup repeats the whole sweep with tracking tiles.
+    auto tile = [&](int t, auto buf_c, auto tracking_c) __attribute__((always_inline)) {
         constexpr int buf = decltype(buf_c)::value;
+        constexpr bool tracking = decltype(tracking_c)::value;
         if (t + 1 < NT) issue_tile(t + 1, buf ^ 1);
         const char* cK = sK + buf * K_TILE;
         const char* cV = sV + buf * V_TILE;
 
         // ---- S^T = K . Q^T for 2 x 32 keys.  MFMA i handles key half (i & 1) and k-step (i >> 1), so
         // consecutive MFMAs hit different accumulators; K fragments run 4 reads ahead in a ring.
+        // Register v of tile mt is key k0 + mt*32 + 16*(v/8) + 8*lg + v%8; keys past nk score -inf.
         floatx16 s[2];
+        const int k0 = t * BKV;
         {
             bf16x8 kf[4];
             auto kfrag = [&](int i) {
@@ -162,19 +170,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
         }
-        // first V^T fragments: issued now so that they land while the softmax runs
-        bf16x8 vf[4];
-        auto vfrag = [&](int i) {                   // i = ks * DT + d
-            const int row = (i % DT) * 32 + lj, c = (i / DT) * 2 + lg;
-            return *(const bf16x8*)(cV + row * 128 + ((c ^ vswz(row)) << 4));
-        };
-#pragma unroll
-        for (int i = 0; i < 4; ++i) vf[i] = vfrag(i);
-
-        // ---- online softmax; register v of tile mt is key k0 + mt*32 + 16*(v/8) + 8*lg + v%8.
-        // The max is taken on raw scores (the scale is positive); scale and max-subtraction are one
-        // FMA per element in front of exp2.
-        const int k0 = t * BKV;
         if (k0 + BKV > a.nk) {
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt)
@@ -184,50 +179,66 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
                     if (key >= a.nk) s[mt][v] = -INFINITY;
                 }
         }
-        // maximum of the lane's 32 scores as a tree of three-input maxima (11 + 4 + 1 instructions, depth 4)
-        float mx;
-        {
-            float m3[11];
+        // first V^T fragments: issued now so that they land while the softmax runs
+        bf16x8 vf[4];
+        auto vfrag = [&](int i) {                   // i = ks * DT + d
+            const int row = (i % DT) * 32 + lj, c = (i / DT) * 2 + lg;
+            return *(const bf16x8*)(cV + row * 128 + ((c ^ vswz(row)) << 4));
+        };
 #pragma unroll
-            for (int i = 0; i < 10; ++i) m3[i] = max3f(s[(3 * i) >> 4][(3 * i) & 15], s[(3 * i + 1) >> 4][(3 * i + 1) & 15], s[(3 * i + 2) >> 4][(3 * i + 2) & 15]);
-            m3[10] = fmaxf(s[1][14], s[1][15]);
-            const float a0 = max3f(m3[0], m3[1], m3[2]), a1 = max3f(m3[3], m3[4], m3[5]), a2 = max3f(m3[6], m3[7], m3[8]);
-            mx = max3f(max3f(a0, a1, a2), m3[9], m3[10]);
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // Rescale lazily: the reference maximum only moves when some query of this wave exceeds it by
-        // more than 2^8 (softmax is invariant to the reference as long as numerator and denominator
-        // share it; P then stays below 256, comfortably inside bf16 and fp32 range).
-        const float m_new = fmaxf(m_run, mx);
-        if (__any((m_new - m_run) * c2 > 8.0f)) {
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+        for (int i = 0; i < 4; ++i) vf[i] = vfrag(i);
+        __builtin_amdgcn_sched_barrier(0);
+
+        if constexpr (tracking) {
+            float mx;                                   // the lane's 32 scores: a tree of three-input maxima
+            {
+                float m3[11];
+#pragma unroll
+                for (int i = 0; i < 10; ++i) m3[i] = max3f(s[(3 * i) >> 4][(3 * i) & 15], s[(3 * i + 1) >> 4][(3 * i + 1) & 15], s[(3 * i + 2) >> 4][(3 * i + 2) & 15]);
+                m3[10] = fmaxf(s[1][14], s[1][15]);
+                const float a0 = max3f(m3[0], m3[1], m3[2]), a1 = max3f(m3[3], m3[4], m3[5]), a2 = max3f(m3[6], m3[7], m3[8]);
+                mx = max3f(max3f(a0, a1, a2), m3[9], m3[10]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));         // every tile holds a key below nk: mx is finite
+            const float mc_new = fmaxf(mc, mx * c2);
+            const float alpha = __builtin_amdgcn_exp2f(mc - mc_new);             // 0 from mc = -inf
             l_run *= alpha;
 #pragma unroll
             for (int d = 0; d < DT; ++d)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o[d][v] *= alpha;
-            m_run = m_new;
+            mc = mc_new;
         }
-        const float mc = m_run * c2;
-        float psum[4] = {0.f, 0.f, 0.f, 0.f};             // four chains: a row sum is not one long dependency
+
+        // ---- P^T in bf16, in the B-operand layout of the second contraction (fragment ks = registers
+        // 8*(ks&1).. of half ks>>1).  The row sum adds the rounded values in pairs (bf16 dot product with
+        // (1, 1), fp32 accumulate): the weights the second contraction really applies to V.
+        bf16x8 pf[4];
+        float psum;
+        {
+            float ps[4] = {0.f, 0.f, 0.f, 0.f};           // four chains: a row sum is not one long dependency
+            bf16x2 ones;
+            ones[0] = (bf16)1.0f;
+            ones[1] = (bf16)1.0f;
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+            for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[mt][v], c2, -mc));
-                s[mt][v] = p;
-                psum[v & 3] += p;
-            }
-        l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
+                for (int e = 0; e < 8; e += 2) {
+                    bf16x2 pp;
+                    pp[0] = (bf16)__builtin_amdgcn_exp2f(fmaf(s[ks >> 1][8 * (ks & 1) + e], c2, -mc));
+                    pp[1] = (bf16)__builtin_amdgcn_exp2f(fmaf(s[ks >> 1][8 * (ks & 1) + e + 1], c2, -mc));
+                    pf[ks][e] = pp[0];
+                    pf[ks][e + 1] = pp[1];
+                    ps[(e >> 1) & 3] = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, ps[(e >> 1) & 3], false);
+                }
+            psum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        }
+        l_run += psum;
+        __builtin_amdgcn_sched_barrier(0);
 
         // ---- O^T += V^T . P^T: MFMA i handles k-step (i / DT) of 16 keys and d-tile (i % DT);
         // V^T fragments keep running 4 reads ahead
         {
-            bf16x8 pf[4];
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) pf[ks][e] = (bf16)s[ks >> 1][8 * (ks & 1) + e];
 #pragma unroll
             for (int i = 0; i < 4 * DT; ++i) {
                 o[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i & 3], pf[i / DT], o[i % DT], 0, 0, 0);
@@ -241,12 +252,46 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_fwd_kernel(AttnArgs a) {
             __builtin_amdgcn_sched_group_barrier(0x008, 4, 1);
         }
 
+        if constexpr (!tracking) {
+            const float row = psum + __shfl_xor(psum, 32);
+            if (__any(!(row < 1048576.0f))) {
+                if (__any(!(row < 18446744073709551616.0f))) {
+                    out_of_range = 1;
+                } else {
+                    // queries at or past 2^20: divide by 2^e, e = the sum's binary exponent; the others keep e = 0
+                    const int e = row < 1048576.0f ? 0 : (int)(__float_as_uint(row) >> 23) - 127;
+                    const float alpha = __uint_as_float((uint32_t)(127 - e) << 23);
+                    mc += (float)e;
+                    l_run *= alpha;
+#pragma unroll
+                    for (int d = 0; d < DT; ++d)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) o[d][v] *= alpha;
+                }
+            }
+        }
+
         __syncthreads();                        // tile t+1 has landed, tile t may be overwritten
     };
-    for (int t = 0; t < NT; t += 2) {
-        tile(t, std::integral_constant<int, 0>{});
-        if (t + 1 < NT) tile(t + 1, std::integral_constant<int, 1>{});
-    }
+    // One sweep over the keys: the first tile always tracks (it sets the reference), the others in pairs.
+    auto sweep = [&](auto tracking_c) __attribute__((always_inline)) {
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[d][v] = 0.f;
+        mc = -INFINITY;
+        l_run = 0.f;
+        issue_tile(0, 0);
+        __syncthreads();                        // (waits for the LDS-DMA, then the barrier)
+        tile(0, std::integral_constant<int, 0>{}, std::true_type{});
+        for (int t = 1; t < NT; t += 2) {
+            tile(t, std::integral_constant<int, 1>{}, tracking_c);
+            if (t + 1 < NT) tile(t + 1, std::integral_constant<int, 0>{}, tracking_c);
+        }
+    };
+    sweep(std::false_type{});
+    // the K/V tiles are the workgroup's: if any wave met a tile out of range, all of them go again
+    if (__syncthreads_or(out_of_range)) sweep(std::true_type{});
 
     // ---- normalise and store: lane = query, register quad = 4 consecutive d
     const float l_tot = l_run + __shfl_xor(l_run, 32);

@@ -127,6 +127,26 @@ def test_attention_uniform_values_and_dominant_key():
     assert np.abs(got[0, 3] - bf16_round(v2[0, 150])[0]).max() < 1e-2
 
 
+@pytest.mark.parametrize("step", [0.7, 3.0, 30.0, 200.0])
+def test_attention_scores_that_keep_rising_along_the_keys(step):
+    """Every 64-key tile scores `step` nats above the one before it, for every query: whatever reference
+    the kernel's online softmax keeps has to move again and again (by a little, by 43 binary orders per
+    tile, and by more than exp2 can represent), and late tiles carry nearly all the weight."""
+    rng = np.random.default_rng(int(step * 10))
+    H, nq, nk, hd = 2, 96, 64 * 9 + 17, 128
+    u = rng.normal(size=hd)
+    u /= np.linalg.norm(u)
+    a = 4.0
+    q = a * u + 0.3 * rng.normal(size=(H, nq, hd))
+    ramp = (np.arange(nk) // 64) * step * np.sqrt(hd) / a
+    k = ramp[None, :, None] * u + 0.3 * rng.normal(size=(H, nk, hd))
+    v = rng.normal(size=(H, nk, hd))
+    got, ref = run_attention(q, k, v, hd)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, ref) < 6e-3, rel_l2(got, ref)
+    assert max_abs(got, ref) < 2e-2 * max(1.0, np.abs(ref).max()), max_abs(got, ref)
+
+
 @pytest.mark.parametrize("rows,d", [(100, 512), (37, 3072), (5, 256), (9, 768), (6, 1024), (7, 1536), (3, 2048), (2, 4096)])
 def test_ln_modulate(rows, d):
     """Every row width the kernel is built for (d / 256 in 1, 2, 3, 4, 6, 8, 12, 16), row counts that leave
