@@ -222,6 +222,24 @@ def test_attention_every_workgroup_height(H, n, hd):
     assert rel_l2(got, ref) < 6e-3 and max_abs(got, ref) < 2e-2 * max(1.0, np.abs(ref).max())
 
 
+@pytest.mark.parametrize("H,n,hd,step", [(12, 4608, 128, 3.0), (12, 4608, 128, 200.0), (8, 5000, 64, 200.0), (4, 12800, 128, 30.0),
+                                         (4, 12800, 128, 200.0)])
+def test_attention_rising_scores_at_every_workgroup_height(H, n, hd, step):
+    """The first ten key tiles score `step` nats above one another (then the level holds) on grids that run 8, 8 (ragged,
+    64-wide heads) and 7 waves per workgroup: the softmax reference is shifted tile after tile (3 and 30 nats) or the
+    workgroups repeat their sweep (200 nats)."""
+    rng = np.random.default_rng(int(H + n + hd + step))
+    u = rng.normal(size=hd)
+    u /= np.linalg.norm(u)
+    a = 4.0
+    q = a * u + 0.3 * rng.normal(size=(H, n, hd))
+    ramp = np.minimum(np.arange(n) // 64, 9) * step * np.sqrt(hd) / a
+    k = ramp[None, :, None] * u + 0.3 * rng.normal(size=(H, n, hd))
+    got, ref = run_attention(q, k, rng.normal(size=(H, n, hd)), hd)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, ref) < 6e-3 and max_abs(got, ref) < 2e-2 * max(1.0, np.abs(ref).max())
+
+
 def test_linear_under_one_round_of_tiles():
     """A grid that covers the chip less than once (both epilogues), with a ragged feature edge."""
     rng = np.random.default_rng(21)
