@@ -36,9 +36,9 @@ PEAK_LINK_GBS = 64.0           # PCIe Gen5 x16, one direction
 # scaled by a copy kernel of known size (see profiles/); None until measured for a workload.
 TRAFFIC = {("flux", "gemm_lin1/256x256"): 607860396,      # profiles/hbm_traffic_flux_kernels.md
            ("flux", "gemm_lin2/128x128"): 528712950,
-           ("flux", "attention"): 66201336,               # profiles/hbm_traffic_attention_all_shares.md
-           ("wan", "attention"): 951336124,
-           ("hunyuan", "attention"): 11949334946}
+           ("flux", "attention"): 66248782,               # profiles/hbm_traffic_attention_all_shares.md
+           ("wan", "attention"): 950651315,
+           ("hunyuan", "attention"): 11949446179}
 HEADLINE = "hunyuan"
 
 
